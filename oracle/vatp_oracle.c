@@ -1,0 +1,210 @@
+/*
+ * VATP reference oracle -- TEST INFRASTRUCTURE, NOT PART OF THE PRODUCT.
+ *
+ * A plain, slow, float64 CPU statement of what the value-aware token pruning hot
+ * path computes, written from the paper's equations.  It shares no code with the
+ * HIP library; only tests, the smoke check and the CPU-baseline leg of the bench
+ * may link or call it.
+ *
+ * Every function handles ONE attention head of ONE sequence ("each token in an
+ * attention head" is scored on its own -- Methodology section, value-aware
+ * pruning metric paragraph); the *_units drivers at the end only loop those
+ * single-head functions over independent (sequence, head) units.
+ *
+ * Arrays are dense row-major doubles; a "row" is one token's d-vector.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/*
+ * Accumulated attention score after a causal prompt pass (Eq. 2 with t = L-1,
+ * attention weights a_i^j of Eq. 1 taken as softmax over the keys i <= j of the
+ * scaled dot products c * <q_j, k_i>):
+ *     S_i = sum_{j=i}^{L-1} a_i^j .
+ * Q, K: [L, d].  S: [L] (overwritten).  scratch: [L] doubles.
+ */
+void vatp_oracle_prefill_scores(const double *Q, const double *K, int64_t L, int64_t d,
+                                double c, double *S, double *scratch)
+{
+    for (int64_t i = 0; i < L; ++i) S[i] = 0.0;
+    for (int64_t j = 0; j < L; ++j) {
+        const double *q = Q + j * d;
+        double m = -INFINITY;
+        for (int64_t i = 0; i <= j; ++i) {
+            const double *k = K + i * d;
+            double dot = 0.0;
+            for (int64_t x = 0; x < d; ++x) dot += q[x] * k[x];
+            scratch[i] = c * dot;
+            if (scratch[i] > m) m = scratch[i];
+        }
+        double denom = 0.0;
+        for (int64_t i = 0; i <= j; ++i) {
+            scratch[i] = exp(scratch[i] - m);
+            denom += scratch[i];
+        }
+        for (int64_t i = 0; i <= j; ++i) S[i] += scratch[i] / denom;
+    }
+}
+
+/*
+ * One decode step of Eq. 2: the new query attends over all n rows currently in the
+ * cache (the row of the new token included), and every row's accumulated score
+ * grows by the attention weight it received:  S_r += a_r.
+ * q: [d].  K: [n, d].  S: [n] in/out (the new row enters with S = 0).  a_out: [n] or NULL.
+ */
+void vatp_oracle_decode_scores(const double *q, const double *K, int64_t n, int64_t d,
+                               double c, double *S, double *a_out, double *scratch)
+{
+    double m = -INFINITY;
+    for (int64_t r = 0; r < n; ++r) {
+        const double *k = K + r * d;
+        double dot = 0.0;
+        for (int64_t x = 0; x < d; ++x) dot += q[x] * k[x];
+        scratch[r] = c * dot;
+        if (scratch[r] > m) m = scratch[r];
+    }
+    double denom = 0.0;
+    for (int64_t r = 0; r < n; ++r) {
+        scratch[r] = exp(scratch[r] - m);
+        denom += scratch[r];
+    }
+    for (int64_t r = 0; r < n; ++r) {
+        double a = scratch[r] / denom;
+        S[r] += a;
+        if (a_out) a_out[r] = a;
+    }
+}
+
+/* l1 norm of each value row (the norm used in Eq. 4).  V: [n, d] -> nrm: [n]. */
+void vatp_oracle_l1norm(const double *V, int64_t n, int64_t d, double *nrm)
+{
+    for (int64_t r = 0; r < n; ++r) {
+        double s = 0.0;
+        for (int64_t x = 0; x < d; ++x) s += fabs(V[r * d + x]);
+        nrm[r] = s;
+    }
+}
+
+/*
+ * Value-aware importance, Eq. 4:  I_r = S_r * ||v_r||_1.
+ * decide_f32 != 0 rounds each product to binary32 first: that is the precision in
+ * which the GPU library compares importances, so that a test which feeds both sides
+ * the same binary32 S and norm values takes the keep/evict decision identically.
+ */
+void vatp_oracle_importance(const double *S, const double *nrm, int64_t n, int decide_f32,
+                            double *I)
+{
+    for (int64_t r = 0; r < n; ++r) {
+        double v = S[r] * nrm[r];
+        I[r] = decide_f32 ? (double)(float)v : v;
+    }
+}
+
+/*
+ * Budgeted selection on a cache of n rows (Attention Sink Tokens paragraph for the
+ * forced prefix F; Implementation Details appendix for the budget split into
+ * importance-selected rows plus a local window of the most recent rows).
+ *   n <= B : every row is kept.
+ *   else   : rows [0,F) and [n-R,n) are kept unconditionally; of the candidates
+ *            [F, n-R) the B-F-R with the largest I are kept, equal I resolved in
+ *            favour of the lower row index.
+ * kept (size >= min(n,B)) receives the surviving row indices in ascending order.
+ * Returns the number of rows kept, or -1 if B < F + R.
+ */
+int64_t vatp_oracle_select(const double *I, int64_t n, int64_t B, int64_t F, int64_t R,
+                           int32_t *kept)
+{
+    if (B < F + R) return -1;
+    if (n <= B) {
+        for (int64_t r = 0; r < n; ++r) kept[r] = (int32_t)r;
+        return n;
+    }
+    int64_t n_heavy = B - F - R;
+    int64_t lo = F, hi = n - R;            /* candidates are rows lo .. hi-1 */
+    char *keep = (char *)calloc((size_t)n, 1);
+    for (int64_t r = 0; r < lo; ++r) keep[r] = 1;
+    for (int64_t r = hi; r < n; ++r) keep[r] = 1;
+    /* pick the n_heavy best candidates one at a time: largest I, lowest index first */
+    for (int64_t pick = 0; pick < n_heavy; ++pick) {
+        int64_t best = -1;
+        for (int64_t r = lo; r < hi; ++r) {
+            if (keep[r]) continue;
+            if (best < 0 || I[r] > I[best]) best = r;   /* strict '>' keeps the lower index */
+        }
+        keep[best] = 1;
+    }
+    int64_t out = 0;
+    for (int64_t r = 0; r < n; ++r)
+        if (keep[r]) kept[out++] = (int32_t)r;
+    free(keep);
+    return out;
+}
+
+/* Compaction: out row o = in row kept[o].  Rows are `width` doubles wide. */
+void vatp_oracle_gather_rows(const double *in, const int32_t *kept, int64_t n_kept,
+                             int64_t width, double *out)
+{
+    for (int64_t o = 0; o < n_kept; ++o)
+        memcpy(out + o * width, in + (int64_t)kept[o] * width, (size_t)width * sizeof(double));
+}
+
+/* ---- drivers over independent (sequence, head) units; used for CPU timing ---- */
+
+/* Q, K: [units, cap, d]; len[u] rows valid; S: [units, cap]. */
+void vatp_oracle_prefill_scores_units(const double *Q, const double *K, int64_t units,
+                                      int64_t cap, const int64_t *len, int64_t d, double c,
+                                      double *S)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t u = 0; u < units; ++u) {
+        double *scratch = (double *)malloc((size_t)(len[u] > 0 ? len[u] : 1) * sizeof(double));
+        vatp_oracle_prefill_scores(Q + u * cap * d, K + u * cap * d, len[u], d, c,
+                                   S + u * cap, scratch);
+        free(scratch);
+    }
+}
+
+/*
+ * One decode-and-prune step for every unit, out of place:
+ * (K,V,S,nrm) hold n[u] rows that already include the appended token (S of that row 0).
+ * Scores are updated with q, importance formed, selection taken, survivors gathered
+ * into the *_out arrays; n_out[u] receives the new row count.
+ */
+void vatp_oracle_decode_prune_units(const double *q, const double *K, const double *V,
+                                    double *S, const double *nrm, int64_t units, int64_t cap,
+                                    const int64_t *n, int64_t d, double c, const int64_t *B,
+                                    int64_t F, int64_t R, double *K_out, double *V_out,
+                                    double *S_out, double *nrm_out, int32_t *kept,
+                                    int64_t *n_out)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t u = 0; u < units; ++u) {
+        int64_t nu = n[u];
+        double *scratch = (double *)malloc((size_t)(nu > 0 ? nu : 1) * sizeof(double));
+        double *I = (double *)malloc((size_t)(nu > 0 ? nu : 1) * sizeof(double));
+        vatp_oracle_decode_scores(q + u * d, K + u * cap * d, nu, d, c, S + u * cap, NULL, scratch);
+        vatp_oracle_importance(S + u * cap, nrm + u * cap, nu, 0, I);
+        int64_t nk = vatp_oracle_select(I, nu, B[u], F, R, kept + u * cap);
+        n_out[u] = nk;
+        if (nk >= 0) {
+            vatp_oracle_gather_rows(K + u * cap * d, kept + u * cap, nk, d, K_out + u * cap * d);
+            vatp_oracle_gather_rows(V + u * cap * d, kept + u * cap, nk, d, V_out + u * cap * d);
+            vatp_oracle_gather_rows(S + u * cap, kept + u * cap, nk, 1, S_out + u * cap);
+            vatp_oracle_gather_rows(nrm + u * cap, kept + u * cap, nk, 1, nrm_out + u * cap);
+        }
+        free(I);
+        free(scratch);
+    }
+}
+
+int vatp_oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

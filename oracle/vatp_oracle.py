@@ -1,0 +1,211 @@
+"""Python face of the float64 CPU oracle -- TEST INFRASTRUCTURE, NOT PART OF THE PRODUCT.
+
+Loads `liboracle.so` (built from vatp_oracle.c with gcc) through ctypes and offers
+  * thin per-head wrappers of the C functions, on numpy float64 arrays;
+  * `OracleHead`, the state of one attention head's pruned KV cache carried through the
+    prompt pass, the prune and the decode steps in the order the paper's Fig. 2 caption
+    gives (score, multiply by the value norm, remove the least important).
+
+Only tests, the smoke check and the bench's CPU-baseline leg may import this module.
+It imports nothing from the HIP package.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "vatp_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (plain -O2, no fast-math: IEEE double semantics)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
+                               "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+_f64p = ctypes.POINTER(ctypes.c_double)
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_i64p = ctypes.POINTER(ctypes.c_int64)
+_i64 = ctypes.c_int64
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        L.vatp_oracle_prefill_scores.argtypes = [_f64p, _f64p, _i64, _i64, ctypes.c_double, _f64p, _f64p]
+        L.vatp_oracle_prefill_scores.restype = None
+        L.vatp_oracle_decode_scores.argtypes = [_f64p, _f64p, _i64, _i64, ctypes.c_double, _f64p, _f64p, _f64p]
+        L.vatp_oracle_decode_scores.restype = None
+        L.vatp_oracle_l1norm.argtypes = [_f64p, _i64, _i64, _f64p]
+        L.vatp_oracle_l1norm.restype = None
+        L.vatp_oracle_importance.argtypes = [_f64p, _f64p, _i64, ctypes.c_int, _f64p]
+        L.vatp_oracle_importance.restype = None
+        L.vatp_oracle_select.argtypes = [_f64p, _i64, _i64, _i64, _i64, _i32p]
+        L.vatp_oracle_select.restype = _i64
+        L.vatp_oracle_gather_rows.argtypes = [_f64p, _i32p, _i64, _i64, _f64p]
+        L.vatp_oracle_gather_rows.restype = None
+        L.vatp_oracle_prefill_scores_units.argtypes = [_f64p, _f64p, _i64, _i64, _i64p, _i64,
+                                                       ctypes.c_double, _f64p]
+        L.vatp_oracle_prefill_scores_units.restype = None
+        L.vatp_oracle_decode_prune_units.argtypes = [_f64p, _f64p, _f64p, _f64p, _f64p, _i64, _i64,
+                                                     _i64p, _i64, ctypes.c_double, _i64p, _i64, _i64,
+                                                     _f64p, _f64p, _f64p, _f64p, _i32p, _i64p]
+        L.vatp_oracle_decode_prune_units.restype = None
+        L.vatp_oracle_max_threads.argtypes = []
+        L.vatp_oracle_max_threads.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _p(a: np.ndarray):
+    return a.ctypes.data_as(_f64p)
+
+
+def default_scale(d: int) -> float:
+    """Scaled dot-product attention: logits are <q,k>/sqrt(d)."""
+    return 1.0 / float(np.sqrt(np.float64(d)))
+
+
+def prefill_scores(Q, K, c: Optional[float] = None) -> np.ndarray:
+    """S_i = sum_{j>=i} a_i^j over a causal prompt pass (Eq. 1 and Eq. 2). Q, K: [L, d]."""
+    Q, K = _f64(Q), _f64(K)
+    L, d = Q.shape
+    assert K.shape == (L, d)
+    S = np.zeros(L, dtype=np.float64)
+    scratch = np.zeros(max(L, 1), dtype=np.float64)
+    lib().vatp_oracle_prefill_scores(_p(Q), _p(K), L, d, default_scale(d) if c is None else c,
+                                     _p(S), _p(scratch))
+    return S
+
+
+def decode_scores(q, K, S, c: Optional[float] = None):
+    """One decode step of Eq. 2. Returns (S + a, a) for the n rows of K."""
+    q, K = _f64(q), _f64(K)
+    n, d = K.shape
+    S = _f64(S).copy()
+    assert S.shape == (n,) and q.shape == (d,)
+    a = np.zeros(n, dtype=np.float64)
+    scratch = np.zeros(max(n, 1), dtype=np.float64)
+    lib().vatp_oracle_decode_scores(_p(q), _p(K), n, d, default_scale(d) if c is None else c,
+                                    _p(S), _p(a), _p(scratch))
+    return S, a
+
+
+def l1norm(V) -> np.ndarray:
+    V = _f64(V)
+    n, d = V.shape
+    out = np.zeros(n, dtype=np.float64)
+    lib().vatp_oracle_l1norm(_p(V), n, d, _p(out))
+    return out
+
+
+def importance(S, nrm, decide_f32: bool = False) -> np.ndarray:
+    """Eq. 4. decide_f32 rounds each product to binary32 (the GPU's comparison precision)."""
+    S, nrm = _f64(S), _f64(nrm)
+    out = np.zeros_like(S)
+    lib().vatp_oracle_importance(_p(S), _p(nrm), S.shape[0], int(decide_f32), _p(out))
+    return out
+
+
+def select(I, B: int, F: int, R: int) -> np.ndarray:
+    """Ascending surviving row indices (int32). Raises ValueError if B < F + R."""
+    I = _f64(I)
+    n = I.shape[0]
+    kept = np.zeros(max(min(n, B), 1), dtype=np.int32)
+    nk = lib().vatp_oracle_select(_p(I), n, B, F, R, kept.ctypes.data_as(_i32p))
+    if nk < 0:
+        raise ValueError("budget smaller than forced prefix + recent window")
+    return kept[:nk].copy()
+
+
+def gather_rows(x, kept) -> np.ndarray:
+    x = _f64(x)
+    kept = np.ascontiguousarray(kept, dtype=np.int32)
+    flat = x.reshape(x.shape[0], -1)
+    out = np.zeros((kept.shape[0], flat.shape[1]), dtype=np.float64)
+    lib().vatp_oracle_gather_rows(_p(flat), kept.ctypes.data_as(_i32p), kept.shape[0],
+                                  flat.shape[1], _p(out))
+    return out.reshape((kept.shape[0],) + x.shape[1:])
+
+
+def threshold_and_slack(I, n: int, B: int, F: int, R: int):
+    """tau = the smallest importance among the oracle's importance-selected candidates,
+    or None when nothing is selected by importance (n <= B or B == F + R)."""
+    if n <= B or B - F - R <= 0:
+        return None
+    cand = np.sort(np.asarray(I[F:n - R], dtype=np.float64))[::-1]
+    return float(cand[B - F - R - 1])
+
+
+class OracleHead:
+    """Pruned KV cache of one head, stepped exactly as the method prescribes.
+
+    prefill(Q, K, V)    full causal pass over the prompt, norms, no pruning yet
+    prune(B, F, R)      Eq. 4 importance -> budgeted selection -> compaction
+    append_and_score()  the new token's row joins the cache, its query attends over all
+                        rows (itself included) and the accumulated scores grow (Eq. 2)
+    `prune` accepts a forced surviving set so that a harness can re-align this state with
+    another implementation after an admissible near-tie difference.
+    """
+
+    def __init__(self, d: int, c: Optional[float] = None):
+        self.d = d
+        self.c = default_scale(d) if c is None else c
+        self.K = np.zeros((0, d))
+        self.V = np.zeros((0, d))
+        self.S = np.zeros(0)
+        self.nrm = np.zeros(0)
+        self.pos = np.zeros(0, dtype=np.int64)
+
+    @property
+    def n(self) -> int:
+        return self.K.shape[0]
+
+    def prefill(self, Q, K, V):
+        self.K, self.V = _f64(K).copy(), _f64(V).copy()
+        self.S = prefill_scores(Q, self.K, self.c)
+        self.nrm = l1norm(self.V)
+        self.pos = np.arange(self.K.shape[0], dtype=np.int64)
+
+    def importance(self, decide_f32: bool = False) -> np.ndarray:
+        return importance(self.S, self.nrm, decide_f32)
+
+    def prune(self, B: int, F: int, R: int, forced: Optional[Sequence[int]] = None) -> np.ndarray:
+        kept = select(self.importance(), B, F, R) if forced is None \
+            else np.ascontiguousarray(forced, dtype=np.int32)
+        self.K = gather_rows(self.K, kept)
+        self.V = gather_rows(self.V, kept)
+        self.S = gather_rows(self.S, kept)
+        self.nrm = gather_rows(self.nrm, kept)
+        self.pos = self.pos[kept]
+        return kept
+
+    def append_and_score(self, q, k, v, new_pos: int) -> np.ndarray:
+        self.K = np.concatenate([self.K, _f64(k)[None, :]], axis=0)
+        self.V = np.concatenate([self.V, _f64(v)[None, :]], axis=0)
+        self.S = np.concatenate([self.S, np.zeros(1)])
+        self.nrm = np.concatenate([self.nrm, l1norm(_f64(v)[None, :])])
+        self.pos = np.concatenate([self.pos, np.array([new_pos], dtype=np.int64)])
+        self.S, a = decode_scores(q, self.K, self.S, self.c)
+        return a
+
+
+def max_threads() -> int:
+    return int(lib().vatp_oracle_max_threads())

@@ -1,0 +1,265 @@
+"""Pins for the float64 CPU oracle: things the paper and the mathematics fix,
+none of which re-use the oracle's own code.
+
+  brute force      full attention matrix in pure Python (Eq. 1, 2, 4) on tiny inputs
+  library routine  torch float64 softmax / abs-sum / stable sort
+  closed forms     uniform attention -> harmonic sums (exact Fractions)
+  invariants       softmax rows sum to one; kept count equals the budget; protected rows
+  reductions       uniform value norms -> attention-only ranking; B = F + R -> sinks+window
+"""
+import math
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+import bruteforce as bf
+from oracle import vatp_oracle as orc
+
+
+def _rand(rng, *shape):
+    return rng.standard_normal(shape)
+
+
+# ---------------------------------------------------------------- brute force
+
+@pytest.mark.parametrize("L,d,seed", [(1, 1, 0), (2, 3, 1), (7, 4, 2), (19, 8, 3), (32, 8, 4)])
+def test_prefill_scores_match_bruteforce(L, d, seed):
+    rng = np.random.default_rng(seed)
+    Q, K = 2.0 * _rand(rng, L, d), 1.5 * _rand(rng, L, d)
+    c = 1.0 / math.sqrt(d)
+    A = bf.attention_matrix(Q.tolist(), K.tolist(), c)
+    S_bf = bf.accumulated_scores(A)
+    S = orc.prefill_scores(Q, K)
+    np.testing.assert_allclose(S, S_bf, rtol=1e-12, atol=0)
+
+
+def test_l1norm_and_importance_match_bruteforce():
+    rng = np.random.default_rng(5)
+    V = _rand(rng, 23, 8)
+    S = rng.random(23)
+    nrm = orc.l1norm(V)
+    np.testing.assert_allclose(nrm, bf.l1(V.tolist()), rtol=1e-15)
+    np.testing.assert_array_equal(orc.importance(S, nrm), S * nrm)
+    i32 = orc.importance(S, nrm, decide_f32=True)
+    np.testing.assert_array_equal(i32, (S * nrm).astype(np.float32).astype(np.float64))
+
+
+@pytest.mark.parametrize("n,B,F,R,seed", [(32, 16, 2, 4, 0), (32, 31, 0, 0, 1), (17, 9, 3, 6, 2),
+                                          (20, 20, 2, 4, 3), (12, 30, 2, 4, 4), (25, 7, 0, 7, 5)])
+def test_select_matches_sorted_bruteforce(n, B, F, R, seed):
+    rng = np.random.default_rng(seed)
+    I = rng.random(n)
+    I[rng.integers(0, n, 6)] = 0.25          # planted exact ties
+    kept = orc.select(I, B, F, R)
+    assert kept.tolist() == bf.keep_set(I.tolist(), n, B, F, R)
+
+
+@pytest.mark.parametrize("seed,B,F,R", [(0, 12, 2, 4), (1, 10, 0, 0), (2, 9, 1, 8)])
+def test_decode_trajectory_matches_bruteforce_replay(seed, B, F, R):
+    rng = np.random.default_rng(100 + seed)
+    L, d, T = 24, 6, 10
+    Q, K, V = _rand(rng, L, d) * 2, _rand(rng, L, d) * 2, _rand(rng, L, d)
+    V *= np.exp(0.7 * _rand(rng, L, 1))
+    qd, kd, vd = _rand(rng, T, d) * 2, _rand(rng, T, d) * 2, _rand(rng, T, d)
+    c = 1.0 / math.sqrt(d)
+    want = bf.replay(Q.tolist(), K.tolist(), V.tolist(), qd.tolist(), kd.tolist(), vd.tolist(),
+                     c, B, F, R)
+    h = orc.OracleHead(d)
+    h.prefill(Q, K, V)
+    kept = h.prune(B, F, R)
+    got = [(h.pos.tolist(), h.S.copy(), kept.tolist())]
+    for t in range(T):
+        h.append_and_score(qd[t], kd[t], vd[t], L + t)
+        kept = h.prune(B, F, R)
+        got.append((h.pos.tolist(), h.S.copy(), kept.tolist()))
+    assert len(got) == len(want)
+    for (gp, gS, gk), (wp, wS, wk) in zip(got, want):
+        assert gp == wp and gk == wk
+        np.testing.assert_allclose(gS, wS, rtol=1e-12)
+
+
+# ---------------------------------------------------------------- library routines
+
+@pytest.mark.parametrize("L,d", [(257, 64), (1024, 128)])
+def test_prefill_scores_match_torch_softmax(L, d):
+    g = torch.Generator().manual_seed(L)
+    Q = torch.randn(L, d, generator=g, dtype=torch.float64) * 1.3
+    K = torch.randn(L, d, generator=g, dtype=torch.float64)
+    logits = (Q @ K.T) / math.sqrt(d)
+    logits = logits.masked_fill(torch.triu(torch.ones(L, L, dtype=torch.bool), 1), float("-inf"))
+    want = torch.softmax(logits, dim=-1).sum(dim=0).numpy()
+    got = orc.prefill_scores(Q.numpy(), K.numpy())
+    np.testing.assert_allclose(got, want, rtol=1e-11)
+
+
+def test_decode_scores_match_torch_softmax():
+    g = torch.Generator().manual_seed(9)
+    n, d = 333, 128
+    K = torch.randn(n, d, generator=g, dtype=torch.float64)
+    q = torch.randn(d, generator=g, dtype=torch.float64) * 2
+    S0 = torch.rand(n, generator=g, dtype=torch.float64)
+    a = torch.softmax(K @ q / math.sqrt(d), dim=0)
+    S1, a_got = orc.decode_scores(q.numpy(), K.numpy(), S0.numpy())
+    np.testing.assert_allclose(a_got, a.numpy(), rtol=1e-12)
+    np.testing.assert_allclose(S1, (S0 + a).numpy(), rtol=1e-13)
+
+
+def test_l1norm_matches_torch():
+    g = torch.Generator().manual_seed(3)
+    V = torch.randn(100, 128, generator=g, dtype=torch.float64)
+    np.testing.assert_allclose(orc.l1norm(V.numpy()), V.abs().sum(-1).numpy(), rtol=1e-14)
+
+
+def test_select_matches_stable_argsort():
+    rng = np.random.default_rng(11)
+    n, B, F, R = 3000, 900, 20, 100
+    I = np.round(rng.random(n), 3)            # many exact ties
+    order = np.argsort(-I[F:n - R], kind="stable") + F
+    want = np.sort(np.concatenate([np.arange(F), order[:B - F - R], np.arange(n - R, n)]))
+    np.testing.assert_array_equal(orc.select(I, B, F, R), want)
+
+
+# ---------------------------------------------------------------- closed forms
+
+@pytest.mark.parametrize("L", [1, 5, 64])
+def test_uniform_attention_gives_harmonic_sums(L):
+    d = 4
+    K = np.random.default_rng(L).standard_normal((L, d))
+    Q = np.zeros((L, d))
+    want = [float(x) for x in bf.harmonic_scores(L)]
+    np.testing.assert_allclose(orc.prefill_scores(Q, K), want, rtol=1e-13)
+    # equal keys give the same uniform attention, whatever the queries are
+    Q2 = np.random.default_rng(L + 1).standard_normal((L, d))
+    np.testing.assert_allclose(orc.prefill_scores(Q2, np.tile(K[:1], (L, 1))), want, rtol=1e-12)
+
+
+def test_uniform_attention_equal_norms_keeps_oldest_candidates():
+    L, d, B, F, R = 40, 4, 20, 3, 5
+    S = orc.prefill_scores(np.zeros((L, d)), np.ones((L, d)))
+    assert np.all(np.diff(S) < 0)                       # H_L - H_i strictly decreasing
+    kept = orc.select(orc.importance(S, np.full(L, 7.0)), B, F, R)
+    assert kept.tolist() == list(range(B - R)) + list(range(L - R, L))
+
+
+def test_group_onehot_attention_gives_per_group_harmonic_sums():
+    # tokens alternate between two groups; a very large logit inside the own group makes
+    # attention uniform over the earlier tokens of the same group
+    L, beta = 12, 60.0
+    grp = [j % 2 for j in range(L)]
+    E = np.eye(2)
+    Q = np.array([beta * E[g] for g in grp])
+    K = np.array([beta * E[g] for g in grp])
+    S = orc.prefill_scores(Q, K, c=1.0)
+    for i in range(L):
+        same = [j for j in range(L) if grp[j] == grp[i]]
+        rank = {j: r for r, j in enumerate(same)}
+        want = sum(Fraction(1, rank[j] + 1) for j in same if j >= i)
+        assert S[i] == pytest.approx(float(want), rel=1e-12)
+
+
+# ---------------------------------------------------------------- invariants
+
+def test_softmax_rows_sum_to_one_invariants():
+    rng = np.random.default_rng(21)
+    L, d = 300, 16
+    Q, K = 3 * _rand(rng, L, d), 3 * _rand(rng, L, d)
+    S = orc.prefill_scores(Q, K)
+    assert S.sum() == pytest.approx(L, rel=1e-12)       # every query row distributes mass 1
+    assert S[0] >= 1.0                                  # a_0^0 = 1
+    assert 0.0 < S[-1] <= 1.0                           # only the last query sees the last key
+    assert np.all(S > 0)
+    q = _rand(rng, d)
+    S2, a = orc.decode_scores(q, K, S)
+    assert a.sum() == pytest.approx(1.0, rel=1e-13)
+    assert S2.sum() == pytest.approx(L + 1.0, rel=1e-12)
+
+
+def test_key_shift_leaves_scores_unchanged_and_value_scale_is_homogeneous():
+    rng = np.random.default_rng(22)
+    L, d = 64, 8
+    Q, K, V = _rand(rng, L, d), _rand(rng, L, d), _rand(rng, L, d)
+    S = orc.prefill_scores(Q, K)
+    np.testing.assert_allclose(orc.prefill_scores(Q, K + _rand(rng, 1, d)), S, rtol=1e-10)
+    alpha = rng.random(L) + 0.5
+    I = orc.importance(S, orc.l1norm(V))
+    I2 = orc.importance(S, orc.l1norm(V * alpha[:, None]))
+    np.testing.assert_allclose(I2, alpha * I, rtol=1e-13)
+    assert orc.select(I, 20, 2, 4).tolist() == orc.select(8.0 * I, 20, 2, 4).tolist()
+    # swapping Q and K is a different computation: a transposed operand cannot pass unnoticed
+    assert not np.allclose(orc.prefill_scores(K, Q), S, rtol=1e-3)
+
+
+@pytest.mark.parametrize("n,B,F,R", [(100, 40, 2, 8), (100, 99, 0, 0), (50, 10, 5, 5), (9, 9, 1, 1)])
+def test_selection_invariants(n, B, F, R):
+    rng = np.random.default_rng(n + B)
+    I = rng.random(n)
+    kept = orc.select(I, B, F, R)
+    assert len(kept) == min(n, B)
+    assert np.all(np.diff(kept) > 0)
+    assert set(range(F)) <= set(kept.tolist())
+    assert set(range(n - R, n)) <= set(kept.tolist())
+    dropped = sorted(set(range(n)) - set(kept.tolist()))
+    heavy = [r for r in kept.tolist() if F <= r < n - R]
+    if dropped and heavy:
+        assert min(I[heavy]) >= max(I[dropped])
+    rows = rng.standard_normal((n, 5))
+    np.testing.assert_array_equal(orc.gather_rows(rows, kept), rows[kept])   # bit-for-bit
+
+
+def test_budget_smaller_than_protected_rows_is_an_error():
+    with pytest.raises(ValueError):
+        orc.select(np.ones(50), 9, 4, 6)
+
+
+# ---------------------------------------------------------------- reductions to known methods
+
+def test_uniform_value_norms_reduce_to_attention_only_ranking():
+    rng = np.random.default_rng(31)
+    L, d, B, F, R = 200, 16, 60, 2, 10
+    Q, K = 2 * _rand(rng, L, d), 2 * _rand(rng, L, d)
+    V = rng.choice([-1.0, 1.0], size=(L, d))            # every row has l1 norm exactly d
+    S = orc.prefill_scores(Q, K)
+    nrm = orc.l1norm(V)
+    assert np.all(nrm == d)
+    vatp = orc.select(orc.importance(S, nrm), B, F, R)
+    attn_only = orc.select(S, B, F, R)
+    assert vatp.tolist() == attn_only.tolist()
+    # and a non-uniform norm does change the set (the metric is not attention-only)
+    nrm2 = nrm * np.exp(rng.standard_normal(L))
+    assert orc.select(orc.importance(S, nrm2), B, F, R).tolist() != attn_only.tolist()
+
+
+def test_zero_importance_slots_reduce_to_sinks_plus_window():
+    rng = np.random.default_rng(32)
+    n, F, R = 80, 4, 12
+    kept = orc.select(rng.random(n), F + R, F, R)
+    assert kept.tolist() == list(range(F)) + list(range(n - R, n))
+
+
+def test_exact_ties_keep_lowest_indices_and_evict_one_takes_last_minimum():
+    n, F, R = 30, 2, 4
+    I = np.linspace(1.0, 2.0, n)
+    zero_rows = [5, 9, 10, 17, 21]
+    I[zero_rows] = 0.0                                  # e.g. all-zero value rows
+    kept = orc.select(I, n - 2, F, R)                   # evict two of the five tied rows
+    assert sorted(set(range(n)) - set(kept.tolist())) == [17, 21]
+    I2 = np.array([3.0, 1.0, 2.0, 1.0, 5.0, 1.0, 4.0])
+    kept = orc.select(I2, len(I2) - 1, 0, 0)            # F = R = 0, evict one
+    assert sorted(set(range(7)) - set(kept.tolist())) == [5]
+
+
+def test_splitting_units_gives_identical_results():
+    rng = np.random.default_rng(33)
+    units, cap, d = 3, 20, 4
+    lens = np.array([20, 7, 13], dtype=np.int64)
+    Q, K = _rand(rng, units, cap, d), _rand(rng, units, cap, d)
+    S = np.zeros((units, cap))
+    import ctypes
+    f64p = ctypes.POINTER(ctypes.c_double)
+    orc.lib().vatp_oracle_prefill_scores_units(
+        Q.ctypes.data_as(f64p), K.ctypes.data_as(f64p), units, cap,
+        lens.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), d, 0.5, S.ctypes.data_as(f64p))
+    for u in range(units):
+        np.testing.assert_array_equal(S[u, :lens[u]], orc.prefill_scores(Q[u, :lens[u]], K[u, :lens[u]], 0.5))
