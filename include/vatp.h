@@ -1,0 +1,138 @@
+/*
+ * vatp.h -- C ABI of the MI355X (gfx950) value-aware token pruning library.
+ *
+ * The library scores the tokens of a per-head KV cache by accumulated attention
+ * (paper Eq. 2) times the l1 norm of the token's value vector (Eq. 4), keeps a fixed
+ * budget of rows per head -- a forced prefix of F "attention sink" rows, a window of the
+ * R most recent rows and the most important of the rest -- and compacts the surviving
+ * K/V rows (Methodology section; Implementation Details appendix; Fig. 2).
+ *
+ * Conventions shared by every call
+ *   - Plain C types only.  Pointers named in UPPER CASE or documented "device" are device
+ *     pointers owned by the caller; `len`, `budget`, `new_pos` are HOST arrays.  The
+ *     library never allocates or frees device memory in a call (vatp_create allocates one
+ *     small device block of counters that vatp_destroy frees).
+ *   - Layout is head-major: a cache tensor is [batch, n_heads, cap, head_dim] contiguous,
+ *     per-row scalars (S, nrm, pos) are [batch, n_heads, cap].  Heads keep different
+ *     tokens after pruning, so every (batch, head) unit owns `cap` rows of its own.
+ *     Rows [0, len[b]) of a unit are valid; the others are never read.
+ *   - dtype covers Q, K, V and the caches; S and nrm are always float32, pos int32.
+ *   - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = the null
+ *     stream) and return without synchronising.  Errors that can be seen before launch
+ *     are returned at once and nothing is enqueued; launch failures give VATP_E_DEVICE.
+ *   - A context serves one stream at a time: calls that share a context must be
+ *     stream-ordered with respect to each other.
+ *   - Inputs must be finite.  A NaN or infinity in Q, K or V gives unspecified scores
+ *     (never an out-of-bounds access).
+ */
+#ifndef VATP_H
+#define VATP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VATP_MAX_BATCH 64          /* sequences per call                                  */
+#define VATP_MAX_UNITS 16384       /* batch * n_heads per call                            */
+
+typedef struct vatp_ctx vatp_ctx;  /* opaque */
+
+typedef enum {
+    VATP_OK = 0,
+    VATP_E_NULL = -1,        /* a required pointer is NULL                                 */
+    VATP_E_SHAPE = -2,       /* batch / heads / head_dim / cap / len out of range          */
+    VATP_E_DTYPE = -3,       /* dtype is neither VATP_F32 nor VATP_BF16                    */
+    VATP_E_BUDGET = -4,      /* budget[b] < n_sink + recent, or budget[b] > cap_out        */
+    VATP_E_WORKSPACE = -5,   /* workspace missing, too small or not 256-byte aligned       */
+    VATP_E_DEVICE = -6       /* HIP reported an error (no device, launch failure)          */
+} vatp_status;
+
+enum { VATP_F32 = 0, VATP_BF16 = 1 };
+enum { VATP_CALL_PREFILL_SCORE = 0, VATP_CALL_DECODE_STEP = 1, VATP_CALL_SELECT_COMPACT = 2 };
+
+typedef struct {
+    int32_t batch;          /* 1 .. VATP_MAX_BATCH                                         */
+    int32_t n_heads;        /* >= 1, batch * n_heads <= VATP_MAX_UNITS                     */
+    int32_t head_dim;       /* 64 or 128                                                   */
+    int32_t dtype;          /* VATP_F32 or VATP_BF16                                       */
+    int32_t n_sink;         /* F: rows [0,F) are always kept (Attention Sink Tokens par.)  */
+    int32_t recent;         /* R: the last R rows are always kept (local window, App. A)   */
+    int32_t cap;            /* rows allocated per (batch, head) unit in the input buffers  */
+    int32_t cap_out;        /* same for the *_out buffers of vatp_select_compact; 0 = cap  */
+    float   scale;          /* logit scale c; 0 selects 1/sqrt(head_dim)                   */
+    const int32_t *len;     /* HOST [batch]: valid rows per sequence, same for all heads   */
+    const int32_t *budget;  /* HOST [batch]: B, rows kept per head (F and R included).     */
+                            /*   only vatp_select_compact reads it; may be NULL elsewhere  */
+} vatp_params;
+
+/* Creates a context on HIP device `device` (allocates a 64 KiB zeroed counter block). */
+vatp_status vatp_create(vatp_ctx **ctx, int device);
+void        vatp_destroy(vatp_ctx *ctx);
+const char *vatp_strerror(vatp_status st);
+
+/*
+ * Checks `p` for call `which_call` (a VATP_CALL_* value) exactly as that call does before
+ * it launches anything; touches no device.  For VATP_CALL_DECODE_STEP, len[b] + 1 <= cap
+ * is required (room for the appended row).
+ */
+vatp_status vatp_validate(const vatp_params *p, int which_call);
+
+/* Bytes of device workspace call `which_call` needs for `p` (0 on invalid params).
+ * `ctx` may be NULL.  The workspace must be 256-byte aligned; its contents on entry do
+ * not matter and are undefined on return. */
+size_t vatp_workspace_bytes(const vatp_ctx *ctx, const vatp_params *p, int which_call);
+
+/*
+ * Prompt pass (Eq. 1 and Eq. 2 with t = len-1; Eq. 4's norm).
+ * For every unit:  S[i]   = sum_{j=i}^{len-1} softmax_{i'<=j}(c <q_j, k_i'>)[i]
+ *                  nrm[i] = sum_x |V[i][x]|                       for i < len[b].
+ * Q, K, V: device [batch, n_heads, cap, head_dim] (dtype).  S, nrm: device float32
+ * [batch, n_heads, cap], written for rows < len[b] only.  Nothing is pruned here.
+ */
+vatp_status vatp_prefill_score(vatp_ctx *ctx, const vatp_params *p,
+                               const void *Q, const void *K, const void *V,
+                               float *S, float *nrm,
+                               void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * One decode step (Eq. 2 taken incrementally; order of operations as in Fig. 2).
+ * For every unit with n0 = len[b] rows: the new token's k, v are stored as row n0 of the
+ * K, V caches, nrm[n0] = |v|_1, pos[n0] = new_pos[b]; the new query attends over the
+ * n0 + 1 rows and S[r] += a_r for r <= n0 (row n0 starts from 0).  The caller then uses
+ * len[b] + 1.  q, k, v: device [batch, n_heads, head_dim] (dtype).  K, V, S, nrm, pos:
+ * device caches, updated in place.  pos may be NULL (then new_pos may be NULL too).
+ * new_pos: HOST [batch].
+ */
+vatp_status vatp_decode_step(vatp_ctx *ctx, const vatp_params *p,
+                             const void *q, const void *k, const void *v,
+                             void *K, void *V, float *S, float *nrm, int32_t *pos,
+                             const int32_t *new_pos,
+                             void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Budgeted selection and compaction (Eq. 4; forced prefix, budget and local window from
+ * the Attention Sink Tokens paragraph and the Implementation Details appendix).
+ * For every unit with n = len[b] rows and B = budget[b]:
+ *   n <= B : all rows survive (identity copy);
+ *   else   : rows [0,F) and [n-R,n) survive, and of rows [F,n-R) the B-F-R with the
+ *            largest I = S*nrm (float32 product; equal I: the lower row index wins).
+ * The min(n,B) survivors are written, in ascending source-row order, to rows
+ * [0, min(n,B)) of K_out, V_out ([batch, n_heads, cap_out, head_dim]) and S_out, nrm_out,
+ * pos_out ([batch, n_heads, cap_out]); kept_idx ([batch, n_heads, cap_out], int32)
+ * receives the source row of each survivor.  Out-of-place: no *_out buffer may alias an
+ * input.  pos / pos_out may both be NULL.  The caller then uses len[b] = min(n, B).
+ */
+vatp_status vatp_select_compact(vatp_ctx *ctx, const vatp_params *p,
+                                const void *K, const void *V, const float *S,
+                                const float *nrm, const int32_t *pos,
+                                void *K_out, void *V_out, float *S_out, float *nrm_out,
+                                int32_t *pos_out, int32_t *kept_idx,
+                                void *ws, size_t ws_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VATP_H */

@@ -24,12 +24,15 @@
  * scaled dot products c * <q_j, k_i>):
  *     S_i = sum_{j=i}^{L-1} a_i^j .
  * Q, K: [L, d].  S: [L] (overwritten).  scratch: [L] doubles.
+ * j_start > 0 restricts the sum to query rows j >= j_start: the entries i >= j_start are
+ * then still the complete S_i (no earlier query sees those keys), which lets a test check
+ * the tail of a very long prompt without paying for all of its rows.
  */
-void vatp_oracle_prefill_scores(const double *Q, const double *K, int64_t L, int64_t d,
-                                double c, double *S, double *scratch)
+void vatp_oracle_prefill_scores_from(const double *Q, const double *K, int64_t L, int64_t d,
+                                     double c, int64_t j_start, double *S, double *scratch)
 {
     for (int64_t i = 0; i < L; ++i) S[i] = 0.0;
-    for (int64_t j = 0; j < L; ++j) {
+    for (int64_t j = j_start; j < L; ++j) {
         const double *q = Q + j * d;
         double m = -INFINITY;
         for (int64_t i = 0; i <= j; ++i) {
@@ -46,6 +49,12 @@ void vatp_oracle_prefill_scores(const double *Q, const double *K, int64_t L, int
         }
         for (int64_t i = 0; i <= j; ++i) S[i] += scratch[i] / denom;
     }
+}
+
+void vatp_oracle_prefill_scores(const double *Q, const double *K, int64_t L, int64_t d,
+                                double c, double *S, double *scratch)
+{
+    vatp_oracle_prefill_scores_from(Q, K, L, d, c, 0, S, scratch);
 }
 
 /*

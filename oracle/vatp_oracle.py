@@ -47,6 +47,8 @@ def lib():
         L = ctypes.CDLL(build())
         L.vatp_oracle_prefill_scores.argtypes = [_f64p, _f64p, _i64, _i64, ctypes.c_double, _f64p, _f64p]
         L.vatp_oracle_prefill_scores.restype = None
+        L.vatp_oracle_prefill_scores_from.argtypes = [_f64p, _f64p, _i64, _i64, ctypes.c_double, _i64, _f64p, _f64p]
+        L.vatp_oracle_prefill_scores_from.restype = None
         L.vatp_oracle_decode_scores.argtypes = [_f64p, _f64p, _i64, _i64, ctypes.c_double, _f64p, _f64p, _f64p]
         L.vatp_oracle_decode_scores.restype = None
         L.vatp_oracle_l1norm.argtypes = [_f64p, _i64, _i64, _f64p]
@@ -92,6 +94,28 @@ def prefill_scores(Q, K, c: Optional[float] = None) -> np.ndarray:
     scratch = np.zeros(max(L, 1), dtype=np.float64)
     lib().vatp_oracle_prefill_scores(_p(Q), _p(K), L, d, default_scale(d) if c is None else c,
                                      _p(S), _p(scratch))
+    return S
+
+
+def prefill_scores_tail(Q, K, j_start: int, c: Optional[float] = None) -> np.ndarray:
+    """Entries i >= j_start of prefill_scores(Q, K), from the query rows j >= j_start only."""
+    Q, K = _f64(Q), _f64(K)
+    L, d = Q.shape
+    S = np.zeros(L, dtype=np.float64)
+    scratch = np.zeros(max(L, 1), dtype=np.float64)
+    lib().vatp_oracle_prefill_scores_from(_p(Q), _p(K), L, d, default_scale(d) if c is None else c,
+                                          int(j_start), _p(S), _p(scratch))
+    return S[j_start:]
+
+
+def prefill_scores_units(Q, K, lens, c: Optional[float] = None) -> np.ndarray:
+    """prefill_scores for every unit of Q, K: [units, cap, d] (OpenMP over units). Returns [units, cap]."""
+    Q, K = _f64(Q), _f64(K)
+    units, cap, d = Q.shape
+    lens = np.ascontiguousarray(lens, dtype=np.int64)
+    S = np.zeros((units, cap), dtype=np.float64)
+    lib().vatp_oracle_prefill_scores_units(_p(Q), _p(K), units, cap, lens.ctypes.data_as(_i64p), d,
+                                           default_scale(d) if c is None else c, _p(S))
     return S
 
 

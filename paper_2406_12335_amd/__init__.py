@@ -1,0 +1,10 @@
+"""MI355X-native value-aware token pruning (VATP) hot path: HIP kernels behind a C ABI.
+
+`binding` mirrors the C entry points one to one; `runner.PrunedKVCache` only owns the
+device buffers of a pruned per-head KV cache and calls the entry points in order.
+"""
+from .binding import (  # noqa: F401
+    CALL_DECODE_STEP, CALL_PREFILL_SCORE, CALL_SELECT_COMPACT, VATP_BF16, VATP_F32, Params, VatpError,
+    load, strerror, vatp_create, vatp_decode_step, vatp_destroy, vatp_prefill_score, vatp_select_compact,
+    vatp_validate, vatp_workspace_bytes,
+)

@@ -1,0 +1,158 @@
+"""ctypes binding of libvatp.so: argument marshalling only.
+
+Every function has the name and the argument order of the C entry point it calls
+(include/vatp.h); torch tensors stand for device pointers, Python int lists for the host
+arrays.  Nothing is computed here, and there is no fallback: if the HIP library is
+missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libvatp.so")
+
+VATP_F32, VATP_BF16 = 0, 1
+CALL_PREFILL_SCORE, CALL_DECODE_STEP, CALL_SELECT_COMPACT = 0, 1, 2
+VATP_MAX_BATCH, VATP_MAX_UNITS = 64, 16384
+OK, E_NULL, E_SHAPE, E_DTYPE, E_BUDGET, E_WORKSPACE, E_DEVICE = 0, -1, -2, -3, -4, -5, -6
+
+EXPORTS = ("vatp_create", "vatp_destroy", "vatp_strerror", "vatp_validate", "vatp_workspace_bytes",
+           "vatp_prefill_score", "vatp_decode_step", "vatp_select_compact")
+
+
+class VatpError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s (%d)" % (where, strerror(status), status))
+
+
+class _Params(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("n_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("n_sink", ctypes.c_int32), ("recent", ctypes.c_int32),
+                ("cap", ctypes.c_int32), ("cap_out", ctypes.c_int32), ("scale", ctypes.c_float),
+                ("len", ctypes.POINTER(ctypes.c_int32)), ("budget", ctypes.POINTER(ctypes.c_int32))]
+
+
+_lib = None
+_vp = ctypes.c_void_p
+
+
+def load() -> ctypes.CDLL:
+    """Loads the built library; builds it first only when no built library exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build_library()
+    L = ctypes.CDLL(LIB_PATH)
+    pp = ctypes.POINTER(_Params)
+    L.vatp_create.argtypes = [ctypes.POINTER(_vp), ctypes.c_int]
+    L.vatp_create.restype = ctypes.c_int
+    L.vatp_destroy.argtypes = [_vp]
+    L.vatp_destroy.restype = None
+    L.vatp_strerror.argtypes = [ctypes.c_int]
+    L.vatp_strerror.restype = ctypes.c_char_p
+    L.vatp_validate.argtypes = [pp, ctypes.c_int]
+    L.vatp_validate.restype = ctypes.c_int
+    L.vatp_workspace_bytes.argtypes = [_vp, pp, ctypes.c_int]
+    L.vatp_workspace_bytes.restype = ctypes.c_size_t
+    L.vatp_prefill_score.argtypes = [_vp, pp] + [_vp] * 5 + [_vp, ctypes.c_size_t, _vp]
+    L.vatp_prefill_score.restype = ctypes.c_int
+    L.vatp_decode_step.argtypes = [_vp, pp] + [_vp] * 8 + [ctypes.POINTER(ctypes.c_int32), _vp, ctypes.c_size_t, _vp]
+    L.vatp_decode_step.restype = ctypes.c_int
+    L.vatp_select_compact.argtypes = [_vp, pp] + [_vp] * 11 + [_vp, ctypes.c_size_t, _vp]
+    L.vatp_select_compact.restype = ctypes.c_int
+    _lib = L
+    return L
+
+
+def strerror(status: int) -> str:
+    return load().vatp_strerror(int(status)).decode()
+
+
+class Params:
+    """Host-side mirror of vatp_params; keeps the int arrays alive while a call runs."""
+
+    def __init__(self, batch: int, n_heads: int, head_dim: int, dtype, n_sink: int, recent: int,
+                 cap: int, len: Sequence[int], budget: Optional[Sequence[int]] = None,
+                 cap_out: int = 0, scale: float = 0.0):
+        if isinstance(dtype, torch.dtype):
+            dtype = {torch.float32: VATP_F32, torch.bfloat16: VATP_BF16}.get(dtype, -1)
+        self._len = (ctypes.c_int32 * max(1, batch))(*list(len)) if len is not None else None
+        self._budget = (ctypes.c_int32 * max(1, batch))(*list(budget)) if budget is not None else None
+        self.c = _Params(batch, n_heads, head_dim, int(dtype), n_sink, recent, cap, cap_out, scale,
+                         ctypes.cast(self._len, ctypes.POINTER(ctypes.c_int32)) if self._len is not None else None,
+                         ctypes.cast(self._budget, ctypes.POINTER(ctypes.c_int32)) if self._budget is not None else None)
+
+    def set_len(self, len: Sequence[int]) -> None:
+        for i, v in enumerate(len):
+            self._len[i] = int(v)
+
+    def ref(self):
+        return ctypes.byref(self.c)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("vatp: tensors must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _check(st: int, where: str) -> None:
+    if st != OK:
+        raise VatpError(st, where)
+
+
+def vatp_create(device: int = 0) -> ctypes.c_void_p:
+    ctx = _vp()
+    _check(load().vatp_create(ctypes.byref(ctx), int(device)), "vatp_create")
+    return ctx
+
+
+def vatp_destroy(ctx) -> None:
+    load().vatp_destroy(ctx)
+
+
+def vatp_validate(p: Params, which_call: int) -> int:
+    return int(load().vatp_validate(p.ref(), which_call))
+
+
+def vatp_workspace_bytes(ctx, p: Params, which_call: int) -> int:
+    return int(load().vatp_workspace_bytes(ctx, p.ref(), which_call))
+
+
+def vatp_prefill_score(ctx, p: Params, Q, K, V, S, nrm, ws, stream=None) -> None:
+    _check(load().vatp_prefill_score(ctx, p.ref(), _ptr(Q), _ptr(K), _ptr(V), _ptr(S), _ptr(nrm),
+                                     _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0,
+                                     _stream(stream)), "vatp_prefill_score")
+
+
+def vatp_decode_step(ctx, p: Params, q, k, v, K, V, S, nrm, pos, new_pos: Optional[Sequence[int]], ws,
+                     stream=None) -> None:
+    npos = (ctypes.c_int32 * len(new_pos))(*[int(x) for x in new_pos]) if new_pos is not None else None
+    _check(load().vatp_decode_step(ctx, p.ref(), _ptr(q), _ptr(k), _ptr(v), _ptr(K), _ptr(V), _ptr(S), _ptr(nrm),
+                                   _ptr(pos), npos, _ptr(ws),
+                                   ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)),
+           "vatp_decode_step")
+
+
+def vatp_select_compact(ctx, p: Params, K, V, S, nrm, pos, K_out, V_out, S_out, nrm_out, pos_out, kept_idx,
+                        ws=None, stream=None) -> None:
+    _check(load().vatp_select_compact(ctx, p.ref(), _ptr(K), _ptr(V), _ptr(S), _ptr(nrm), _ptr(pos), _ptr(K_out),
+                                      _ptr(V_out), _ptr(S_out), _ptr(nrm_out), _ptr(pos_out), _ptr(kept_idx),
+                                      _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0,
+                                      _stream(stream)), "vatp_select_compact")

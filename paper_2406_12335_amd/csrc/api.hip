@@ -1,0 +1,228 @@
+// C ABI of libvatp: argument checks, workspace carving and kernel dispatch.
+// Declarations and the contract of every call are in include/vatp.h.
+#include <math.h>
+#include <new>
+
+#include "vatp_device.h"
+
+using namespace vatp;
+
+struct vatp_ctx {
+    int device;
+    unsigned *counters;      // VATP_MAX_UNITS arrival counters, zero between calls
+};
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Prepared {
+    BatchMeta meta;
+    Geometry g;
+};
+
+vatp_status check_params(const vatp_params *p, int which_call)
+{
+    if (!p || !p->len) return VATP_E_NULL;
+    if (which_call == VATP_CALL_SELECT_COMPACT && !p->budget) return VATP_E_NULL;
+    if (which_call < VATP_CALL_PREFILL_SCORE || which_call > VATP_CALL_SELECT_COMPACT) return VATP_E_SHAPE;
+    if (p->dtype != VATP_F32 && p->dtype != VATP_BF16) return VATP_E_DTYPE;
+    if (p->batch < 1 || p->batch > VATP_MAX_BATCH || p->n_heads < 1) return VATP_E_SHAPE;
+    if (static_cast<int64_t>(p->batch) * p->n_heads > VATP_MAX_UNITS) return VATP_E_SHAPE;
+    if (p->head_dim != 64 && p->head_dim != 128) return VATP_E_SHAPE;
+    if (p->cap < 1 || p->cap_out < 0 || p->n_sink < 0 || p->recent < 0) return VATP_E_SHAPE;
+    if (!(p->scale >= 0.f) || isinf(p->scale)) return VATP_E_SHAPE;
+    // element counts of one buffer stay below 2^40 (indexing is 64-bit, row indices 32-bit)
+    if (static_cast<double>(p->batch) * p->n_heads * static_cast<double>(p->cap > p->cap_out ? p->cap : p->cap_out) *
+            p->head_dim > 1099511627776.0)
+        return VATP_E_SHAPE;
+    const int cap_out = p->cap_out ? p->cap_out : p->cap;
+    for (int b = 0; b < p->batch; ++b) {
+        const int len = p->len[b];
+        if (len < 0 || len > p->cap) return VATP_E_SHAPE;
+        if (which_call == VATP_CALL_DECODE_STEP && len + 1 > p->cap) return VATP_E_SHAPE;
+        if (which_call == VATP_CALL_SELECT_COMPACT) {
+            const int B = p->budget[b];
+            if (B < 0 || B < p->n_sink + p->recent) return VATP_E_BUDGET;
+            const int n_keep = len < B ? len : B;
+            if (n_keep > cap_out) return VATP_E_BUDGET;
+        }
+    }
+    return VATP_OK;
+}
+
+void prepare(const vatp_params *p, int which_call, const int32_t *new_pos, Prepared *out)
+{
+    Geometry &g = out->g;
+    g.batch = p->batch;
+    g.n_heads = p->n_heads;
+    g.cap = p->cap;
+    g.cap_out = p->cap_out ? p->cap_out : p->cap;
+    g.n_sink = p->n_sink;
+    g.recent = p->recent;
+    const double c = p->scale > 0.f ? static_cast<double>(p->scale) : 1.0 / sqrt(static_cast<double>(p->head_dim));
+    g.scale_log2 = static_cast<float>(c * 1.4426950408889634074);
+    g.max_len = 0;
+    for (int b = 0; b < VATP_MAX_BATCH; ++b) { out->meta.len[b] = 0; out->meta.aux[b] = 0; }
+    for (int b = 0; b < p->batch; ++b) {
+        const int len = p->len[b];
+        out->meta.len[b] = len;
+        int extent = len;
+        if (which_call == VATP_CALL_DECODE_STEP) {
+            out->meta.aux[b] = new_pos ? new_pos[b] : 0;
+            extent = len + 1;
+        } else if (which_call == VATP_CALL_SELECT_COMPACT) {
+            out->meta.aux[b] = p->budget[b];
+            extent = len < p->budget[b] ? len : p->budget[b];
+        }
+        if (extent > g.max_len) g.max_len = extent;
+    }
+}
+
+inline bool misaligned(const void *ptr, size_t a) { return (reinterpret_cast<uintptr_t>(ptr) & (a - 1)) != 0; }
+
+}  // namespace
+
+#pragma GCC visibility push(default)
+extern "C" {
+
+const char *vatp_strerror(vatp_status st)
+{
+    switch (st) {
+    case VATP_OK: return "ok";
+    case VATP_E_NULL: return "a required pointer is NULL";
+    case VATP_E_SHAPE: return "shape out of range (batch, heads, head_dim, cap or len)";
+    case VATP_E_DTYPE: return "unsupported dtype";
+    case VATP_E_BUDGET: return "budget smaller than n_sink + recent, or larger than cap_out";
+    case VATP_E_WORKSPACE: return "workspace missing, too small or misaligned";
+    case VATP_E_DEVICE: return "HIP error";
+    }
+    return "unknown status";
+}
+
+vatp_status vatp_create(vatp_ctx **ctx, int device)
+{
+    if (!ctx) return VATP_E_NULL;
+    *ctx = nullptr;
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) {
+        (void)hipGetLastError();
+        return VATP_E_DEVICE;
+    }
+    int prev = 0;
+    if (hipGetDevice(&prev) != hipSuccess) return VATP_E_DEVICE;
+    if (hipSetDevice(device) != hipSuccess) return VATP_E_DEVICE;
+    unsigned *counters = nullptr;
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&counters), VATP_MAX_UNITS * sizeof(unsigned));
+    if (e == hipSuccess) e = hipMemset(counters, 0, VATP_MAX_UNITS * sizeof(unsigned));
+    (void)hipSetDevice(prev);
+    if (e != hipSuccess) {
+        if (counters) (void)hipFree(counters);
+        (void)hipGetLastError();
+        return VATP_E_DEVICE;
+    }
+    vatp_ctx *c = new (std::nothrow) vatp_ctx;
+    if (!c) { (void)hipFree(counters); return VATP_E_DEVICE; }
+    c->device = device;
+    c->counters = counters;
+    *ctx = c;
+    return VATP_OK;
+}
+
+void vatp_destroy(vatp_ctx *ctx)
+{
+    if (!ctx) return;
+    if (ctx->counters) (void)hipFree(ctx->counters);
+    delete ctx;
+}
+
+vatp_status vatp_validate(const vatp_params *p, int which_call) { return check_params(p, which_call); }
+
+size_t vatp_workspace_bytes(const vatp_ctx *, const vatp_params *p, int which_call)
+{
+    if (check_params(p, which_call) != VATP_OK) return 0;
+    const size_t units = static_cast<size_t>(p->batch) * p->n_heads;
+    switch (which_call) {
+    case VATP_CALL_PREFILL_SCORE:           // lse2[units, cap]
+        return align_up(units * p->cap * sizeof(float));
+    case VATP_CALL_DECODE_STEP: {           // logits[units, cap] + chunk statistics
+        const size_t chunks = (static_cast<size_t>(p->cap) + kDecodeChunk - 1) / kDecodeChunk;
+        return align_up(units * p->cap * sizeof(float)) + align_up(units * chunks * sizeof(float2));
+    }
+    default:
+        return 0;
+    }
+}
+
+vatp_status vatp_prefill_score(vatp_ctx *ctx, const vatp_params *p, const void *Q, const void *K,
+                               const void *V, float *S, float *nrm, void *ws, size_t ws_bytes,
+                               void *hip_stream)
+{
+    if (!ctx || !Q || !K || !V || !S || !nrm) return VATP_E_NULL;
+    const vatp_status st = check_params(p, VATP_CALL_PREFILL_SCORE);
+    if (st != VATP_OK) return st;
+    if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16)) return VATP_E_SHAPE;
+    const size_t need = vatp_workspace_bytes(ctx, p, VATP_CALL_PREFILL_SCORE);
+    if (!ws || ws_bytes < need || misaligned(ws, kAlign)) return VATP_E_WORKSPACE;
+    Prepared pr;
+    prepare(p, VATP_CALL_PREFILL_SCORE, nullptr, &pr);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (launch_l1norm(p->dtype, p->head_dim, V, nrm, pr.meta, pr.g, stream) != hipSuccess) return VATP_E_DEVICE;
+    if (launch_prefill_generic(p->dtype, p->head_dim, Q, K, S, static_cast<float *>(ws), pr.meta, pr.g, stream) !=
+        hipSuccess)
+        return VATP_E_DEVICE;
+    return VATP_OK;
+}
+
+vatp_status vatp_decode_step(vatp_ctx *ctx, const vatp_params *p, const void *q, const void *k,
+                             const void *v, void *K, void *V, float *S, float *nrm, int32_t *pos,
+                             const int32_t *new_pos, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    if (!ctx || !q || !k || !v || !K || !V || !S || !nrm) return VATP_E_NULL;
+    if (pos && !new_pos) return VATP_E_NULL;
+    const vatp_status st = check_params(p, VATP_CALL_DECODE_STEP);
+    if (st != VATP_OK) return st;
+    if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(K, 16) || misaligned(V, 16))
+        return VATP_E_SHAPE;
+    const size_t need = vatp_workspace_bytes(ctx, p, VATP_CALL_DECODE_STEP);
+    if (!ws || ws_bytes < need || misaligned(ws, kAlign)) return VATP_E_WORKSPACE;
+    Prepared pr;
+    prepare(p, VATP_CALL_DECODE_STEP, pos ? new_pos : nullptr, &pr);
+    const size_t units = static_cast<size_t>(p->batch) * p->n_heads;
+    float *ws_logit = static_cast<float *>(ws);
+    float2 *ws_part = reinterpret_cast<float2 *>(static_cast<char *>(ws) + align_up(units * p->cap * sizeof(float)));
+    if (launch_decode(p->dtype, p->head_dim, q, k, v, K, V, S, nrm, pos, ws_logit, ws_part, ctx->counters,
+                      pr.meta, pr.g, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return VATP_E_DEVICE;
+    return VATP_OK;
+}
+
+vatp_status vatp_select_compact(vatp_ctx *ctx, const vatp_params *p, const void *K, const void *V,
+                                const float *S, const float *nrm, const int32_t *pos, void *K_out,
+                                void *V_out, float *S_out, float *nrm_out, int32_t *pos_out,
+                                int32_t *kept_idx, void *, size_t, void *hip_stream)
+{
+    if (!ctx || !K || !V || !S || !nrm || !K_out || !V_out || !S_out || !nrm_out || !kept_idx) return VATP_E_NULL;
+    if ((pos == nullptr) != (pos_out == nullptr)) return VATP_E_NULL;
+    const vatp_status st = check_params(p, VATP_CALL_SELECT_COMPACT);
+    if (st != VATP_OK) return st;
+    if (misaligned(K, 16) || misaligned(V, 16) || misaligned(K_out, 16) || misaligned(V_out, 16)) return VATP_E_SHAPE;
+    if (K_out == K || V_out == V || S_out == S || nrm_out == nrm || (pos && pos_out == pos)) return VATP_E_SHAPE;
+    Prepared pr;
+    prepare(p, VATP_CALL_SELECT_COMPACT, nullptr, &pr);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    bool evict_one = true;            // every sequence loses at most one row
+    for (int b = 0; b < p->batch; ++b)
+        if (p->len[b] > p->budget[b] + 1) evict_one = false;
+    if (!evict_one) {
+        if (launch_select(S, nrm, kept_idx, pr.meta, pr.g, stream) != hipSuccess) return VATP_E_DEVICE;
+    }
+    if (launch_gather(p->dtype, p->head_dim, evict_one, K, V, S, nrm, pos, K_out, V_out, S_out, nrm_out, pos_out,
+                      kept_idx, pr.meta, pr.g, stream) != hipSuccess)
+        return VATP_E_DEVICE;
+    return VATP_OK;
+}
+
+}  // extern "C"
+#pragma GCC visibility pop

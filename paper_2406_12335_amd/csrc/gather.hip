@@ -1,0 +1,142 @@
+// Compaction of the surviving rows (paper Fig. 2: the least important token's K/V row is
+// removed; Implementation Details appendix: a fixed budget of rows per head remains).
+//
+// HBM-bound row gather, out of place, order preserving: output row o of a unit receives
+// source row kept[o]; a row of head_dim elements moves as 16 bytes per lane, a group of
+// lanes per row, so consecutive surviving rows make one contiguous span on both sides.
+//
+// Two ways to learn kept[]:
+//   kFromIndex  the selection kernel has already written kept_idx;
+//   kEvictOne   exactly one row leaves (a decode step at steady state, n = B + 1): every
+//               workgroup finds the evicted row itself -- the candidate with the smallest
+//               importance S*nrm, the highest index among equals, which is the complement
+//               of "largest first, lower index wins" -- and writes its share of kept_idx.
+#include "vatp_device.h"
+
+namespace vatp {
+
+namespace {
+
+constexpr int kGatherRows = 64;    // output rows per workgroup
+
+template <typename T, int D, bool kEvictOne>
+__global__ __launch_bounds__(256) void gather_kernel(
+    const T *__restrict__ K, const T *__restrict__ V, const float *__restrict__ S,
+    const float *__restrict__ nrm, const int32_t *__restrict__ pos, T *__restrict__ K_out,
+    T *__restrict__ V_out, float *__restrict__ S_out, float *__restrict__ nrm_out,
+    int32_t *__restrict__ pos_out, int32_t *kept_idx, BatchMeta meta, int n_heads, int cap,
+    int cap_out, int n_sink, int recent)
+{
+    constexpr int kE = Elt<T>::kPer16B;
+    constexpr int kLanesPerRow = D / kE;
+    constexpr int kRowsPerPass = 256 / kLanesPerRow;
+
+    __shared__ unsigned long long s_min[4];
+    __shared__ int s_src[kGatherRows];
+
+    const int b = blockIdx.z, h = blockIdx.y;
+    const int n = meta.len[b], B = meta.aux[b];
+    const int n_keep = n < B ? n : B;
+    const int o0 = blockIdx.x * kGatherRows;
+    if (o0 >= n_keep) return;
+    const size_t unit = static_cast<size_t>(b) * n_heads + h;
+    const float *Su = S + unit * cap;
+    const float *Nu = nrm + unit * cap;
+    int32_t *ku = kept_idx + unit * cap_out;
+    const int tid = threadIdx.x;
+
+    if constexpr (kEvictOne) {
+        int evicted = n;                                   // n <= B: nothing leaves
+        if (n > B) {
+            const int lo = n_sink, hi = n - recent;
+            // minimise (importance bits, ~row): smallest importance, highest row among equals
+            unsigned long long best = ~0ull;
+            for (int r = lo + tid; r < hi; r += 256) {
+                const unsigned key = __float_as_uint(__fmul_rn(Su[r], Nu[r]));
+                const unsigned long long c = (static_cast<unsigned long long>(key) << 32) |
+                                             static_cast<unsigned>(~static_cast<unsigned>(r));
+                best = c < best ? c : best;
+            }
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) {
+                const unsigned long long o = __shfl_xor(best, off);
+                best = o < best ? o : best;
+            }
+            if ((tid & 63) == 0) s_min[tid >> 6] = best;
+            __syncthreads();
+            best = s_min[0];
+#pragma unroll
+            for (int w = 1; w < 4; ++w) best = s_min[w] < best ? s_min[w] : best;
+            evicted = static_cast<int>(~static_cast<unsigned>(best & 0xffffffffull));
+        }
+        if (tid < kGatherRows) {
+            const int o = o0 + tid;
+            const int src = o + (o >= evicted ? 1 : 0);
+            s_src[tid] = src;
+            if (o < n_keep) ku[o] = src;
+        }
+    } else {
+        if (tid < kGatherRows) {
+            const int o = o0 + tid;
+            s_src[tid] = (o < n_keep) ? ku[o] : 0;
+        }
+    }
+    __syncthreads();
+
+    if (tid < kGatherRows) {
+        const int o = o0 + tid;
+        if (o < n_keep) {
+            const int src = s_src[tid];
+            S_out[unit * cap_out + o] = Su[src];
+            nrm_out[unit * cap_out + o] = Nu[src];
+            if (pos_out) pos_out[unit * cap_out + o] = pos[unit * cap + src];
+        }
+    }
+
+    const uint4 *Ku = reinterpret_cast<const uint4 *>(K + unit * cap * D);
+    const uint4 *Vu = reinterpret_cast<const uint4 *>(V + unit * cap * D);
+    uint4 *Ko = reinterpret_cast<uint4 *>(K_out + unit * cap_out * D);
+    uint4 *Vo = reinterpret_cast<uint4 *>(V_out + unit * cap_out * D);
+    const int sub = tid % kLanesPerRow;
+    const int rloc = tid / kLanesPerRow;
+#pragma unroll
+    for (int pass = 0; pass < kGatherRows / kRowsPerPass; ++pass) {
+        const int ol = pass * kRowsPerPass + rloc;
+        const int o = o0 + ol;
+        if (o < n_keep) {
+            const size_t src = static_cast<size_t>(s_src[ol]) * kLanesPerRow + sub;
+            const size_t dst = static_cast<size_t>(o) * kLanesPerRow + sub;
+            const uint4 kr = Ku[src];
+            const uint4 vr = Vu[src];
+            Ko[dst] = kr;
+            Vo[dst] = vr;
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_gather(int dtype, int head_dim, bool evict_one,
+                         const void *K, const void *V, const float *S, const float *nrm,
+                         const int32_t *pos, void *K_out, void *V_out, float *S_out,
+                         float *nrm_out, int32_t *pos_out, int32_t *kept_idx,
+                         const BatchMeta &meta, const Geometry &g, hipStream_t st)
+{
+    if (g.max_len <= 0) return hipSuccess;       // max_len: largest surviving row count
+    dim3 grid((g.max_len + kGatherRows - 1) / kGatherRows, g.n_heads, g.batch), block(256);
+#define VATP_GA(T, D, E)                                                                         \
+    hipLaunchKernelGGL((gather_kernel<T, D, E>), grid, block, 0, st, static_cast<const T *>(K),   \
+                       static_cast<const T *>(V), S, nrm, pos, static_cast<T *>(K_out),          \
+                       static_cast<T *>(V_out), S_out, nrm_out, pos_out, kept_idx, meta,         \
+                       g.n_heads, g.cap, g.cap_out, g.n_sink, g.recent)
+#define VATP_GA2(T, D) do { if (evict_one) VATP_GA(T, D, true); else VATP_GA(T, D, false); } while (0)
+    if (dtype == VATP_F32 && head_dim == 64) VATP_GA2(float, 64);
+    else if (dtype == VATP_F32) VATP_GA2(float, 128);
+    else if (head_dim == 64) VATP_GA2(bf16_t, 64);
+    else VATP_GA2(bf16_t, 128);
+#undef VATP_GA2
+#undef VATP_GA
+    return hipGetLastError();
+}
+
+}  // namespace vatp

@@ -1,0 +1,173 @@
+"""Harness that walks the HIP path and the CPU oracle through the same trajectory.
+
+Comparison rules
+  scores        |gpu - oracle| <= rtol * |oracle| + 1e-12, rtol = 1e-5 (fp32) / 1e-3 (bf16)
+  kept sets     identical, except that a difference is admitted when it lies inside the
+                oracle's own near-tie band: every candidate the GPU kept has oracle
+                importance >= tau (1 - rtol) and every candidate it dropped has
+                <= tau (1 + rtol), tau being the oracle's weakest importance-selected
+                candidate.  After an admitted difference the oracle state is re-aligned to
+                the GPU's kept set (and the event counted), since both continue from
+                different caches otherwise.
+  compaction    rows, scores, norms and positions of the survivors equal their source rows
+                bit for bit (checked on the GPU's own buffers).
+"""
+from __future__ import annotations
+
+import dataclasses
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+from oracle import vatp_oracle as orc
+from paper_2406_12335_amd.runner import PrunedKVCache
+
+ATOL = 1e-12
+
+
+def rtol_for(dtype: torch.dtype) -> float:
+    return 1e-5 if dtype == torch.float32 else 1e-3
+
+
+def assert_scores_close(got, want, rtol, what=""):
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    err = np.abs(got - want)
+    bound = rtol * np.abs(want) + ATOL
+    if not np.all(err <= bound):
+        i = int(np.argmax(err / bound))
+        raise AssertionError("%s: %d of %d beyond tolerance; worst at %d: got %.9g want %.9g (rel %.3g)" % (
+            what, int(np.sum(err > bound)), err.size, i, got[i], want[i], err[i] / max(abs(want[i]), 1e-300)))
+    return float(np.max(err / np.maximum(np.abs(want), 1e-300))) if err.size else 0.0
+
+
+def check_kept_set(kept_gpu: np.ndarray, I_oracle: np.ndarray, n: int, B: int, F: int, R: int,
+                   rtol: float) -> Tuple[bool, np.ndarray]:
+    """Returns (identical, oracle_kept). Raises if the GPU set is outside the near-tie band."""
+    kept_or = orc.select(I_oracle, B, F, R)
+    assert len(kept_gpu) == len(kept_or) == min(n, B), "kept count differs from the budget"
+    if np.array_equal(kept_gpu, kept_or):
+        return True, kept_or
+    assert np.all(np.diff(kept_gpu) > 0), "kept indices not strictly ascending"
+    gset = set(kept_gpu.tolist())
+    assert set(range(F)) <= gset and set(range(n - R, n)) <= gset, "protected rows missing"
+    tau = orc.threshold_and_slack(I_oracle, n, B, F, R)
+    assert tau is not None
+    cand = np.arange(F, n - R)
+    in_gpu = np.isin(cand, kept_gpu)
+    Ic = I_oracle[cand]
+    bad_kept = cand[in_gpu & (Ic < tau * (1 - rtol))]
+    bad_drop = cand[~in_gpu & (Ic > tau * (1 + rtol))]
+    if len(bad_kept) or len(bad_drop):
+        raise AssertionError("kept set differs outside the near-tie band: wrongly kept %s, wrongly dropped %s "
+                             "(tau=%.9g)" % (bad_kept[:8].tolist(), bad_drop[:8].tolist(), tau))
+    return False, kept_or
+
+
+@dataclasses.dataclass
+class TrajectoryReport:
+    units_checked: int = 0
+    prune_events: int = 0
+    admitted_near_ties: int = 0
+    max_rel_err_prefill: float = 0.0
+    max_rel_err_decode: float = 0.0
+
+
+def _unit_rows(t: torch.Tensor, b: int, h: int, n: int) -> np.ndarray:
+    return t[b, h, :n].detach().to(torch.float64).cpu().numpy()
+
+
+def _vec(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+def run_trajectory(inp, device, units: Optional[Sequence[Tuple[int, int]]] = None, steps: Optional[int] = None,
+                   n_sink: Optional[int] = None, check_every: int = 1, cap_cache: Optional[int] = None,
+                   full_prefill_check: bool = True) -> TrajectoryReport:
+    """Prompt pass -> prune -> decode/prune steps on the GPU, mirrored by OracleHead on the chosen units."""
+    cfg = inp.cfg
+    b, H, d = cfg.batch, cfg.n_heads, cfg.head_dim
+    F = cfg.n_sink_keep if n_sink is None else n_sink
+    R = cfg.recent
+    T = cfg.decode_steps if steps is None else steps
+    rtol = rtol_for(cfg.torch_dtype())
+    units = [(bb, hh) for bb in range(b) for hh in range(H)] if units is None else list(units)
+    rep = TrajectoryReport(units_checked=len(units))
+
+    dev = lambda t: t.to(device)
+    Q, K, V = dev(inp.Q), dev(inp.K), dev(inp.V)
+    qd, kd, vd = dev(inp.qd), dev(inp.kd), dev(inp.vd)
+    cache = PrunedKVCache(b, H, d, cfg.torch_dtype(), F, R, inp.budgets, device, cap_cache=cap_cache)
+    try:
+        cache.prefill_score(Q, K, V, inp.lens)
+        torch.cuda.synchronize()
+        heads: Dict[Tuple[int, int], orc.OracleHead] = {}
+        # oracle prompt pass for the chosen units (OpenMP over units)
+        Lmax = max(inp.lens)
+        Qh = np.stack([_unit_rows(inp.Q, bb, hh, Lmax) for bb, hh in units])
+        Kh = np.stack([_unit_rows(inp.K, bb, hh, Lmax) for bb, hh in units])
+        S_or = orc.prefill_scores_units(Qh, Kh, [inp.lens[bb] for bb, _ in units]) if full_prefill_check else None
+        for ui, (bb, hh) in enumerate(units):
+            L = inp.lens[bb]
+            o = orc.OracleHead(d)
+            o.K, o.V = Kh[ui, :L].copy(), _unit_rows(inp.V, bb, hh, L)
+            o.nrm = orc.l1norm(o.V)
+            o.pos = np.arange(L, dtype=np.int64)
+            S_gpu = _unit_rows(cache.S_prompt, bb, hh, L)
+            if full_prefill_check:
+                o.S = S_or[ui, :L].copy()
+                e = assert_scores_close(S_gpu, o.S, rtol, "prefill S unit (%d,%d)" % (bb, hh))
+                rep.max_rel_err_prefill = max(rep.max_rel_err_prefill, e)
+            else:
+                o.S = S_gpu.copy()        # trajectory continues from the GPU's prompt scores
+            assert_scores_close(_unit_rows(cache.nrm_prompt, bb, hh, L), o.nrm, rtol, "nrm unit (%d,%d)" % (bb, hh))
+            heads[(bb, hh)] = o
+
+        def check_prune(src_K, src_V, src_S, src_nrm, src_pos, n_before: List[int]):
+            torch.cuda.synchronize()
+            c = cache.cur
+            for (bb, hh), o in heads.items():
+                n, Bq = n_before[bb], inp.budgets[bb]
+                nk = min(n, Bq)
+                kept_gpu = cache.kept_idx[bb, hh, :nk].cpu().numpy()
+                same, _ = check_kept_set(kept_gpu, o.importance(), n, Bq, F, R, rtol)
+                rep.prune_events += 1
+                rep.admitted_near_ties += 0 if same else 1
+                o.prune(Bq, F, R, forced=kept_gpu)
+                idx = torch.from_numpy(kept_gpu.astype(np.int64)).to(device)
+                assert torch.equal(cache.K[c][bb, hh, :nk], src_K[bb, hh].index_select(0, idx)), "K rows differ"
+                assert torch.equal(cache.V[c][bb, hh, :nk], src_V[bb, hh].index_select(0, idx)), "V rows differ"
+                assert torch.equal(cache.S[c][bb, hh, :nk], src_S[bb, hh].index_select(0, idx)), "S entries differ"
+                assert torch.equal(cache.nrm[c][bb, hh, :nk], src_nrm[bb, hh].index_select(0, idx)), "nrm differ"
+                if src_pos is not None:
+                    assert torch.equal(cache.pos[c][bb, hh, :nk], src_pos[bb, hh].index_select(0, idx)), "pos differ"
+                    assert np.array_equal(cache.pos[c][bb, hh, :nk].cpu().numpy(), o.pos), "positions differ from oracle"
+
+        n_before = list(inp.lens)
+        cache.prune_prompt(K, V)
+        check_prune(K, V, cache.S_prompt, cache.nrm_prompt, cache._pos_prompt, n_before)
+
+        for t in range(T):
+            c = cache.cur
+            new_pos = [L + t for L in inp.lens]
+            cache.decode_step(qd[t], kd[t], vd[t], new_pos)
+            n_before = list(cache.lens)
+            do_check = (t % check_every == 0) or t == T - 1
+            if do_check:
+                torch.cuda.synchronize()
+            for (bb, hh), o in heads.items():
+                o.append_and_score(_vec(inp.qd[t, bb, hh]), _vec(inp.kd[t, bb, hh]), _vec(inp.vd[t, bb, hh]),
+                                   new_pos[bb])
+                if do_check:
+                    n = n_before[bb]
+                    e = assert_scores_close(_unit_rows(cache.S[c], bb, hh, n), o.S, rtol,
+                                            "decode S step %d unit (%d,%d)" % (t, bb, hh))
+                    rep.max_rel_err_decode = max(rep.max_rel_err_decode, e)
+                    assert_scores_close(_unit_rows(cache.nrm[c], bb, hh, n), o.nrm, rtol, "decode nrm")
+            cache.prune()
+            check_prune(cache.K[c], cache.V[c], cache.S[c], cache.nrm[c], cache.pos[c], n_before)
+        return rep
+    finally:
+        torch.cuda.synchronize()
+        cache.close()

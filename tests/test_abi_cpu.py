@@ -1,0 +1,91 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+the header declares, and rejects bad arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+import paper_2406_12335_amd as vatp
+from paper_2406_12335_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "vatp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(vatp_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = vatp.load()
+    names = _declared_symbols()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def _params(**kw):
+    base = dict(batch=2, n_heads=4, head_dim=128, dtype=vatp.VATP_BF16, n_sink=2, recent=8, cap=64,
+                len=[64, 10], budget=[32, 32])
+    base.update(kw)
+    return vatp.Params(**base)
+
+
+def test_validate_accepts_good_params():
+    for call in (vatp.CALL_PREFILL_SCORE, vatp.CALL_SELECT_COMPACT):
+        assert vatp.vatp_validate(_params(), call) == binding.OK
+    assert vatp.vatp_validate(_params(len=[63, 10]), vatp.CALL_DECODE_STEP) == binding.OK
+
+
+@pytest.mark.parametrize("kw,call,want", [
+    (dict(dtype=7), 0, binding.E_DTYPE),
+    (dict(head_dim=96), 0, binding.E_SHAPE),
+    (dict(batch=0, len=[], budget=[]), 0, binding.E_SHAPE),
+    (dict(batch=65, len=[1] * 65, budget=[32] * 65), 0, binding.E_SHAPE),
+    (dict(n_heads=16384), 0, binding.E_SHAPE),
+    (dict(len=[65, 1]), 0, binding.E_SHAPE),
+    (dict(len=[-1, 1]), 0, binding.E_SHAPE),
+    (dict(len=[64, 1]), vatp.CALL_DECODE_STEP, binding.E_SHAPE),          # no room to append
+    (dict(budget=[9, 32]), vatp.CALL_SELECT_COMPACT, binding.E_BUDGET),   # B < F + R
+    (dict(cap_out=16), vatp.CALL_SELECT_COMPACT, binding.E_BUDGET),       # survivors do not fit
+    (dict(budget=None), vatp.CALL_SELECT_COMPACT, binding.E_NULL),
+    (dict(len=None), 0, binding.E_NULL),
+    (dict(scale=float("nan")), 0, binding.E_SHAPE),
+    (dict(n_sink=-1), 0, binding.E_SHAPE),
+])
+def test_validate_rejects(kw, call, want):
+    assert vatp.vatp_validate(_params(**kw), call) == want
+
+
+def test_workspace_bytes():
+    p = _params()
+    units, cap = 8, 64
+    assert vatp.vatp_workspace_bytes(None, p, vatp.CALL_PREFILL_SCORE) == units * cap * 4
+    dec = vatp.vatp_workspace_bytes(None, _params(len=[10, 10]), vatp.CALL_DECODE_STEP)
+    assert dec >= units * cap * 4 + units * 8 and dec % 256 == 0
+    assert vatp.vatp_workspace_bytes(None, p, vatp.CALL_SELECT_COMPACT) == 0
+    assert vatp.vatp_workspace_bytes(None, _params(dtype=9), vatp.CALL_PREFILL_SCORE) == 0
+
+
+def test_entry_points_reject_null_before_any_launch():
+    lib = vatp.load()
+    p = _params()
+    assert lib.vatp_prefill_score(None, p.ref(), None, None, None, None, None, None, 0, None) == binding.E_NULL
+    assert lib.vatp_decode_step(None, p.ref(), *([None] * 9), None, 0, None) == binding.E_NULL
+    assert lib.vatp_select_compact(None, p.ref(), *([None] * 11), None, 0, None) == binding.E_NULL
+    assert "NULL" in vatp.strerror(binding.E_NULL)
+    assert vatp.strerror(-99) == "unknown status"
+
+
+def test_create_without_device_is_an_error_not_a_crash():
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(vatp.VatpError) as e:
+        vatp.vatp_create(0)
+    assert e.value.status == binding.E_DEVICE
+    lib = vatp.load()
+    assert lib.vatp_create(None, 0) == binding.E_NULL
+    lib.vatp_destroy(None)

@@ -1,0 +1,228 @@
+"""GPU parity: the HIP path, called through the C ABI, against the float64 CPU oracle."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import parity
+import vatp_synth as vs
+from oracle import vatp_oracle as orc
+import paper_2406_12335_amd as vatp
+from paper_2406_12335_amd.runner import PrunedKVCache
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+# ------------------------------------------------------------------ whole trajectories
+
+def test_tiny_config_every_unit_every_step(gpu_device):
+    cfg = vs.CONFIGS["tiny"]
+    _say("tiny fp32 full trajectory")
+    rep = parity.run_trajectory(vs.make_inputs(cfg, seed=0), gpu_device)
+    assert rep.units_checked == 4 and rep.prune_events == 4 * 33
+    _say("tiny report %r" % rep)
+
+
+@pytest.mark.parametrize("dtype,d,L,T,pct,R,F,seed", [
+    ("bf16", 128, 700, 24, 50, 64, 2, 1),      # several tiles and a ragged tail
+    ("bf16", 64, 333, 16, 30, 16, 2, 2),
+    ("fp32", 128, 257, 12, 50, 32, 20, 3),     # the paper's F = 20
+    ("fp32", 64, 130, 12, 20, 8, 0, 4),        # no forced prefix
+    ("bf16", 128, 300, 10, 50, 148, 2, 5),     # B = F + R: sinks + window only
+])
+def test_reduced_size_trajectories(gpu_device, dtype, d, L, T, pct, R, F, seed):
+    cfg = vs.scaled(vs.CONFIGS["llama7b_layer"], n_heads=3, head_dim=d, prompt_len=L, dtype=dtype,
+                    budget_pct=pct, recent=R, decode_steps=T)
+    _say("reduced %s d=%d L=%d T=%d pct=%d R=%d F=%d" % (dtype, d, L, T, pct, R, F))
+    rep = parity.run_trajectory(vs.make_inputs(cfg, seed=seed), gpu_device, n_sink=F)
+    _say("report %r" % rep)
+
+
+def test_ragged_batch_small(gpu_device):
+    cfg = vs.scaled(vs.CONFIGS["ragged16"], batch=5, n_heads=2, ragged=(1, 300), decode_steps=6, recent=4,
+                    n_sinks=1)
+    inp = vs.make_inputs(cfg, seed=7)
+    # budgets below F + R are not allowed: lift tiny ones
+    inp.budgets = [max(b, cfg.n_sinks + cfg.recent) for b in inp.budgets]
+    _say("ragged small lens=%s budgets=%s" % (inp.lens, inp.budgets))
+    rep = parity.run_trajectory(inp, gpu_device)
+    _say("report %r" % rep)
+
+
+def test_llama7b_layer_full_size(gpu_device):
+    cfg = vs.CONFIGS["llama7b_layer"]
+    _say("llama7b_layer full size: prompt pass on all 32 heads, decode on 8 heads")
+    inp = vs.make_inputs(cfg, seed=0)
+    S = _prompt_scores_gpu(inp, gpu_device)
+    lens = inp.lens
+    Qh = inp.Q[0].double().numpy()
+    Kh = inp.K[0].double().numpy()
+    S_or = orc.prefill_scores_units(Qh, Kh, [lens[0]] * cfg.n_heads)
+    for h in range(cfg.n_heads):
+        parity.assert_scores_close(S[0, h].cpu().numpy(), S_or[h], 1e-3, "prompt S head %d" % h)
+    units = [(0, h) for h in (0, 5, 11, 13, 17, 22, 29, 31)]
+    rep = parity.run_trajectory(inp, gpu_device, units=units, full_prefill_check=False)
+    _say("report %r" % rep)
+
+
+def test_llama7b_stack_one_layer_full_size(gpu_device):
+    cfg = vs.CONFIGS["llama7b_stack"]
+    _say("llama7b_stack layer 3, batch 8 x 32 heads, sampled units, 256 steps")
+    inp = vs.make_inputs(cfg, seed=0, layer=3, device=gpu_device)
+    units = [(0, 0), (3, 17), (7, 31), (5, 8)]
+    rep = parity.run_trajectory(inp, gpu_device, units=units)
+    _say("report %r" % rep)
+
+
+def test_ragged16_full_size(gpu_device):
+    cfg = vs.CONFIGS["ragged16"]
+    inp = vs.make_inputs(cfg, seed=0, device=gpu_device)
+    order = np.argsort(inp.lens)
+    units = [(int(order[0]), 3), (int(order[-1]), 30), (int(order[8]), 12)]
+    _say("ragged16 full size lens=%s units=%s" % (inp.lens, units))
+    rep = parity.run_trajectory(inp, gpu_device, units=units)
+    _say("report %r" % rep)
+
+
+def test_long32k_full_size(gpu_device):
+    cfg = vs.CONFIGS["long32k"]
+    _say("long32k full size: invariants on all heads, tail of S on 3 heads, decode on 2 heads")
+    inp = vs.make_inputs(cfg, seed=0, device=gpu_device)
+    S = _prompt_scores_gpu(inp, gpu_device)
+    L = cfg.prompt_len
+    tot = S.double().sum(-1).cpu().numpy()
+    np.testing.assert_allclose(tot, L, rtol=1e-5)           # every softmax row sums to one
+    assert torch.all(S[..., 0] >= 1.0 - 1e-6) and torch.all(S[..., L - 1] <= 1.0 + 1e-6) and torch.all(S > 0)
+    j0 = L - 384
+    for h in (0, 14, 31):
+        want = orc.prefill_scores_tail(inp.Q[0, h].double().cpu().numpy(), inp.K[0, h].double().cpu().numpy(), j0)
+        parity.assert_scores_close(S[0, h, j0:].cpu().numpy(), want, 1e-3, "tail S head %d" % h)
+    rep = parity.run_trajectory(inp, gpu_device, units=[(0, 2), (0, 27)], full_prefill_check=False)
+    _say("report %r" % rep)
+
+
+def _prompt_scores_gpu(inp, device):
+    cfg = inp.cfg
+    cache = PrunedKVCache(cfg.batch, cfg.n_heads, cfg.head_dim, cfg.torch_dtype(), cfg.n_sink_keep, cfg.recent,
+                          inp.budgets, device)
+    try:
+        cache.prefill_score(inp.Q.to(device), inp.K.to(device), inp.V.to(device), inp.lens)
+        torch.cuda.synchronize()
+        return cache.S_prompt.clone()
+    finally:
+        cache.close()
+
+
+# ------------------------------------------------------------------ selection in isolation
+
+@pytest.mark.parametrize("n,B,F,R,seed", [
+    (4096, 2048, 2, 64, 0), (2049, 2048, 2, 64, 1), (1000, 999, 0, 0, 2), (1500, 300, 20, 100, 3),
+    (70, 70, 2, 4, 4), (50, 80, 2, 4, 5), (300, 66, 2, 64, 6), (5000, 1, 0, 0, 7), (1025, 1024, 0, 1024, 8),
+    (33000, 3276, 4, 128, 9),
+])
+def test_select_compact_bit_exact_with_planted_ties(gpu_device, n, B, F, R, seed):
+    """Same binary32 S and nrm on both sides, decision in binary32 on both sides: identical sets."""
+    _say("select n=%d B=%d F=%d R=%d" % (n, B, F, R))
+    H, d = 3, 64
+    g = torch.Generator().manual_seed(seed)
+    S = torch.rand(1, H, n, generator=g) * 3
+    nrm = torch.rand(1, H, n, generator=g) * 50
+    # exact ties: quantise some products, zero some norms
+    S[0, 1] = torch.round(S[0, 1] * 4) / 4
+    nrm[0, 1] = torch.round(nrm[0, 1])
+    nrm[0, 2, torch.randint(0, n, (max(n // 10, 1),), generator=g)] = 0.0
+    K = torch.randn(1, H, n, d, generator=g)
+    V = torch.randn(1, H, n, d, generator=g)
+    pos = torch.arange(n, dtype=torch.int32).expand(1, H, n).contiguous()
+    cap_out = min(n, B) + 3
+    ctx = vatp.vatp_create(0)
+    try:
+        dev = gpu_device
+        out = dict(K=torch.zeros(1, H, cap_out, d), V=torch.zeros(1, H, cap_out, d), S=torch.zeros(1, H, cap_out),
+                   nrm=torch.zeros(1, H, cap_out), pos=torch.zeros(1, H, cap_out, dtype=torch.int32),
+                   kept=torch.full((1, H, cap_out), -1, dtype=torch.int32))
+        out = {k: v.to(dev) for k, v in out.items()}
+        p = vatp.Params(1, H, d, torch.float32, F, R, n, [n], [B], cap_out=cap_out)
+        vatp.vatp_select_compact(ctx, p, K.to(dev), V.to(dev), S.to(dev), nrm.to(dev), pos.to(dev), out["K"],
+                                 out["V"], out["S"], out["nrm"], out["pos"], out["kept"])
+        torch.cuda.synchronize()
+    finally:
+        vatp.vatp_destroy(ctx)
+    nk = min(n, B)
+    for h in range(H):
+        I = orc.importance(S[0, h].double().numpy(), nrm[0, h].double().numpy(), decide_f32=True)
+        want = orc.select(I, B, F, R)
+        got = out["kept"][0, h, :nk].cpu().numpy()
+        np.testing.assert_array_equal(got, want)
+        assert torch.all(out["kept"][0, h, nk:] == -1)                      # nothing written past the survivors
+        idx = torch.from_numpy(want.astype(np.int64))
+        assert torch.equal(out["K"][0, h, :nk].cpu(), K[0, h, idx]) and torch.equal(out["V"][0, h, :nk].cpu(), V[0, h, idx])
+        assert torch.equal(out["S"][0, h, :nk].cpu(), S[0, h, idx]) and torch.equal(out["nrm"][0, h, :nk].cpu(), nrm[0, h, idx])
+        assert torch.equal(out["pos"][0, h, :nk].cpu(), pos[0, h, idx])
+
+
+# ------------------------------------------------------------------ properties
+
+def test_uniform_value_norms_reduce_to_attention_only_ranking(gpu_device):
+    cfg = vs.scaled(vs.CONFIGS["llama7b_layer"], n_heads=2, prompt_len=600, decode_steps=0)
+    inp = vs.make_inputs(cfg, seed=11)
+    g = torch.Generator().manual_seed(5)
+    inp.V = (torch.randint(0, 2, inp.V.shape, generator=g).float() * 2 - 1).to(torch.bfloat16)   # |v|_1 = d exactly
+    _say("uniform norms")
+    cache = PrunedKVCache(1, 2, 128, torch.bfloat16, 2, 64, inp.budgets, gpu_device)
+    try:
+        dev = gpu_device
+        cache.prefill_score(inp.Q.to(dev), inp.K.to(dev), inp.V.to(dev), inp.lens)
+        cache.prune_prompt(inp.K.to(dev), inp.V.to(dev))
+        torch.cuda.synchronize()
+        assert torch.all(cache.nrm_prompt == 128.0)
+        for h in range(2):
+            S32 = cache.S_prompt[0, h].cpu().double().numpy()
+            want = orc.select(S32, inp.budgets[0], 2, 64)       # attention-only ranking of the same scores
+            np.testing.assert_array_equal(cache.kept_idx[0, h, :inp.budgets[0]].cpu().numpy(), want)
+    finally:
+        cache.close()
+
+
+def test_prompt_pass_is_deterministic_and_leaves_padding_alone(gpu_device):
+    cfg = vs.scaled(vs.CONFIGS["ragged16"], batch=3, n_heads=2, ragged=(100, 400), decode_steps=0)
+    inp = vs.make_inputs(cfg, seed=3)
+    _say("determinism lens=%s" % inp.lens)
+    runs = []
+    for _ in range(2):
+        cache = PrunedKVCache(3, 2, 128, torch.bfloat16, 2, 64, [max(b, 66) for b in inp.budgets], gpu_device)
+        try:
+            dev = gpu_device
+            cache.S_prompt = torch.full((3, 2, inp.cap), -7.0, device=dev)
+            cache.nrm_prompt = torch.full((3, 2, inp.cap), -7.0, device=dev)
+            cache.prefill_score(inp.Q.to(dev), inp.K.to(dev), inp.V.to(dev), inp.lens)
+            torch.cuda.synchronize()
+            runs.append((cache.S_prompt.cpu(), cache.nrm_prompt.cpu()))
+        finally:
+            cache.close()
+    assert torch.equal(runs[0][0], runs[1][0]) and torch.equal(runs[0][1], runs[1][1])
+    for b, L in enumerate(inp.lens):
+        assert torch.all(runs[0][0][b, :, L:] == -7.0) and torch.all(runs[0][1][b, :, L:] == -7.0)
+        assert torch.all(runs[0][0][b, :, :L] > 0)
+
+
+def test_entry_points_report_errors_on_device(gpu_device):
+    ctx = vatp.vatp_create(0)
+    try:
+        t = torch.zeros(1, 1, 8, 64, device=gpu_device)
+        s = torch.zeros(1, 1, 8, device=gpu_device)
+        p = vatp.Params(1, 1, 64, torch.float32, 0, 0, 8, [8], [4])
+        with pytest.raises(vatp.VatpError) as e:
+            vatp.vatp_prefill_score(ctx, p, t, t, t, s, s, None)
+        assert e.value.status == -5                                          # workspace missing
+        with pytest.raises(vatp.VatpError) as e:
+            vatp.vatp_select_compact(ctx, p, t, t, s, s, None, t, t, s, s, None, s.int())
+        assert e.value.status == -2                                          # output aliases input
+    finally:
+        vatp.vatp_destroy(ctx)

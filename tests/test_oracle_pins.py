@@ -263,3 +263,13 @@ def test_splitting_units_gives_identical_results():
         lens.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), d, 0.5, S.ctypes.data_as(f64p))
     for u in range(units):
         np.testing.assert_array_equal(S[u, :lens[u]], orc.prefill_scores(Q[u, :lens[u]], K[u, :lens[u]], 0.5))
+
+
+def test_tail_scores_equal_the_tail_of_the_full_pass():
+    rng = np.random.default_rng(34)
+    L, d = 90, 8
+    Q, K = _rand(rng, L, d), _rand(rng, L, d)
+    full = orc.prefill_scores(Q, K)
+    np.testing.assert_allclose(orc.prefill_scores_tail(Q, K, 60), full[60:], rtol=1e-13)
+    np.testing.assert_array_equal(orc.prefill_scores_tail(Q, K, 0), full)
+    np.testing.assert_array_equal(orc.prefill_scores_units(Q[None], K[None], [L])[0], full)
