@@ -10,8 +10,7 @@
  * Conventions shared by every call
  *   - Plain C types only.  Pointers named in UPPER CASE or documented "device" are device
  *     pointers owned by the caller; `len`, `budget`, `new_pos` are HOST arrays.  The
- *     library never allocates or frees device memory in a call (vatp_create allocates one
- *     small device block of counters that vatp_destroy frees).
+ *     library never allocates or frees device memory.
  *   - Layout is head-major: a cache tensor is [batch, n_heads, cap, head_dim] contiguous,
  *     per-row scalars (S, nrm, pos) are [batch, n_heads, cap].  Heads keep different
  *     tokens after pruning, so every (batch, head) unit owns `cap` rows of its own.
@@ -68,7 +67,8 @@ typedef struct {
                             /*   only vatp_select_compact reads it; may be NULL elsewhere  */
 } vatp_params;
 
-/* Creates a context on HIP device `device` (allocates a 64 KiB zeroed counter block). */
+/* Creates a context for HIP device `device` (host memory only).  The device must be the
+ * current HIP device whenever a call that takes the context is made. */
 vatp_status vatp_create(vatp_ctx **ctx, int device);
 void        vatp_destroy(vatp_ctx *ctx);
 const char *vatp_strerror(vatp_status st);

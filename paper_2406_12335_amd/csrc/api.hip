@@ -9,7 +9,6 @@ using namespace vatp;
 
 struct vatp_ctx {
     int device;
-    unsigned *counters;      // VATP_MAX_UNITS arrival counters, zero between calls
 };
 
 namespace {
@@ -110,22 +109,9 @@ vatp_status vatp_create(vatp_ctx **ctx, int device)
         (void)hipGetLastError();
         return VATP_E_DEVICE;
     }
-    int prev = 0;
-    if (hipGetDevice(&prev) != hipSuccess) return VATP_E_DEVICE;
-    if (hipSetDevice(device) != hipSuccess) return VATP_E_DEVICE;
-    unsigned *counters = nullptr;
-    hipError_t e = hipMalloc(reinterpret_cast<void **>(&counters), VATP_MAX_UNITS * sizeof(unsigned));
-    if (e == hipSuccess) e = hipMemset(counters, 0, VATP_MAX_UNITS * sizeof(unsigned));
-    (void)hipSetDevice(prev);
-    if (e != hipSuccess) {
-        if (counters) (void)hipFree(counters);
-        (void)hipGetLastError();
-        return VATP_E_DEVICE;
-    }
     vatp_ctx *c = new (std::nothrow) vatp_ctx;
-    if (!c) { (void)hipFree(counters); return VATP_E_DEVICE; }
+    if (!c) return VATP_E_DEVICE;
     c->device = device;
-    c->counters = counters;
     *ctx = c;
     return VATP_OK;
 }
@@ -133,7 +119,6 @@ vatp_status vatp_create(vatp_ctx **ctx, int device)
 void vatp_destroy(vatp_ctx *ctx)
 {
     if (!ctx) return;
-    if (ctx->counters) (void)hipFree(ctx->counters);
     delete ctx;
 }
 
@@ -146,10 +131,8 @@ size_t vatp_workspace_bytes(const vatp_ctx *, const vatp_params *p, int which_ca
     switch (which_call) {
     case VATP_CALL_PREFILL_SCORE:           // lse2[units, cap]
         return align_up(units * p->cap * sizeof(float));
-    case VATP_CALL_DECODE_STEP: {           // logits[units, cap] + chunk statistics
-        const size_t chunks = (static_cast<size_t>(p->cap) + kDecodeChunk - 1) / kDecodeChunk;
-        return align_up(units * p->cap * sizeof(float)) + align_up(units * chunks * sizeof(float2));
-    }
+    case VATP_CALL_DECODE_STEP:             // logits[units, cap]
+        return align_up(units * p->cap * sizeof(float));
     default:
         return 0;
     }
@@ -169,9 +152,12 @@ vatp_status vatp_prefill_score(vatp_ctx *ctx, const vatp_params *p, const void *
     prepare(p, VATP_CALL_PREFILL_SCORE, nullptr, &pr);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (launch_l1norm(p->dtype, p->head_dim, V, nrm, pr.meta, pr.g, stream) != hipSuccess) return VATP_E_DEVICE;
-    if (launch_prefill_generic(p->dtype, p->head_dim, Q, K, S, static_cast<float *>(ws), pr.meta, pr.g, stream) !=
-        hipSuccess)
-        return VATP_E_DEVICE;
+    // bf16 with head_dim 128 runs on the matrix cores; everything else on the fp32 FMA kernels
+    const hipError_t e = (p->dtype == VATP_BF16 && p->head_dim == 128)
+                             ? launch_prefill_mfma(Q, K, S, static_cast<float *>(ws), pr.meta, pr.g, stream)
+                             : launch_prefill_generic(p->dtype, p->head_dim, Q, K, S, static_cast<float *>(ws),
+                                                      pr.meta, pr.g, stream);
+    if (e != hipSuccess) return VATP_E_DEVICE;
     return VATP_OK;
 }
 
@@ -189,11 +175,8 @@ vatp_status vatp_decode_step(vatp_ctx *ctx, const vatp_params *p, const void *q,
     if (!ws || ws_bytes < need || misaligned(ws, kAlign)) return VATP_E_WORKSPACE;
     Prepared pr;
     prepare(p, VATP_CALL_DECODE_STEP, pos ? new_pos : nullptr, &pr);
-    const size_t units = static_cast<size_t>(p->batch) * p->n_heads;
-    float *ws_logit = static_cast<float *>(ws);
-    float2 *ws_part = reinterpret_cast<float2 *>(static_cast<char *>(ws) + align_up(units * p->cap * sizeof(float)));
-    if (launch_decode(p->dtype, p->head_dim, q, k, v, K, V, S, nrm, pos, ws_logit, ws_part, ctx->counters,
-                      pr.meta, pr.g, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    if (launch_decode(p->dtype, p->head_dim, q, k, v, K, V, S, nrm, pos, static_cast<float *>(ws), pr.meta, pr.g,
+                      static_cast<hipStream_t>(hip_stream)) != hipSuccess)
         return VATP_E_DEVICE;
     return VATP_OK;
 }

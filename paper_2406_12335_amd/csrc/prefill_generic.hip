@@ -201,7 +201,7 @@ hipError_t launch_prefill_generic(int dtype, int head_dim, const void *Q, const 
     if (dtype == VATP_F32 && head_dim == 64) VATP_PF(float, 64);
     else if (dtype == VATP_F32) VATP_PF(float, 128);
     else if (head_dim == 64) VATP_PF(bf16_t, 64);
-    else VATP_PF(bf16_t, 128);
+    else return hipErrorInvalidValue;      // bf16 with head_dim 128 belongs to the MFMA kernels
 #undef VATP_PF
     return hipGetLastError();
 }

@@ -55,6 +55,35 @@ def test_ragged_batch_small(gpu_device):
     _say("report %r" % rep)
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("fp32", 64), ("fp32", 128)])
+def test_prompt_scores_at_tile_edges(gpu_device, dtype, d):
+    """Prompt lengths just below, at and above every tile size the kernels use."""
+    lens = [1, 2, 31, 33, 63, 64, 65, 127, 129, 255, 256, 257, 511, 513, 770]
+    cfg = vs.scaled(vs.CONFIGS["llama7b_layer"], batch=len(lens), n_heads=2, head_dim=d, dtype=dtype,
+                    decode_steps=0, n_sinks=1)
+    inp = vs.make_inputs(vs.scaled(cfg, prompt_len=max(lens)), seed=21)
+    # shorten the sequences by hand: rows past a sequence's length hold junk on purpose
+    inp.lens = lens
+    for t in (inp.Q, inp.K, inp.V):
+        for b, L in enumerate(lens):
+            t[b, :, L:] = 77.0
+    _say("tile edges %s d=%d" % (dtype, d))
+    dev = gpu_device
+    cache = PrunedKVCache(cfg.batch, 2, d, cfg.torch_dtype(), 0, 0, [max(lens)] * len(lens), dev)
+    try:
+        cache.prefill_score(inp.Q.to(dev), inp.K.to(dev), inp.V.to(dev), lens)
+        torch.cuda.synchronize()
+        S, nrm = cache.S_prompt.cpu(), cache.nrm_prompt.cpu()
+    finally:
+        cache.close()
+    rtol = parity.rtol_for(cfg.torch_dtype())
+    for b, L in enumerate(lens):
+        for h in range(2):
+            want = orc.prefill_scores(inp.Q[b, h, :L].double().numpy(), inp.K[b, h, :L].double().numpy())
+            parity.assert_scores_close(S[b, h, :L].numpy(), want, rtol, "S len %d head %d" % (L, h))
+            parity.assert_scores_close(nrm[b, h, :L].numpy(), orc.l1norm(inp.V[b, h, :L].double().numpy()), rtol, "nrm")
+
+
 def test_llama7b_layer_full_size(gpu_device):
     cfg = vs.CONFIGS["llama7b_layer"]
     _say("llama7b_layer full size: prompt pass on all 32 heads, decode on 8 heads")
