@@ -36,6 +36,7 @@ extern "C" {
 
 #define VATP_MAX_BATCH 64          /* sequences per call                                  */
 #define VATP_MAX_UNITS 16384       /* batch * n_heads per call                            */
+#define VATP_MAX_CAP   4194304     /* rows per (batch, head) unit: cap and cap_out        */
 
 typedef struct vatp_ctx vatp_ctx;  /* opaque */
 
@@ -59,7 +60,8 @@ typedef struct {
     int32_t dtype;          /* VATP_F32 or VATP_BF16                                       */
     int32_t n_sink;         /* F: rows [0,F) are always kept (Attention Sink Tokens par.)  */
     int32_t recent;         /* R: the last R rows are always kept (local window, App. A)   */
-    int32_t cap;            /* rows allocated per (batch, head) unit in the input buffers  */
+    int32_t cap;            /* rows allocated per (batch, head) unit in the input buffers, */
+                            /*   1 .. VATP_MAX_CAP                                         */
     int32_t cap_out;        /* same for the *_out buffers of vatp_select_compact; 0 = cap  */
     float   scale;          /* logit scale c; 0 selects 1/sqrt(head_dim)                   */
     const int32_t *len;     /* HOST [batch]: valid rows per sequence, same for all heads   */

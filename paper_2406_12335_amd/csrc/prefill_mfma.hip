@@ -9,26 +9,35 @@
 //
 // Skeleton.  A workgroup of 4 wavefronts owns 256 "stationary" rows (64 per wavefront), kept
 // in registers as the B operand of v_mfma_f32_32x32x16_bf16 (columns of the logit tile).  The
-// other matrix streams through LDS in stages of 64 rows (double buffered, one barrier per
-// stage) and is the A operand (rows of the logit tile).  In the 32x32 accumulator a lane then
-// holds ONE stationary column and 16 streamed rows, so the reduction each pass needs -- over
-// keys for a query's row statistics, over queries for a key's column sum -- runs inside the
-// lane; the two lane halves are merged once at the end with a single shuffle, and wavefronts
-// own disjoint columns, so nothing is reduced through memory and there are no atomics.
+// other matrix streams through LDS in stages of 64 rows and is the A operand (rows of the
+// logit tile).  In the 32x32 accumulator a lane then holds ONE stationary column and 16
+// streamed rows, so the reduction each pass needs -- over keys for a query's row statistics,
+// over queries for a key's column sum -- runs inside the lane; the two lane halves are merged
+// once at the end with a single shuffle, and wavefronts own disjoint columns, so nothing is
+// reduced through memory and there are no atomics.
+//
+// Streaming.  Stages are copied global -> LDS by the load unit itself
+// (global_load_lds_dwordx4: each lane's 16 bytes land at LDS base + 16*lane, no registers),
+// three stages ahead of the one being consumed, into a ring of four 16 KiB buffers; one
+// s_barrier per stage.  The copies are issued from inline assembly, so their completion is
+// tracked by hand: a wavefront waits until at most the copies of the younger stages are
+// outstanding (s_waitcnt vmcnt) before the barrier that publishes a stage.  LDS rows are 256
+// bytes; chunk c of row r sits at chunk c ^ (r & 15), which the copy realises on the source
+// side (the lane that fills LDS chunk p of row r fetches global chunk p ^ (r & 15)).
 //
 // The exponentials cost more vector-ALU time than the contraction costs matrix time, so the
 // two are overlapped inside every wavefront: while the 16 MFMAs of one pair of tiles (32
 // streamed rows x 64 columns) execute, the lane works through the exponentials of the
-// previous pair ("pending" accumulators).  Causal masking is applied to a finished
-// accumulator by writing -inf into the masked entries, which both epilogues turn into 0.
+// previous pair ("pending" accumulators).  Masking (causal diagonal, rows past the end) is
+// applied to a finished accumulator by writing -inf into the masked entries, which both
+// epilogues turn into 0.
 //
 // Causal work per 256-row block grows (rowstat) or shrinks (colsum) linearly with the block
 // index; a workgroup therefore takes the pair of blocks (x, n_blocks-1-x), which gives every
 // workgroup the same amount of work.
 //
 // The contraction index (head dimension) may be permuted freely as long as both operands
-// agree: lane half g takes the 16-byte chunk  s + 8g  of a row for MFMA step s.  LDS rows
-// are 256 bytes; chunk c of row r is stored at chunk  c ^ (r & 15).
+// agree: lane half g takes the 16-byte chunk  s + 8g  of a row for MFMA step s.
 #include <type_traits>
 
 #include "vatp_device.h"
@@ -39,12 +48,16 @@ namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+typedef __attribute__((address_space(3))) char lds_char;
 
 constexpr int kD = 128;            // head_dim
 constexpr int kStage = 64;         // streamed rows per LDS stage
+constexpr int kRing = 4;           // LDS stage buffers
+constexpr int kAhead = kRing - 1;  // stages in flight beyond the one being consumed
 constexpr int kWaveCols = 64;      // stationary rows per wavefront
 constexpr int kBlockCols = 256;    // stationary rows per workgroup
 constexpr int kChunksPerRow = kD * 2 / 16;   // 16-byte chunks per row = 16
+constexpr int kStageBytes = kStage * kD * 2; // 16 KiB
 
 __device__ __forceinline__ int swizzled_chunk(int row, int c) { return c ^ (row & 15); }
 
@@ -56,19 +69,26 @@ __device__ __forceinline__ constexpr int acc_row(int v) { return 8 * (v / 4) + (
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // Scheduling request for two MFMA slots: one MFMA, V0 vector-ALU instructions, one MFMA, V1
-// vector-ALU instructions, and optionally one LDS read (0x008 MFMA, 0x002 VALU, 0x100 DS read).
-template <int V0, int V1, bool kRead>
+// vector-ALU instructions (0x008 MFMA, 0x002 VALU).
+template <int V0, int V1>
 __device__ __forceinline__ void sched_two_slots()
 {
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
     __builtin_amdgcn_sched_group_barrier(0x002, V0, 0);
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
     __builtin_amdgcn_sched_group_barrier(0x002, V1, 0);
-    if constexpr (kRead) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+}
+
+// Wait until at most kPending of this wavefront's vector-memory operations are outstanding,
+// then meet the other wavefronts.  The "memory" clobber keeps LDS reads below it.
+template <int kPending>
+__device__ __forceinline__ void wait_copies_then_barrier()
+{
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(kPending) : "memory");
 }
 
 template <bool kColsum>
-struct Pending {               // a finished pair of 32x32 tiles awaiting its exponentials
+struct Pending {                 // a finished pair of 32x32 tiles awaiting its exponentials
     floatx16 acc[2];
     float lse[kColsum ? 16 : 1];
 };
@@ -79,7 +99,7 @@ struct Running {                 // per column block: rowstat (m, l) or colsum p
 };
 
 // The exponentials of a pending pair, cut into 16 pieces so that one piece can follow each
-// MFMA of the next pair.  piece < 0 runs everything that is left after piece 15.
+// MFMA of the next pair; finish() runs what is left after piece 15.
 template <bool kColsum>
 struct Epilogue {
     float ref[2], corr[2], part[2], tmax[2];
@@ -139,20 +159,47 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t *__restr
                                                            int n_heads, int cap, int n_blocks,
                                                            float scale_log2)
 {
-    __shared__ uint4 stage[2][kStage * kChunksPerRow];     // 2 x 16 KiB
-    __shared__ __attribute__((aligned(16))) float lse_stage[2][kStage];
+    __shared__ uint4 stage[kRing][kStage * kChunksPerRow];      // 4 x 16 KiB, filled by the load unit
+    __shared__ __attribute__((aligned(16))) float lse_stage[kRing][kStage];
 
     const int b = blockIdx.z, h = blockIdx.y;
     const int len = meta.len[b];
     const size_t unit = static_cast<size_t>(b) * n_heads + h;
     const uint4 *stat = reinterpret_cast<const uint4 *>((kColsum ? K : Q) + unit * cap * kD);
-    const uint4 *strm = reinterpret_cast<const uint4 *>((kColsum ? Q : K) + unit * cap * kD);
+    const bf16_t *strm = (kColsum ? Q : K) + unit * cap * kD;
     float *lse_u = lse2 + unit * cap;
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63, g = lane >> 5, n = lane & 31;
-    const int ld_row = tid >> 4, ld_c = tid & 15;      // this thread's share of a stage
+
+    const unsigned lds_stage0 = static_cast<unsigned>(reinterpret_cast<size_t>((lds_char *)(char *)&stage[0][0]));
+    const unsigned lds_lse0 = static_cast<unsigned>(reinterpret_cast<size_t>((lds_char *)(char *)&lse_stage[0][0]));
+
+    // Copy stage t (64 streamed rows) into ring slot `slot`.  This wavefront moves rows
+    // 16*wave .. 16*wave+15, four rows (1 KiB) per instruction.  Rows past the end of the
+    // sequence are redirected to its last row (any finite data: they are masked later).
+    auto copy_stage = [&](int t, int slot) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = 16 * wave + 4 * i + (lane >> 4);           // row inside the stage
+            const int c = (lane & 15) ^ (r & 15);                    // global chunk for LDS chunk lane&15
+            const int grow = min(t * kStage + r, len - 1);
+            const unsigned voff = static_cast<unsigned>(grow) * (kD * 2) + c * 16;
+            const unsigned m0v = lds_stage0 + slot * kStageBytes + (16 * wave + 4 * i) * (kD * 2);
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0v), "v"(voff), "s"(strm)
+                         : "memory");
+        }
+        if (kColsum && wave == 0) {
+            const int grow = min(t * kStage + lane, len - 1);
+            const unsigned voff = static_cast<unsigned>(grow) * 4;
+            const unsigned m0v = lds_lse0 + slot * kStage * 4;
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2" ::"s"(m0v), "v"(voff), "s"(lse_u)
+                         : "memory");
+        }
+    };
+    // copies per stage issued by this wavefront (wavefront 0 also brings the lse values)
+    const bool extra_copy = kColsum && wave == 0;
 
     for (int job = 0; job < 2; ++job) {
         const int blk = job == 0 ? static_cast<int>(blockIdx.x) : n_blocks - 1 - static_cast<int>(blockIdx.x);
@@ -160,6 +207,15 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t *__restr
         const int base0 = blk * kBlockCols;
         if (base0 >= len) continue;
         const int w0 = base0 + wave * kWaveCols;       // first stationary row of this wavefront
+
+        // stages of streamed rows this workgroup walks through
+        const int t_begin = kColsum ? base0 / kStage : 0;
+        const int last_row = kColsum ? len - 1 : min(base0 + kBlockCols - 1, len - 1);
+        const int t_end = last_row / kStage;               // inclusive
+
+#pragma unroll
+        for (int k = 0; k < kAhead; ++k)
+            if (t_begin + k <= t_end) copy_stage(t_begin + k, k);
 
         // stationary operand: 2 column blocks x 8 MFMA steps, 8 bf16 per lane each
         bf16x8 Bf[2][8];
@@ -174,32 +230,13 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t *__restr
             }
         }
 
-        // stages of streamed rows this workgroup walks through
-        const int t_begin = kColsum ? base0 / kStage : 0;
-        const int last_row = kColsum ? len - 1 : min(base0 + kBlockCols - 1, len - 1);
-        const int t_end = last_row / kStage;               // inclusive
-
-        uint4 pre[4];
-        float pre_lse = 0.f;
-        auto fetch = [&](int t) {
+        // Make the stationary loads complete here, where the compiler can see it: otherwise it
+        // waits for them (vmcnt(0)) inside the stage loop, which would also drain the copies in
+        // flight that it does not know about.
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int r = t * kStage + ld_row + 16 * i;
-                pre[i] = (r < len) ? strm[static_cast<size_t>(r) * kChunksPerRow + ld_c] : make_uint4(0, 0, 0, 0);
-            }
-            if (kColsum && tid < kStage) {
-                const int r = t * kStage + tid;
-                pre_lse = (r < len) ? lse_u[r] : INFINITY;   // 2^(t - inf) = 0: rows past the end add nothing
-            }
-        };
-        auto commit = [&](int buf) {
+        for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int r = ld_row + 16 * i;
-                stage[buf][r * kChunksPerRow + swizzled_chunk(r, ld_c)] = pre[i];
-            }
-            if (kColsum && tid < kStage) lse_stage[buf][tid] = pre_lse;
-        };
+            for (int s = 0; s < 8; ++s) asm volatile("" ::"v"(Bf[cb][s]));
 
         Running<kColsum> run;
         run.m[0] = run.m[1] = -1e30f;
@@ -214,37 +251,47 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t *__restr
             if (kColsum) pend.lse[v] = 0.f;
         }
 
-        fetch(t_begin);
-        commit(0);
-        __syncthreads();
-
         for (int t = t_begin; t <= t_end; ++t) {
-            const int buf = (t - t_begin) & 1;
-            if (t < t_end) fetch(t + 1);
+            const int slot = (t - t_begin) & (kRing - 1);
+            // stage t is complete once only the copies of younger stages are outstanding
+            const int younger = min(t_end - t, kAhead - 1);
+            if (younger == 2) {
+                if (extra_copy) wait_copies_then_barrier<10>(); else wait_copies_then_barrier<8>();
+            } else if (younger == 1) {
+                if (extra_copy) wait_copies_then_barrier<5>(); else wait_copies_then_barrier<4>();
+            } else {
+                wait_copies_then_barrier<0>();
+            }
+            // the slot freed by stage t-1 (every wavefront is past it now) takes stage t+3
+            if (t + kAhead <= t_end) copy_stage(t + kAhead, (slot + kAhead) & (kRing - 1));
 
             const int s0 = t * kStage;                      // first streamed row of the stage
             // rowstat: streamed = keys, stationary = queries; a key counts iff key <= query
             // colsum : streamed = queries, stationary = keys
             const bool skip = kColsum ? (s0 < w0) : (s0 > w0);
             if (!skip) {
-                // One stage = two pairs of tiles.  The body is branch-free (the diagonal variant is
+                // One stage = two pairs of tiles.  The body is branch-free (the masked variant is
                 // a separate instantiation) so that MFMAs and exponentials share one basic block.
-                auto do_stage = [&](auto diag_tag) {
-                    constexpr bool kDiag = decltype(diag_tag)::value;
+                auto do_stage = [&](auto masked_tag) {
+                    constexpr bool kMasked = decltype(masked_tag)::value;
                     // the two instantiations must not share a hoisted prefix: the pending pair's
-                    // exponentials belong next to this stage's MFMAs
-                    // (the scale is re-read through an opaque asm so nothing that uses it can move up)
+                    // exponentials belong next to this stage's MFMAs (the scale is re-read through
+                    // an opaque asm so nothing that uses it can move up)
                     float scale = scale_log2;
-                    asm volatile("; stage variant %1" : "+s"(scale) : "n"(kDiag ? 1 : 0));
+                    asm volatile("; stage variant %1" : "+s"(scale) : "n"(kMasked ? 1 : 0));
 #pragma unroll
                     for (int kb = 0; kb < 2; ++kb) {
                         const int ar = 32 * kb + n;            // this lane's row of the streamed tile
                         Pending<kColsum> next;
+                        bf16x8 a[8];
+#pragma unroll
+                        for (int s = 0; s < 8; ++s)
+                            a[s] = as_bf16x8(stage[slot][ar * kChunksPerRow + swizzled_chunk(ar, s + 8 * g)]);
                         if (kColsum) {
 #pragma unroll
                             for (int q4 = 0; q4 < 4; ++q4) {
                                 const float4 x =
-                                    *reinterpret_cast<const float4 *>(&lse_stage[buf][32 * kb + 8 * q4 + 4 * g]);
+                                    *reinterpret_cast<const float4 *>(&lse_stage[slot][32 * kb + 8 * q4 + 4 * g]);
                                 next.lse[4 * q4 + 0] = x.x; next.lse[4 * q4 + 1] = x.y;
                                 next.lse[4 * q4 + 2] = x.z; next.lse[4 * q4 + 3] = x.w;
                             }
@@ -252,10 +299,6 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t *__restr
 #pragma unroll
                         for (int v = 0; v < 16; ++v) { next.acc[0][v] = 0.f; next.acc[1][v] = 0.f; }
                         Epilogue<kColsum> epi;
-                        bf16x8 a[8];
-#pragma unroll
-                        for (int s = 0; s < 8; ++s)
-                            a[s] = as_bf16x8(stage[buf][ar * kChunksPerRow + swizzled_chunk(ar, s + 8 * g)]);
 #pragma unroll
                         for (int s = 0; s < 8; ++s) {
                             next.acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], Bf[0][s], next.acc[0], 0, 0, 0);
@@ -272,18 +315,21 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t *__restr
                         // MFMA per slice of exponentials.
                         __builtin_amdgcn_sched_group_barrier(0x100, kColsum ? 12 : 8, 0);
                         __builtin_amdgcn_sched_group_barrier(0x002, 16, 0);
-                        sched_two_slots<5, 5, false>(); sched_two_slots<5, 5, false>(); sched_two_slots<5, 5, false>();
-                        sched_two_slots<5, 5, false>(); sched_two_slots<5, 5, false>(); sched_two_slots<5, 5, false>();
-                        sched_two_slots<5, 5, false>(); sched_two_slots<5, 5, false>();
-                        if constexpr (kDiag) {
-                            // mask the entries above the diagonal of the finished pair
+                        sched_two_slots<5, 5>(); sched_two_slots<5, 5>(); sched_two_slots<5, 5>(); sched_two_slots<5, 5>();
+                        sched_two_slots<5, 5>(); sched_two_slots<5, 5>(); sched_two_slots<5, 5>(); sched_two_slots<5, 5>();
+                        if constexpr (kMasked) {
+                            // -inf above the diagonal of the finished pair and, for streamed
+                            // queries, in rows past the end of the sequence
 #pragma unroll
                             for (int cb = 0; cb < 2; ++cb) {
                                 // lane's stationary index minus the first streamed row it holds
-                                const int d0 = (w0 + 32 * cb + n) - (s0 + 32 * kb + 4 * g);
+                                const int row0 = s0 + 32 * kb + 4 * g;
+                                const int d0 = (w0 + 32 * cb + n) - row0;
+                                const int rows_left = len - row0;
 #pragma unroll
                                 for (int v = 0; v < 16; ++v) {
-                                    const bool ok = kColsum ? (acc_row(v) >= d0) : (acc_row(v) <= d0);
+                                    const bool ok = kColsum ? (acc_row(v) >= d0 && acc_row(v) < rows_left)
+                                                            : (acc_row(v) <= d0);
                                     next.acc[cb][v] = ok ? next.acc[cb][v] : -INFINITY;
                                 }
                             }
@@ -291,12 +337,10 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t *__restr
                         pend = next;
                     }
                 };
-                if (s0 == w0) do_stage(std::true_type{});
+                const bool masked = (s0 == w0) || (kColsum && s0 + kStage > len);
+                if (masked) do_stage(std::true_type{});
                 else do_stage(std::false_type{});
             }
-
-            if (t < t_end) commit(buf ^ 1);
-            __syncthreads();
         }
 
         // the last pair still waits for its exponentials
@@ -321,6 +365,8 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t *__restr
                 if (g == 0 && idx < len) S[unit * cap + idx] = s;
             }
         }
+        // every wavefront must be done reading the ring before the next job refills it
+        wait_copies_then_barrier<0>();
     }
 }
 
