@@ -251,9 +251,9 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t *__restr
             if (kColsum) pend.lse[v] = 0.f;
         }
 
-        for (int t = t_begin; t <= t_end; ++t) {
-            const int slot = (t - t_begin) & (kRing - 1);
-            // stage t is complete once only the copies of younger stages are outstanding
+        // Publish stage t: it is complete once only the copies of younger stages are outstanding.
+        // Then the slot freed by stage t-1 (every wavefront is past it now) takes stage t+3.
+        auto stage_sync = [&](int t) {
             const int younger = min(t_end - t, kAhead - 1);
             if (younger == 2) {
                 if (extra_copy) wait_copies_then_barrier<10>(); else wait_copies_then_barrier<8>();
@@ -262,18 +262,19 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t *__restr
             } else {
                 wait_copies_then_barrier<0>();
             }
-            // the slot freed by stage t-1 (every wavefront is past it now) takes stage t+3
-            if (t + kAhead <= t_end) copy_stage(t + kAhead, (slot + kAhead) & (kRing - 1));
+            if (t + kAhead <= t_end) copy_stage(t + kAhead, (t + kAhead - t_begin) & (kRing - 1));
+        };
 
-            const int s0 = t * kStage;                      // first streamed row of the stage
-            // rowstat: streamed = keys, stationary = queries; a key counts iff key <= query
-            // colsum : streamed = queries, stationary = keys
-            const bool skip = kColsum ? (s0 < w0) : (s0 > w0);
-            if (!skip) {
-                // One stage = two pairs of tiles.  The body is branch-free (the masked variant is
-                // a separate instantiation) so that MFMAs and exponentials share one basic block.
-                auto do_stage = [&](auto masked_tag) {
+        // One stage = two pairs of tiles.  The body is branch-free (the masked variant is a
+        // separate instantiation) so that MFMAs and exponentials share one basic block.
+        // rowstat: streamed = keys, stationary = queries; a key counts iff key <= query
+        // colsum : streamed = queries, stationary = keys
+        {
+            {
+                auto do_stage = [&](int t, auto masked_tag) {
                     constexpr bool kMasked = decltype(masked_tag)::value;
+                    const int slot = (t - t_begin) & (kRing - 1);
+                    const int s0 = t * kStage;                  // first streamed row of the stage
                     // the two instantiations must not share a hoisted prefix: the pending pair's
                     // exponentials belong next to this stage's MFMAs (the scale is re-read through
                     // an opaque asm so nothing that uses it can move up)
@@ -337,9 +338,23 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t *__restr
                         pend = next;
                     }
                 };
-                const bool masked = (s0 == w0) || (kColsum && s0 + kStage > len);
-                if (masked) do_stage(std::true_type{});
-                else do_stage(std::false_type{});
+                // Every wavefront walks the same stages (same number of barriers) but spends them
+                // differently: full stages, its one diagonal stage, and stages it only waits through.
+                const int t_diag = w0 / kStage;
+                int t = t_begin;
+                if (w0 >= len) {
+                    for (; t <= t_end; ++t) stage_sync(t);              // no valid stationary row
+                } else if constexpr (!kColsum) {
+                    for (; t < t_diag; ++t) { stage_sync(t); do_stage(t, std::false_type{}); }
+                    stage_sync(t); do_stage(t, std::true_type{}); ++t;   // t_diag <= t_end here
+                    for (; t <= t_end; ++t) stage_sync(t);               // keys past the diagonal
+                } else {
+                    const int t_full_end = len / kStage - 1;             // last stage with 64 valid rows
+                    for (; t < t_diag; ++t) stage_sync(t);               // queries before the diagonal
+                    stage_sync(t); do_stage(t, std::true_type{}); ++t;
+                    for (; t <= t_full_end; ++t) { stage_sync(t); do_stage(t, std::false_type{}); }
+                    for (; t <= t_end; ++t) { stage_sync(t); do_stage(t, std::true_type{}); }   // ragged tail
+                }
             }
         }
 
