@@ -132,8 +132,10 @@ size_t vatp_workspace_bytes(const vatp_ctx *, const vatp_params *p, int which_ca
     switch (which_call) {
     case VATP_CALL_PREFILL_SCORE:           // lse2[units, cap]
         return align_up(units * p->cap * sizeof(float));
-    case VATP_CALL_DECODE_STEP:             // logits[units, cap]
-        return align_up(units * p->cap * sizeof(float));
+    case VATP_CALL_DECODE_STEP: {           // logits[units, cap] + per-chunk softmax statistics
+        const size_t chunks = (static_cast<size_t>(p->cap) + kDecodeChunk - 1) / kDecodeChunk;
+        return align_up(units * p->cap * sizeof(float)) + align_up(units * chunks * sizeof(float2));
+    }
     default:
         return 0;
     }
@@ -176,8 +178,10 @@ vatp_status vatp_decode_step(vatp_ctx *ctx, const vatp_params *p, const void *q,
     if (!ws || ws_bytes < need || misaligned(ws, kAlign)) return VATP_E_WORKSPACE;
     Prepared pr;
     prepare(p, VATP_CALL_DECODE_STEP, pos ? new_pos : nullptr, &pr);
-    if (launch_decode(p->dtype, p->head_dim, q, k, v, K, V, S, nrm, pos, static_cast<float *>(ws), pr.meta, pr.g,
-                      static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    const size_t units = static_cast<size_t>(p->batch) * p->n_heads;
+    float2 *ws_part = reinterpret_cast<float2 *>(static_cast<char *>(ws) + align_up(units * p->cap * sizeof(float)));
+    if (launch_decode(p->dtype, p->head_dim, q, k, v, K, V, S, nrm, pos, static_cast<float *>(ws), ws_part, pr.meta,
+                      pr.g, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
         return VATP_E_DEVICE;
     return VATP_OK;
 }

@@ -2,60 +2,46 @@
 // order of operations as in Fig. 2): append the new token's row, let its query attend
 // over every cached row, add the attention weights to the rows' running scores.
 //
-// HBM-bound GEMV: every K row is read exactly once, 16 bytes per lane, a group of lanes per
-// row, four rows in flight per lane.  One workgroup of 1024 threads owns a (batch, head)
-// unit, so the softmax over the unit's rows is finished inside the workgroup (LDS and
-// wavefront shuffles) and the kernel needs no cross-workgroup hand-off, no atomics and no
-// memory fences.  Logits live in the base-2 domain, t = c*log2(e)*<q,k>; they are parked in
-// LDS while the unit has at most kLdsRows rows, else in the caller's workspace.
+// Two launches, no atomics, no fences:
+//   logits  HBM-bound GEMV.  A (batch, head) unit is cut into chunks of 256 rows, one
+//           workgroup each, so that even a single sequence fills the chip.  Every K row is
+//           read exactly once, 16 bytes per lane, a group of lanes per row, all of the
+//           workgroup's loads in flight before the first is used.  The workgroup leaves its
+//           logits (base-2 domain, t = c*log2(e)*<q,k>) and its chunk's (max, sum of 2^(t-max))
+//           in the workspace, and the one that owns the new row appends k, v, |v|_1 and pos.
+//   finish  same grid, one row per thread: every workgroup merges the unit's few chunk
+//           statistics into log2 sum 2^t and applies S += 2^(t - lse2); 12 bytes per row, a
+//           tiny launch ordered after the first by the stream.
 #include "vatp_device.h"
 
 namespace vatp {
 
 namespace {
 
-constexpr int kThreads = 1024;
-constexpr int kWaves = kThreads / 64;
-constexpr int kLdsRows = 8192;
-
-__device__ __forceinline__ float block_reduce(float x, bool is_max, float *s_red)
-{
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        const float o = __shfl_xor(x, off);
-        x = is_max ? fmaxf(x, o) : x + o;
-    }
-    __syncthreads();                               // s_red may still be read from an earlier call
-    if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = x;
-    __syncthreads();
-    float r = s_red[0];
-#pragma unroll
-    for (int w = 1; w < kWaves; ++w) r = is_max ? fmaxf(r, s_red[w]) : r + s_red[w];
-    return r;
-}
-
-template <typename T, int D, bool kLdsLogits>
-__global__ __launch_bounds__(kThreads) void decode_score_kernel(
+template <typename T, int D>
+__global__ __launch_bounds__(256) void decode_logits_kernel(
     const T *__restrict__ q, const T *__restrict__ k_new, const T *__restrict__ v_new,
-    T *__restrict__ K, T *__restrict__ V, float *__restrict__ S, float *__restrict__ nrm,
-    int32_t *__restrict__ pos, float *ws_logit, BatchMeta meta, int n_heads, int cap,
-    float scale_log2)
+    T *__restrict__ K, T *__restrict__ V, float *__restrict__ nrm, int32_t *__restrict__ pos,
+    float *__restrict__ ws_logit, float2 *__restrict__ ws_part, BatchMeta meta, int n_heads,
+    int cap, int chunks_alloc, float scale_log2)
 {
     constexpr int kE = Elt<T>::kPer16B;
     constexpr int kLanesPerRow = D / kE;
-    constexpr int kRowsPerPass = kThreads / kLanesPerRow;
-    constexpr int kUnroll = 4;
+    constexpr int kRowsPerPass = 256 / kLanesPerRow;
+    constexpr int kPasses = kDecodeChunk / kRowsPerPass;
+    constexpr int kGroup = kPasses < 16 ? kPasses : 16;        // loads issued back to back
 
-    __shared__ float s_logit[kLdsLogits ? kLdsRows : 1];
-    __shared__ float s_red[kWaves];
+    __shared__ float s_logit[kDecodeChunk];
+    __shared__ float s_red[8];
 
-    const size_t unit = blockIdx.x;
-    const int b = static_cast<int>(unit / n_heads);
+    const size_t unit = blockIdx.y;
+    const int b = static_cast<int>(unit / n_heads), chunk = blockIdx.x;
     const int n0 = meta.len[b];            // rows cached before this step = index of the new row
     const int n = n0 + 1;
+    const int row0 = chunk * kDecodeChunk;
+    if (row0 >= n) return;
     const uint4 *Ku = reinterpret_cast<const uint4 *>(K + unit * cap * D);
     const uint4 *knew = reinterpret_cast<const uint4 *>(k_new + unit * D);
-    float *logit = kLdsLogits ? s_logit : ws_logit + unit * cap;
     const int tid = threadIdx.x;
     const int sub = tid % kLanesPerRow;
     const int rloc = tid / kLanesPerRow;
@@ -64,8 +50,8 @@ __global__ __launch_bounds__(kThreads) void decode_score_kernel(
     float qf[kE];
     Elt<T>::unpack(reinterpret_cast<const uint4 *>(q + unit * D)[sub], qf);
 
-    // append: k, v, |v|_1 and pos of the new token become row n0 of the caches
-    if (tid < kLanesPerRow) {
+    // the workgroup that owns the new row stores k, v, |v|_1 and pos into the caches
+    if (n0 >= row0 && n0 < row0 + kDecodeChunk && tid < kLanesPerRow) {
         const uint4 kraw = knew[sub];
         const uint4 vraw = reinterpret_cast<const uint4 *>(v_new + unit * D)[sub];
         reinterpret_cast<uint4 *>(K + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = kraw;
@@ -82,64 +68,97 @@ __global__ __launch_bounds__(kThreads) void decode_score_kernel(
         }
     }
 
-    // logits of every row; the new row is read from the step's input, not from the cache
-    for (int base = 0; base < n; base += kRowsPerPass * kUnroll) {
-        uint4 raw[kUnroll];
+    // logits of the chunk's rows; the new row is read from the step's input, not from the cache
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int r = base + u * kRowsPerPass + rloc;
+    for (int p0 = 0; p0 < kPasses; p0 += kGroup) {
+        uint4 raw[kGroup];
+#pragma unroll
+        for (int u = 0; u < kGroup; ++u) {
+            const int r = row0 + (p0 + u) * kRowsPerPass + rloc;
             const uint4 *src = (r == n0) ? knew + sub : Ku + static_cast<size_t>(r) * kLanesPerRow + sub;
             raw[u] = (r < n) ? *src : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int r = base + u * kRowsPerPass + rloc;
+        for (int u = 0; u < kGroup; ++u) {
+            const int rl = (p0 + u) * kRowsPerPass + rloc;
             float kf[kE], dot = 0.f;
             Elt<T>::unpack(raw[u], kf);
 #pragma unroll
             for (int e = 0; e < kE; ++e) dot = fmaf(qf[e], kf[e], dot);
 #pragma unroll
             for (int off = kLanesPerRow / 2; off > 0; off >>= 1) dot += __shfl_xor(dot, off);
-            if (sub == 0 && r < n) logit[r] = dot * scale_log2;
+            if (sub == 0) s_logit[rl] = (row0 + rl < n) ? dot * scale_log2 : -INFINITY;
         }
     }
     __syncthreads();
 
-    // softmax over the n rows, then S += a
-    float mx = -INFINITY;
-    for (int r = tid; r < n; r += kThreads) mx = fmaxf(mx, logit[r]);
-    mx = block_reduce(mx, true, s_red);
-    float sum = 0.f;
-    for (int r = tid; r < n; r += kThreads) sum += exp2f(logit[r] - mx);
-    sum = block_reduce(sum, false, s_red);
-    const float lse2 = mx + log2f(sum);
-    float *Su = S + unit * cap;
-    for (int r = tid; r < n; r += kThreads) {
-        const float a = exp2f(logit[r] - lse2);
-        Su[r] = (r == n0 ? 0.f : Su[r]) + a;
+    // chunk statistics: maximum and sum of 2^(t - max) over the chunk's rows
+    const int lane = tid & 63, wave = tid >> 6;
+    const float t = s_logit[tid];
+    float mx = t;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+    if (lane == 0) s_red[wave] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+    float e = exp2f(t - mx);                         // 2^(-inf) = 0 for rows past the end
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) e += __shfl_xor(e, off);
+    if (lane == 0) s_red[4 + wave] = e;
+    if (row0 + tid < n) ws_logit[unit * cap + row0 + tid] = t;
+    __syncthreads();
+    if (tid == 0)
+        ws_part[unit * chunks_alloc + chunk] = make_float2(mx, s_red[4] + s_red[5] + s_red[6] + s_red[7]);
+}
+
+__global__ __launch_bounds__(256) void decode_finish_kernel(float *__restrict__ S,
+                                                            const float *__restrict__ ws_logit,
+                                                            const float2 *__restrict__ ws_part,
+                                                            BatchMeta meta, int n_heads, int cap,
+                                                            int chunks_alloc)
+{
+    const size_t unit = blockIdx.y;
+    const int b = static_cast<int>(unit / n_heads);
+    const int n0 = meta.len[b], n = n0 + 1;
+    const int r = blockIdx.x * kDecodeChunk + threadIdx.x;       // one row per thread
+    if (blockIdx.x * kDecodeChunk >= n) return;
+    float logit = 0.f, s_old = 0.f;
+    if (r < n) {
+        logit = ws_logit[unit * cap + r];
+        if (r != n0) s_old = S[unit * cap + r];
     }
+    // every thread merges the unit's few chunk statistics itself
+    const int n_chunks = (n + kDecodeChunk - 1) / kDecodeChunk;
+    const float2 *part = ws_part + unit * chunks_alloc;
+    float M = -INFINITY;
+    for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, part[c].x);
+    float L = 0.f;
+    for (int c = 0; c < n_chunks; ++c) L += part[c].y * exp2f(part[c].x - M);
+    const float lse2 = M + log2f(L);
+    if (r < n) S[unit * cap + r] = s_old + exp2f(logit - lse2);
 }
 
 }  // namespace
 
 hipError_t launch_decode(int dtype, int head_dim, const void *q, const void *k, const void *v,
                          void *K, void *V, float *S, float *nrm, int32_t *pos, float *ws_logit,
-                         const BatchMeta &meta, const Geometry &g, hipStream_t st)
+                         float2 *ws_part, const BatchMeta &meta, const Geometry &g, hipStream_t st)
 {
-    dim3 grid(static_cast<unsigned>(g.batch) * g.n_heads), block(kThreads);
-    const bool lds = g.max_len <= kLdsRows;
-#define VATP_DEC(T, D, L)                                                                          \
-    hipLaunchKernelGGL((decode_score_kernel<T, D, L>), grid, block, 0, st, static_cast<const T *>(q), \
+    const int chunks_alloc = (g.cap + kDecodeChunk - 1) / kDecodeChunk;
+    const unsigned units = static_cast<unsigned>(g.batch) * g.n_heads;
+    dim3 grid((g.max_len + kDecodeChunk - 1) / kDecodeChunk, units), block(256);
+#define VATP_DEC(T, D)                                                                             \
+    hipLaunchKernelGGL((decode_logits_kernel<T, D>), grid, block, 0, st, static_cast<const T *>(q), \
                        static_cast<const T *>(k), static_cast<const T *>(v), static_cast<T *>(K),  \
-                       static_cast<T *>(V), S, nrm, pos, ws_logit, meta, g.n_heads, g.cap,         \
-                       g.scale_log2)
-#define VATP_DEC2(T, D) do { if (lds) VATP_DEC(T, D, true); else VATP_DEC(T, D, false); } while (0)
-    if (dtype == VATP_F32 && head_dim == 64) VATP_DEC2(float, 64);
-    else if (dtype == VATP_F32) VATP_DEC2(float, 128);
-    else if (head_dim == 64) VATP_DEC2(bf16_t, 64);
-    else VATP_DEC2(bf16_t, 128);
-#undef VATP_DEC2
+                       static_cast<T *>(V), nrm, pos, ws_logit, ws_part, meta, g.n_heads, g.cap,   \
+                       chunks_alloc, g.scale_log2)
+    if (dtype == VATP_F32 && head_dim == 64) VATP_DEC(float, 64);
+    else if (dtype == VATP_F32) VATP_DEC(float, 128);
+    else if (head_dim == 64) VATP_DEC(bf16_t, 64);
+    else VATP_DEC(bf16_t, 128);
 #undef VATP_DEC
+    hipLaunchKernelGGL(decode_finish_kernel, grid, block, 0, st, S, ws_logit, ws_part, meta, g.n_heads, g.cap,
+                       chunks_alloc);
     return hipGetLastError();
 }
 

@@ -24,6 +24,8 @@ struct Geometry {
     int32_t max_len;               // max over the batch of len (decode: len + 1)
 };
 
+constexpr int kDecodeChunk = 256;  // rows of one unit handled by one workgroup of the decode GEMV
+
 __device__ __forceinline__ float bf16_to_f32(bf16_t x) {
     return __uint_as_float(static_cast<uint32_t>(x) << 16);
 }
@@ -59,7 +61,8 @@ hipError_t launch_prefill_mfma(const void *Q, const void *K, float *S, float *ls
 
 hipError_t launch_decode(int dtype, int head_dim, const void *q, const void *k, const void *v,
                          void *K, void *V, float *S, float *nrm, int32_t *pos,
-                         float *ws_logit, const BatchMeta &meta, const Geometry &g, hipStream_t st);
+                         float *ws_logit, float2 *ws_part, const BatchMeta &meta, const Geometry &g,
+                         hipStream_t st);
 
 hipError_t launch_select(const float *S, const float *nrm, int32_t *kept_idx,
                          const BatchMeta &meta, const Geometry &g, hipStream_t st);
