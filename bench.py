@@ -92,6 +92,14 @@ def run(args):
         if ev is not None:
             ev["decode_loop"].append((e3, mark()))
 
+    if args.copy_calibration:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)          # 256 MiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)          # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()
@@ -227,6 +235,9 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch three plain 256 MiB -> 256 MiB element-wise copies (a known traffic "
+                         "figure to scale rocprofv3's FETCH_SIZE / WRITE_SIZE against)")
     run(ap.parse_args())
 
 

@@ -156,15 +156,23 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t *__restr
                                                            const bf16_t *__restrict__ K,
                                                            float *__restrict__ lse2,
                                                            float *__restrict__ S, BatchMeta meta,
-                                                           int n_heads, int cap, int n_blocks,
-                                                           float scale_log2)
+                                                           int n_heads, int n_units, int cap,
+                                                           int n_blocks, float scale_log2)
 {
     __shared__ uint4 stage[kRing][kStage * kChunksPerRow];      // 4 x 16 KiB, filled by the load unit
     __shared__ __attribute__((aligned(16))) float lse_stage[kRing][kStage];
 
-    const int b = blockIdx.z, h = blockIdx.y;
+    // Workgroups are handed to the 8 XCDs round-robin by linear id.  All block pairs of one
+    // (batch, head) unit are given ids that are equal mod 8, so the unit's streamed matrix is
+    // pulled into one XCD's L2 once instead of into all eight.
+    const int n_pairs = (n_blocks + 1) / 2;
+    const int xcd = blockIdx.x & 7, in_xcd = blockIdx.x >> 3;
+    const int unit_i = xcd + 8 * (in_xcd / n_pairs);
+    const int pair = in_xcd % n_pairs;
+    if (unit_i >= n_units) return;
+    const int b = unit_i / n_heads;
     const int len = meta.len[b];
-    const size_t unit = static_cast<size_t>(b) * n_heads + h;
+    const size_t unit = static_cast<size_t>(unit_i);
     const uint4 *stat = reinterpret_cast<const uint4 *>((kColsum ? K : Q) + unit * cap * kD);
     const bf16_t *strm = (kColsum ? Q : K) + unit * cap * kD;
     float *lse_u = lse2 + unit * cap;
@@ -202,8 +210,8 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t *__restr
     const bool extra_copy = kColsum && wave == 0;
 
     for (int job = 0; job < 2; ++job) {
-        const int blk = job == 0 ? static_cast<int>(blockIdx.x) : n_blocks - 1 - static_cast<int>(blockIdx.x);
-        if (job == 1 && blk == static_cast<int>(blockIdx.x)) break;      // odd count: the middle block once
+        const int blk = job == 0 ? pair : n_blocks - 1 - pair;
+        if (job == 1 && blk == pair) break;               // odd count: the middle block once
         const int base0 = blk * kBlockCols;
         if (base0 >= len) continue;
         const int w0 = base0 + wave * kWaveCols;       // first stationary row of this wavefront
@@ -392,11 +400,15 @@ hipError_t launch_prefill_mfma(const void *Q, const void *K, float *S, float *ls
 {
     if (g.max_len <= 0) return hipSuccess;
     const int n_blocks = (g.max_len + kBlockCols - 1) / kBlockCols;
-    dim3 grid((n_blocks + 1) / 2, g.n_heads, g.batch), block(256);
+    const int n_units = g.batch * g.n_heads;
+    const int n_pairs = (n_blocks + 1) / 2;
+    dim3 grid(8u * n_pairs * ((n_units + 7) / 8)), block(256);
     hipLaunchKernelGGL((prefill_mfma_kernel<false>), grid, block, 0, st, static_cast<const bf16_t *>(Q),
-                       static_cast<const bf16_t *>(K), lse2, S, meta, g.n_heads, g.cap, n_blocks, g.scale_log2);
+                       static_cast<const bf16_t *>(K), lse2, S, meta, g.n_heads, n_units, g.cap, n_blocks,
+                       g.scale_log2);
     hipLaunchKernelGGL((prefill_mfma_kernel<true>), grid, block, 0, st, static_cast<const bf16_t *>(Q),
-                       static_cast<const bf16_t *>(K), lse2, S, meta, g.n_heads, g.cap, n_blocks, g.scale_log2);
+                       static_cast<const bf16_t *>(K), lse2, S, meta, g.n_heads, n_units, g.cap, n_blocks,
+                       g.scale_log2);
     return hipGetLastError();
 }
 
