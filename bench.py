@@ -153,20 +153,23 @@ def run(args):
 
     mfma = cfg.dtype == "bf16"
     peak_tf = MFMA_BF16_PEAK_TFLOPS if mfma else FP32_VECTOR_PEAK_TFLOPS
+    traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name, cfg.layers), {})
     prefill_tflops = flops / (prefill_ms * 1e-3) / 1e12 if prefill_ms > 0 else 0.0
-    roof_prefill = {"kernel": "vatp_prefill_score (l1norm + rowstat + colsum)", "bound": "mfma" if mfma else "alu",
+    roof_prefill = {"kernel": "vatp_prefill_score = l1norm_kernel + prefill rowstat + prefill colsum",
+                    "bound": "mfma" if mfma else "alu",
                     "achieved": round(prefill_tflops, 3), "peak": peak_tf, "unit": "TFLOP/s",
-                    "frac": round(prefill_tflops / peak_tf, 5), "traffic": None,
+                    "frac": round(prefill_tflops / peak_tf, 5), "traffic": traffic.get("prefill_score"),
                     "avg_launch_ms": round(prefill_ms / cfg.layers, 5)}
     decode_gbps = (dec_bytes + sel_bytes) / (decode_ms * 1e-3) / 1e9 if decode_ms > 0 and T else 0.0
     dec_k_gbps = dec_bytes / n_calls / (dec_call_ms * 1e-3) / 1e9 if T and dec_call_ms > 0 else 0.0
     sel_k_gbps = sel_bytes / n_calls / (sel_call_ms * 1e-3) / 1e9 if T and sel_call_ms > 0 else 0.0
-    roof_decode = {"kernel": "decode_score_kernel", "bound": "hbm", "achieved": round(dec_k_gbps, 2),
-                   "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(dec_k_gbps / HBM_PEAK_GBPS, 5),
-                   "traffic": None, "avg_launch_ms": round(dec_call_ms, 5)}
-    roof_gather = {"kernel": "gather_kernel (evict-one select + compact)", "bound": "hbm",
+    roof_decode = {"kernel": "vatp_decode_step = decode_logits_kernel + decode_finish_kernel", "bound": "hbm",
+                   "achieved": round(dec_k_gbps, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                   "frac": round(dec_k_gbps / HBM_PEAK_GBPS, 5), "traffic": traffic.get("decode_step"),
+                   "avg_launch_ms": round(dec_call_ms, 5)}
+    roof_gather = {"kernel": "vatp_select_compact = gather_kernel (evict-one select + compact)", "bound": "hbm",
                    "achieved": round(sel_k_gbps, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                   "frac": round(sel_k_gbps / HBM_PEAK_GBPS, 5), "traffic": None,
+                   "frac": round(sel_k_gbps / HBM_PEAK_GBPS, 5), "traffic": traffic.get("select_compact"),
                    "avg_launch_ms": round(sel_call_ms, 5)}
     phases = {"prefill_score": prefill_ms, "decode_step": dec_call_ms * n_calls, "select_compact": sel_call_ms * n_calls}
     dominant = max(phases, key=phases.get)
@@ -199,29 +202,69 @@ def run(args):
     print(json.dumps(out), flush=True)
 
 
+# HBM bytes per launch (fetch + write) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# file, scaled by what the same counters read for the plain copy of --copy-calibration
+# (FETCH_SIZE x2.000, WRITE_SIZE x1.000); summaries under profiles/.  Keyed by (workload, layers).
+MEASURED_TRAFFIC_BYTES = {
+    # (fetch KiB summed over the entry point's kernels) * 2 * 1024 + (write KiB) * 1024
+    ("llama7b_layer", 1): {"prefill_score": 2 * 1024 * (32851 + 34195 + 16405) + 1024 * (512 * 3),
+                           "decode_step": 2 * 1024 * (8296 + 323) + 1024 * (291 + 264),
+                           "select_compact": 2 * 1024 * 18617 + 1024 * 33904},
+    ("llama7b_stack", 2): {"prefill_score": 2 * 1024 * (344636 + 447154 + 131093) + 1024 * (4096 * 3),
+                           "decode_step": 2 * 1024 * (26463 + 1012) + 1024 * (1012 + 836),
+                           "select_compact": 2 * 1024 * 59668 + 1024 * 108320},
+}
+
+
 def cpu_baseline(cfg, inp, budget_s):
-    """The float64 oracle, as it stands, timed on this machine's host cores on a bounded sample."""
+    """The float64 oracle, as it stands, timed on this machine's host cores on a bounded sample of
+    the same workload: prompt scoring of sequence 0 (all heads, one layer, prompt truncated only if
+    the estimate exceeds the time budget) and a few decode-and-prune steps at the steady-state size."""
     import numpy as np
     from oracle import vatp_oracle as orc
     threads = orc.max_threads()
-    b = 0
-    L = inp.lens[b]
-    # sample: prompt scoring of `threads` heads of sequence 0, prompt truncated so the work stays bounded
-    n_units = min(cfg.n_heads, threads)
-    est_rate = 1.2e9                                   # key-query pairs * d per second per core, rough
+    L, B = inp.lens[0], inp.budgets[0]
+    H, d = cfg.n_heads, cfg.head_dim
+    est_rate = 0.6e9 * threads                         # (query, key) pairs * d per second, rough
     Ls = L
-    while Ls > 256 and (Ls * Ls / 2) * cfg.head_dim / est_rate > budget_s:
+    while Ls > 256 and H * (Ls * Ls / 2) * d / est_rate > budget_s:
         Ls //= 2
-    Q = inp.Q[b, :n_units, :Ls].double().cpu().numpy()
-    K = inp.K[b, :n_units, :Ls].double().cpu().numpy()
+    Q = inp.Q[0, :, :Ls].double().cpu().numpy()
+    K = inp.K[0, :, :Ls].double().cpu().numpy()
     t0 = time.perf_counter()
-    orc.prefill_scores_units(Q, K, [Ls] * n_units)
+    orc.prefill_scores_units(Q, K, [Ls] * H)
     dt = time.perf_counter() - t0
-    # tokens/s of prompt scoring for the sampled shape: all heads of a layer must be scored per token
-    head_passes = n_units / cfg.n_heads
-    return {"value": round(Ls * head_passes / dt, 2), "unit": "tokens/s", "cores": threads, "kind": "oracle",
-            "sample": "prompt scoring (both softmax passes of the oracle), %d of %d heads, first %d of %d prompt "
-                      "tokens of sequence 0, one layer; %.2f s" % (n_units, cfg.n_heads, Ls, L, dt)}
+    out = {"value": round(Ls / dt, 2), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+           "sample": "prompt scoring (both softmax passes of the float64 oracle), all %d heads of one layer, "
+                     "first %d of %d prompt tokens of sequence 0; %.2f s" % (H, Ls, L, dt)}
+    # decode + prune at the steady-state cache size n = B + 1, a few steps, all heads of sequence 0
+    n = min(B, L) + 1
+    import ctypes
+    rng = np.random.default_rng(0)
+    Kc = np.ascontiguousarray(inp.K[0, :, :n].double().cpu().numpy()) if n <= inp.K.shape[2] else rng.standard_normal((H, n, d))
+    Vc = np.ascontiguousarray(inp.V[0, :, :n].double().cpu().numpy()) if n <= inp.V.shape[2] else rng.standard_normal((H, n, d))
+    Sc = rng.random((H, n)) + 0.1
+    nr = np.abs(Vc).sum(-1)
+    qv = inp.qd[0, 0].double().cpu().numpy() if inp.qd.shape[0] else rng.standard_normal((H, d))
+    Ko, Vo, So, No = np.zeros_like(Kc), np.zeros_like(Vc), np.zeros_like(Sc), np.zeros_like(Sc)
+    kept = np.zeros((H, n), dtype=np.int32)
+    n_arr = np.full(H, n, dtype=np.int64); B_arr = np.full(H, n - 1, dtype=np.int64); n_out = np.zeros(H, dtype=np.int64)
+    f64 = lambda a: a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+    i64 = lambda a: a.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))
+    if n - 1 >= cfg.n_sink_keep + cfg.recent:
+        steps = 3
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            orc.lib().vatp_oracle_decode_prune_units(f64(qv), f64(Kc), f64(Vc), f64(Sc), f64(nr), H, n, i64(n_arr), d,
+                                                     orc.default_scale(d), i64(B_arr), cfg.n_sink_keep, cfg.recent,
+                                                     f64(Ko), f64(Vo), f64(So), f64(No),
+                                                     kept.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), i64(n_out))
+        dt2 = (time.perf_counter() - t0) / steps
+        s_bytes, c_bytes = algorithmic_bytes_decode(cfg, n, n - 1)
+        out["decode_prune_GBps"] = round((s_bytes + c_bytes) * H / dt2 / 1e9, 3)
+        out["sample"] += "; decode+prune: %d steps at n=%d rows, all heads of sequence 0, %.3f s per step, GB/s over the " \
+                         "same algorithmic bytes as the GPU figure" % (steps, n, dt2)
+    return out
 
 
 def main():
