@@ -162,7 +162,8 @@ def select(I, B: int, F: int, R: int) -> np.ndarray:
 def gather_rows(x, kept) -> np.ndarray:
     x = _f64(x)
     kept = np.ascontiguousarray(kept, dtype=np.int32)
-    flat = x.reshape(x.shape[0], -1)
+    width = int(np.prod(x.shape[1:], dtype=np.int64))        # also right for a cache with no rows
+    flat = x.reshape(x.shape[0], width)
     out = np.zeros((kept.shape[0], flat.shape[1]), dtype=np.float64)
     lib().vatp_oracle_gather_rows(_p(flat), kept.ctypes.data_as(_i32p), kept.shape[0],
                                   flat.shape[1], _p(out))

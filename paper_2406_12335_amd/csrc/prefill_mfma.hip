@@ -58,6 +58,14 @@ constexpr int kWaveCols = 64;      // stationary rows per wavefront
 constexpr int kBlockCols = 256;    // stationary rows per workgroup
 constexpr int kChunksPerRow = kD * 2 / 16;   // 16-byte chunks per row = 16
 constexpr int kStageBytes = kStage * kD * 2; // 16 KiB
+#ifndef VATP_LEAD_VALU
+#define VATP_LEAD_VALU 12
+#endif
+#ifndef VATP_SLOT_VALU
+#define VATP_SLOT_VALU 6
+#endif
+constexpr int kLeadValu = VATP_LEAD_VALU;    // vector instructions asked for between the LDS reads and the first MFMA
+constexpr int kSlotValu = VATP_SLOT_VALU;    // vector instructions asked for after every MFMA
 
 __device__ __forceinline__ int swizzled_chunk(int row, int c) { return c ^ (row & 15); }
 
@@ -319,13 +327,14 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t *__restr
                         // keep the pending pair's results inside this block (no sinking past it)
                         if constexpr (kColsum) asm volatile("" : "+v"(run.col[0]), "+v"(run.col[1]));
                         else asm volatile("" : "+v"(run.l[0]), "+v"(run.l[1]), "+v"(run.m[0]), "+v"(run.m[1]));
-                        // Issue order asked of the scheduler: all LDS reads of the pair first, then a
-                        // run of the pending pair's vector work to cover their latency, then one
-                        // MFMA per slice of exponentials.
-                        __builtin_amdgcn_sched_group_barrier(0x100, kColsum ? 12 : 8, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x002, 16, 0);
-                        sched_two_slots<5, 5>(); sched_two_slots<5, 5>(); sched_two_slots<5, 5>(); sched_two_slots<5, 5>();
-                        sched_two_slots<5, 5>(); sched_two_slots<5, 5>(); sched_two_slots<5, 5>(); sched_two_slots<5, 5>();
+                        // Issue order asked of the scheduler: a short run of the pending pair's vector
+                        // work, then one MFMA per slice of exponentials.  (LDS reads are left to the
+                        // scheduler: pinning them makes it drop the whole request.)
+                        __builtin_amdgcn_sched_group_barrier(0x002, kLeadValu, 0);
+                        sched_two_slots<kSlotValu, kSlotValu>(); sched_two_slots<kSlotValu, kSlotValu>();
+                        sched_two_slots<kSlotValu, kSlotValu>(); sched_two_slots<kSlotValu, kSlotValu>();
+                        sched_two_slots<kSlotValu, kSlotValu>(); sched_two_slots<kSlotValu, kSlotValu>();
+                        sched_two_slots<kSlotValu, kSlotValu>(); sched_two_slots<kSlotValu, kSlotValu>();
                         if constexpr (kMasked) {
                             // -inf above the diagonal of the finished pair and, for streamed
                             // queries, in rows past the end of the sequence

@@ -255,3 +255,111 @@ def test_entry_points_report_errors_on_device(gpu_device):
         assert e.value.status == -2                                          # output aliases input
     finally:
         vatp.vatp_destroy(ctx)
+
+
+# ------------------------------------------------------------------ edge cases
+
+def test_empty_and_one_token_sequences_in_a_batch(gpu_device):
+    """A sequence of length 0 (nothing to score, nothing to keep) next to lengths 1 and 70."""
+    lens = [0, 1, 70, 0]
+    cfg = vs.scaled(vs.CONFIGS["llama7b_layer"], batch=4, n_heads=2, prompt_len=70, decode_steps=5, recent=3,
+                    n_sinks=1, budget_pct=50)
+    inp = vs.make_inputs(cfg, seed=31)
+    inp.lens = lens
+    inp.budgets = [4, 4, 35, 6]
+    _say("empty sequences lens=%s budgets=%s" % (lens, inp.budgets))
+    rep = parity.run_trajectory(inp, gpu_device, cap_cache=40)
+    assert rep.units_checked == 8
+    _say("report %r" % rep)
+
+
+def test_custom_scale_and_untracked_positions(gpu_device):
+    cfg = vs.scaled(vs.CONFIGS["llama7b_layer"], n_heads=2, prompt_len=200, decode_steps=3)
+    inp = vs.make_inputs(cfg, seed=32)
+    dev = gpu_device
+    d, L, Bq, F, R = 128, 200, 100, 2, 64
+    scale = 0.05
+    ctx = vatp.vatp_create(0)
+    try:
+        p = vatp.Params(1, 2, d, torch.bfloat16, F, R, L, [L], [Bq], cap_out=Bq + 1, scale=scale)
+        ws = torch.empty(vatp.vatp_workspace_bytes(ctx, p, vatp.CALL_PREFILL_SCORE), dtype=torch.uint8, device=dev)
+        Q, K, V = inp.Q.to(dev), inp.K.to(dev), inp.V.to(dev)
+        S = torch.zeros(1, 2, L, device=dev)
+        nrm = torch.zeros(1, 2, L, device=dev)
+        vatp.vatp_prefill_score(ctx, p, Q, K, V, S, nrm, ws)
+        Ko = torch.zeros(1, 2, Bq + 1, d, dtype=torch.bfloat16, device=dev)
+        Vo = torch.zeros_like(Ko)
+        So = torch.zeros(1, 2, Bq + 1, device=dev)
+        No = torch.zeros_like(So)
+        kept = torch.zeros(1, 2, Bq + 1, dtype=torch.int32, device=dev)
+        vatp.vatp_select_compact(ctx, p, K, V, S, nrm, None, Ko, Vo, So, No, None, kept)     # pos not tracked
+        pd = vatp.Params(1, 2, d, torch.bfloat16, F, R, Bq + 1, [Bq], [Bq], scale=scale)
+        wsd = torch.empty(vatp.vatp_workspace_bytes(ctx, pd, vatp.CALL_DECODE_STEP), dtype=torch.uint8, device=dev)
+        vatp.vatp_decode_step(ctx, pd, inp.qd[0].to(dev), inp.kd[0].to(dev), inp.vd[0].to(dev), Ko, Vo, So, No, None,
+                              None, wsd)
+        torch.cuda.synchronize()
+    finally:
+        vatp.vatp_destroy(ctx)
+    for h in range(2):
+        o = orc.OracleHead(d, c=scale)
+        o.prefill(inp.Q[0, h].double().numpy(), inp.K[0, h].double().numpy(), inp.V[0, h].double().numpy())
+        parity.assert_scores_close(S[0, h].cpu().numpy(), o.S, 1e-3, "S with custom scale")
+        kept_or = o.prune(Bq, F, R)
+        np.testing.assert_array_equal(kept[0, h, :Bq].cpu().numpy(), kept_or)
+        o.append_and_score(inp.qd[0, 0, h].double().numpy(), inp.kd[0, 0, h].double().numpy(),
+                           inp.vd[0, 0, h].double().numpy(), L)
+        parity.assert_scores_close(So[0, h, :Bq + 1].cpu().numpy(), o.S, 1e-3, "decode S with custom scale")
+        parity.assert_scores_close(No[0, h, :Bq + 1].cpu().numpy(), o.nrm, 1e-3, "decode nrm")
+
+
+def test_decode_on_a_long_cache_and_determinism(gpu_device):
+    """One head with 70001 cached rows (hundreds of chunks), run twice: identical bits, oracle parity."""
+    n0, d = 70001, 64
+    g = torch.Generator().manual_seed(41)
+    K = torch.randn(1, 1, n0 + 1, d, generator=g)
+    V = torch.randn(1, 1, n0 + 1, d, generator=g)
+    S0 = torch.rand(1, 1, n0 + 1, generator=g) * 2
+    nrm0 = V.abs().sum(-1)
+    q, k, v = (torch.randn(1, 1, d, generator=g) * 1.5 for _ in range(3))
+    _say("long-cache decode n0=%d" % n0)
+    dev = gpu_device
+    outs = []
+    ctx = vatp.vatp_create(0)
+    try:
+        p = vatp.Params(1, 1, d, torch.float32, 0, 0, n0 + 1, [n0], None)
+        ws = torch.empty(vatp.vatp_workspace_bytes(ctx, p, vatp.CALL_DECODE_STEP), dtype=torch.uint8, device=dev)
+        for _ in range(2):
+            Kd, Vd, Sd, Nd = K.to(dev).clone(), V.to(dev).clone(), S0.to(dev).clone(), nrm0.to(dev).clone()
+            Kd[0, 0, n0] = 7.0          # stale junk in the slot of the new row
+            Sd[0, 0, n0] = 123.0
+            pos = torch.arange(n0 + 1, dtype=torch.int32, device=dev).view(1, 1, -1).clone()
+            vatp.vatp_decode_step(ctx, p, q.to(dev), k.to(dev), v.to(dev), Kd, Vd, Sd, Nd, pos, [555], ws)
+            torch.cuda.synchronize()
+            outs.append((Kd.cpu(), Vd.cpu(), Sd.cpu(), Nd.cpu(), pos.cpu()))
+    finally:
+        vatp.vatp_destroy(ctx)
+    for a, b in zip(outs[0], outs[1]):
+        assert torch.equal(a, b)
+    Kd, Vd, Sd, Nd, pos = outs[0]
+    assert torch.equal(Kd[0, 0, n0], k[0, 0]) and torch.equal(Vd[0, 0, n0], v[0, 0]) and pos[0, 0, n0] == 555
+    Kfull = torch.cat([K[0, 0, :n0], k[0]], 0).double().numpy()
+    S_in = np.concatenate([S0[0, 0, :n0].double().numpy(), np.zeros(1)])
+    S_or, _ = orc.decode_scores(q[0, 0].double().numpy(), Kfull, S_in)
+    parity.assert_scores_close(Sd[0, 0].numpy(), S_or, 1e-5, "long-cache decode S")
+    assert abs(float(Nd[0, 0, n0]) - float(v.abs().sum())) < 1e-4
+
+
+def test_misaligned_pointers_are_rejected(gpu_device):
+    ctx = vatp.vatp_create(0)
+    try:
+        base = torch.zeros(1 * 1 * 8 * 64 + 8, dtype=torch.bfloat16, device=gpu_device)
+        t_bad = base[1:1 + 512].view(1, 1, 8, 64)           # 2 bytes off a 16-byte boundary
+        t_ok = base[:512].view(1, 1, 8, 64)
+        s = torch.zeros(1, 1, 8, device=gpu_device)
+        p = vatp.Params(1, 1, 64, torch.bfloat16, 0, 0, 8, [8], [4])
+        ws = torch.empty(4096, dtype=torch.uint8, device=gpu_device)
+        with pytest.raises(vatp.VatpError) as e:
+            vatp.vatp_prefill_score(ctx, p, t_bad, t_ok, t_ok, s, s.clone(), ws)
+        assert e.value.status == -2
+    finally:
+        vatp.vatp_destroy(ctx)
