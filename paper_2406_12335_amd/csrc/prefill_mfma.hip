@@ -62,7 +62,7 @@ constexpr int kStageBytes = kStage * kD * 2; // 16 KiB
 #define VATP_LEAD_VALU 12
 #endif
 #ifndef VATP_SLOT_VALU
-#define VATP_SLOT_VALU 6
+#define VATP_SLOT_VALU 5
 #endif
 constexpr int kLeadValu = VATP_LEAD_VALU;    // vector instructions asked for between the LDS reads and the first MFMA
 constexpr int kSlotValu = VATP_SLOT_VALU;    // vector instructions asked for after every MFMA
