@@ -206,13 +206,9 @@ def run(args):
 # file, scaled by what the same counters read for the plain copy of --copy-calibration
 # (FETCH_SIZE x2.000, WRITE_SIZE x1.000); summaries under profiles/.  Keyed by (workload, layers).
 MEASURED_TRAFFIC_BYTES = {
-    # (fetch KiB summed over the entry point's kernels) * 2 * 1024 + (write KiB) * 1024
-    ("llama7b_layer", 1): {"prefill_score": 2 * 1024 * (32851 + 34195 + 16405) + 1024 * (512 * 3),
-                           "decode_step": 2 * 1024 * (8296 + 323) + 1024 * (291 + 264),
-                           "select_compact": 2 * 1024 * 18617 + 1024 * 33904},
-    ("llama7b_stack", 2): {"prefill_score": 2 * 1024 * (344636 + 447154 + 131093) + 1024 * (4096 * 3),
-                           "decode_step": 2 * 1024 * (26463 + 1012) + 1024 * (1012 + 836),
-                           "select_compact": 2 * 1024 * 59668 + 1024 * 108320},
+    # calibrated fetch + write bytes per call of the entry point (all of its kernels)
+    ("llama7b_layer", 1): {"prefill_score": 172539487, "decode_step": 18215899, "select_compact": 72840051},
+    ("llama7b_stack", 2): {"prefill_score": 1891085500, "decode_step": 58155237, "select_compact": 233123329},
 }
 
 
