@@ -3,7 +3,7 @@
 // over every cached row, add the attention weights to the rows' running scores.
 //
 // Two launches, no atomics, no fences:
-//   logits  HBM-bound GEMV.  A (batch, head) unit is cut into chunks of 256 rows, one
+//   logits  HBM-bound GEMV.  A (batch, head) unit is cut into chunks of kDecodeChunk rows, one
 //           workgroup each, so that even a single sequence fills the chip.  Every K row is
 //           read exactly once, 16 bytes per lane, a group of lanes per row, all of the
 //           workgroup's loads in flight before the first is used.  The workgroup leaves its
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(
 
     // chunk statistics: maximum and sum of 2^(t - max) over the chunk's rows
     const int lane = tid & 63, wave = tid >> 6;
-    const float t = s_logit[tid];
+    const float t = tid < kDecodeChunk ? s_logit[tid] : -INFINITY;
     float mx = t;
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
@@ -105,7 +105,7 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) e += __shfl_xor(e, off);
     if (lane == 0) s_red[4 + wave] = e;
-    if (row0 + tid < n) ws_logit[unit * cap + row0 + tid] = t;
+    if (tid < kDecodeChunk && row0 + tid < n) ws_logit[unit * cap + row0 + tid] = t;
     __syncthreads();
     if (tid == 0)
         ws_part[unit * chunks_alloc + chunk] = make_float2(mx, s_red[4] + s_red[5] + s_red[6] + s_red[7]);
@@ -120,8 +120,8 @@ __global__ __launch_bounds__(256) void decode_finish_kernel(float *__restrict__ 
     const size_t unit = blockIdx.y;
     const int b = static_cast<int>(unit / n_heads);
     const int n0 = meta.len[b], n = n0 + 1;
-    const int r = blockIdx.x * kDecodeChunk + threadIdx.x;       // one row per thread
-    if (blockIdx.x * kDecodeChunk >= n) return;
+    const int r = blockIdx.x * 256 + threadIdx.x;                // one row per thread
+    if (blockIdx.x * 256 >= n) return;
     float logit = 0.f, s_old = 0.f;
     if (r < n) {
         logit = ws_logit[unit * cap + r];
@@ -157,8 +157,8 @@ hipError_t launch_decode(int dtype, int head_dim, const void *q, const void *k, 
     else if (head_dim == 64) VATP_DEC(bf16_t, 64);
     else VATP_DEC(bf16_t, 128);
 #undef VATP_DEC
-    hipLaunchKernelGGL(decode_finish_kernel, grid, block, 0, st, S, ws_logit, ws_part, meta, g.n_heads, g.cap,
-                       chunks_alloc);
+    hipLaunchKernelGGL(decode_finish_kernel, dim3((g.max_len + 255) / 256, units), block, 0, st, S, ws_logit, ws_part,
+                       meta, g.n_heads, g.cap, chunks_alloc);
     return hipGetLastError();
 }
 

@@ -24,7 +24,7 @@ struct Geometry {
     int32_t max_len;               // max over the batch of len (decode: len + 1)
 };
 
-constexpr int kDecodeChunk = 256;  // rows of one unit handled by one workgroup of the decode GEMV
+constexpr int kDecodeChunk = 128;  // rows of one unit handled by one workgroup of the decode GEMV
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t x) {
     return __uint_as_float(static_cast<uint32_t>(x) << 16);
