@@ -43,7 +43,7 @@ typedef struct vatp_ctx vatp_ctx;  /* opaque */
 typedef enum {
     VATP_OK = 0,
     VATP_E_NULL = -1,        /* a required pointer is NULL                                 */
-    VATP_E_SHAPE = -2,       /* batch / heads / head_dim / cap / len out of range          */
+    VATP_E_SHAPE = -2,       /* batch / heads / head_dim / cap / len / norm out of range   */
     VATP_E_DTYPE = -3,       /* dtype is neither VATP_F32 nor VATP_BF16                    */
     VATP_E_BUDGET = -4,      /* budget[b] < n_sink + recent, or budget[b] > cap_out        */
     VATP_E_WORKSPACE = -5,   /* workspace missing, too small or not 256-byte aligned       */
@@ -51,6 +51,7 @@ typedef enum {
 } vatp_status;
 
 enum { VATP_F32 = 0, VATP_BF16 = 1 };
+enum { VATP_NORM_L1 = 0, VATP_NORM_L2 = 1, VATP_NORM_LINF = 2 };
 enum { VATP_CALL_PREFILL_SCORE = 0, VATP_CALL_DECODE_STEP = 1, VATP_CALL_SELECT_COMPACT = 2 };
 
 typedef struct {
@@ -67,6 +68,8 @@ typedef struct {
     const int32_t *len;     /* HOST [batch]: valid rows per sequence, same for all heads   */
     const int32_t *budget;  /* HOST [batch]: B, rows kept per head (F and R included).     */
                             /*   only vatp_select_compact reads it; may be NULL elsewhere  */
+    int32_t norm;           /* value-row norm of Eq. 4: VATP_NORM_L1 (0, the paper's choice), */
+                            /*   VATP_NORM_L2 or VATP_NORM_LINF (the ablation of Table 2)      */
 } vatp_params;
 
 /* Creates a context for HIP device `device` (host memory only).  The device must be the
@@ -90,7 +93,7 @@ size_t vatp_workspace_bytes(const vatp_ctx *ctx, const vatp_params *p, int which
 /*
  * Prompt pass (Eq. 1 and Eq. 2 with t = len-1; Eq. 4's norm).
  * For every unit:  S[i]   = sum_{j=i}^{len-1} softmax_{i'<=j}(c <q_j, k_i'>)[i]
- *                  nrm[i] = sum_x |V[i][x]|                       for i < len[b].
+ *                  nrm[i] = |V[i]|_1 (or the norm `norm` selects)  for i < len[b].
  * Q, K, V: device [batch, n_heads, cap, head_dim] (dtype).  S, nrm: device float32
  * [batch, n_heads, cap], written for rows < len[b] only.  Nothing is pruned here.
  */
@@ -102,7 +105,7 @@ vatp_status vatp_prefill_score(vatp_ctx *ctx, const vatp_params *p,
 /*
  * One decode step (Eq. 2 taken incrementally; order of operations as in Fig. 2).
  * For every unit with n0 = len[b] rows: the new token's k, v are stored as row n0 of the
- * K, V caches, nrm[n0] = |v|_1, pos[n0] = new_pos[b]; the new query attends over the
+ * K, V caches, nrm[n0] = |v| (same norm), pos[n0] = new_pos[b]; the new query attends over the
  * n0 + 1 rows and S[r] += a_r for r <= n0 (row n0 starts from 0).  The caller then uses
  * len[b] + 1.  q, k, v: device [batch, n_heads, head_dim] (dtype).  K, V, S, nrm, pos:
  * device caches, updated in place.  pos may be NULL (then new_pos may be NULL too).

@@ -97,6 +97,24 @@ void vatp_oracle_l1norm(const double *V, int64_t n, int64_t d, double *nrm)
 }
 
 /*
+ * The norm ablation (Table 2): kind 0 = l1 (the paper's choice, same as above),
+ * 1 = l2 = sqrt(sum v^2), 2 = l-infinity = max |v|.  V: [n, d] -> nrm: [n].
+ */
+void vatp_oracle_vnorm(const double *V, int64_t n, int64_t d, int kind, double *nrm)
+{
+    for (int64_t r = 0; r < n; ++r) {
+        double s = 0.0;
+        for (int64_t x = 0; x < d; ++x) {
+            double a = fabs(V[r * d + x]);
+            if (kind == 0) s += a;
+            else if (kind == 1) s += a * a;
+            else if (a > s) s = a;
+        }
+        nrm[r] = kind == 1 ? sqrt(s) : s;
+    }
+}
+
+/*
  * Value-aware importance, Eq. 4:  I_r = S_r * ||v_r||_1.
  * decide_f32 != 0 rounds each product to binary32 first: that is the precision in
  * which the GPU library compares importances, so that a test which feeds both sides

@@ -53,6 +53,8 @@ def lib():
         L.vatp_oracle_decode_scores.restype = None
         L.vatp_oracle_l1norm.argtypes = [_f64p, _i64, _i64, _f64p]
         L.vatp_oracle_l1norm.restype = None
+        L.vatp_oracle_vnorm.argtypes = [_f64p, _i64, _i64, ctypes.c_int, _f64p]
+        L.vatp_oracle_vnorm.restype = None
         L.vatp_oracle_importance.argtypes = [_f64p, _f64p, _i64, ctypes.c_int, _f64p]
         L.vatp_oracle_importance.restype = None
         L.vatp_oracle_select.argtypes = [_f64p, _i64, _i64, _i64, _i64, _i32p]
@@ -140,6 +142,15 @@ def l1norm(V) -> np.ndarray:
     return out
 
 
+def vnorm(V, kind: int = 0) -> np.ndarray:
+    """Row norms for the ablation of Table 2: kind 0 = l1, 1 = l2, 2 = l-infinity."""
+    V = _f64(V)
+    n, d = V.shape
+    out = np.zeros(n, dtype=np.float64)
+    lib().vatp_oracle_vnorm(_p(V), n, d, int(kind), _p(out))
+    return out
+
+
 def importance(S, nrm, decide_f32: bool = False) -> np.ndarray:
     """Eq. 4. decide_f32 rounds each product to binary32 (the GPU's comparison precision)."""
     S, nrm = _f64(S), _f64(nrm)
@@ -190,8 +201,9 @@ class OracleHead:
     another implementation after an admissible near-tie difference.
     """
 
-    def __init__(self, d: int, c: Optional[float] = None):
+    def __init__(self, d: int, c: Optional[float] = None, norm_kind: int = 0):
         self.d = d
+        self.norm_kind = norm_kind
         self.c = default_scale(d) if c is None else c
         self.K = np.zeros((0, d))
         self.V = np.zeros((0, d))
@@ -206,7 +218,7 @@ class OracleHead:
     def prefill(self, Q, K, V):
         self.K, self.V = _f64(K).copy(), _f64(V).copy()
         self.S = prefill_scores(Q, self.K, self.c)
-        self.nrm = l1norm(self.V)
+        self.nrm = l1norm(self.V) if self.norm_kind == 0 else vnorm(self.V, self.norm_kind)
         self.pos = np.arange(self.K.shape[0], dtype=np.int64)
 
     def importance(self, decide_f32: bool = False) -> np.ndarray:
@@ -226,7 +238,8 @@ class OracleHead:
         self.K = np.concatenate([self.K, _f64(k)[None, :]], axis=0)
         self.V = np.concatenate([self.V, _f64(v)[None, :]], axis=0)
         self.S = np.concatenate([self.S, np.zeros(1)])
-        self.nrm = np.concatenate([self.nrm, l1norm(_f64(v)[None, :])])
+        new_row = _f64(v)[None, :]
+        self.nrm = np.concatenate([self.nrm, l1norm(new_row) if self.norm_kind == 0 else vnorm(new_row, self.norm_kind)])
         self.pos = np.concatenate([self.pos, np.array([new_pos], dtype=np.int64)])
         self.S, a = decode_scores(q, self.K, self.S, self.c)
         return a

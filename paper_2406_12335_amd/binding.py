@@ -17,6 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libvatp.so")
 
 VATP_F32, VATP_BF16 = 0, 1
+NORM_L1, NORM_L2, NORM_LINF = 0, 1, 2
 CALL_PREFILL_SCORE, CALL_DECODE_STEP, CALL_SELECT_COMPACT = 0, 1, 2
 VATP_MAX_BATCH, VATP_MAX_UNITS = 64, 16384
 OK, E_NULL, E_SHAPE, E_DTYPE, E_BUDGET, E_WORKSPACE, E_DEVICE = 0, -1, -2, -3, -4, -5, -6
@@ -35,7 +36,8 @@ class _Params(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("n_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("n_sink", ctypes.c_int32), ("recent", ctypes.c_int32),
                 ("cap", ctypes.c_int32), ("cap_out", ctypes.c_int32), ("scale", ctypes.c_float),
-                ("len", ctypes.POINTER(ctypes.c_int32)), ("budget", ctypes.POINTER(ctypes.c_int32))]
+                ("len", ctypes.POINTER(ctypes.c_int32)), ("budget", ctypes.POINTER(ctypes.c_int32)),
+                ("norm", ctypes.c_int32)]
 
 
 _lib = None
@@ -81,14 +83,15 @@ class Params:
 
     def __init__(self, batch: int, n_heads: int, head_dim: int, dtype, n_sink: int, recent: int,
                  cap: int, len: Sequence[int], budget: Optional[Sequence[int]] = None,
-                 cap_out: int = 0, scale: float = 0.0):
+                 cap_out: int = 0, scale: float = 0.0, norm: int = 0):
         if isinstance(dtype, torch.dtype):
             dtype = {torch.float32: VATP_F32, torch.bfloat16: VATP_BF16}.get(dtype, -1)
         self._len = (ctypes.c_int32 * max(1, batch))(*list(len)) if len is not None else None
         self._budget = (ctypes.c_int32 * max(1, batch))(*list(budget)) if budget is not None else None
         self.c = _Params(batch, n_heads, head_dim, int(dtype), n_sink, recent, cap, cap_out, scale,
                          ctypes.cast(self._len, ctypes.POINTER(ctypes.c_int32)) if self._len is not None else None,
-                         ctypes.cast(self._budget, ctypes.POINTER(ctypes.c_int32)) if self._budget is not None else None)
+                         ctypes.cast(self._budget, ctypes.POINTER(ctypes.c_int32)) if self._budget is not None else None,
+                         int(norm))
 
     def set_len(self, len: Sequence[int]) -> None:
         for i, v in enumerate(len):

@@ -23,7 +23,7 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(
     const T *__restrict__ q, const T *__restrict__ k_new, const T *__restrict__ v_new,
     T *__restrict__ K, T *__restrict__ V, float *__restrict__ nrm, int32_t *__restrict__ pos,
     float *__restrict__ ws_logit, float2 *__restrict__ ws_part, BatchMeta meta, int n_heads,
-    int cap, int chunks_alloc, float scale_log2)
+    int cap, int chunks_alloc, float scale_log2, int norm)
 {
     constexpr int kE = Elt<T>::kPer16B;
     constexpr int kLanesPerRow = D / kE;
@@ -59,11 +59,11 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(
         float vf[kE], a = 0.f;
         Elt<T>::unpack(vraw, vf);
 #pragma unroll
-        for (int e = 0; e < kE; ++e) a += fabsf(vf[e]);
+        for (int e = 0; e < kE; ++e) a = norm_accum(norm, a, vf[e]);
 #pragma unroll
-        for (int off = kLanesPerRow / 2; off > 0; off >>= 1) a += __shfl_xor(a, off);
+        for (int off = kLanesPerRow / 2; off > 0; off >>= 1) a = norm_combine(norm, a, __shfl_xor(a, off));
         if (sub == 0) {
-            nrm[unit * cap + n0] = a;
+            nrm[unit * cap + n0] = norm_finish(norm, a);
             if (pos) pos[unit * cap + n0] = meta.aux[b];
         }
     }
@@ -151,7 +151,7 @@ hipError_t launch_decode(int dtype, int head_dim, const void *q, const void *k, 
     hipLaunchKernelGGL((decode_logits_kernel<T, D>), grid, block, 0, st, static_cast<const T *>(q), \
                        static_cast<const T *>(k), static_cast<const T *>(v), static_cast<T *>(K),  \
                        static_cast<T *>(V), nrm, pos, ws_logit, ws_part, meta, g.n_heads, g.cap,   \
-                       chunks_alloc, g.scale_log2)
+                       chunks_alloc, g.scale_log2, g.norm)
     if (dtype == VATP_F32 && head_dim == 64) VATP_DEC(float, 64);
     else if (dtype == VATP_F32) VATP_DEC(float, 128);
     else if (head_dim == 64) VATP_DEC(bf16_t, 64);

@@ -1,4 +1,4 @@
-// l1 norm of every value row (the norm of the paper's Eq. 4), HBM-bound.
+// Norm of every value row (paper Eq. 4: l1; Table 2 ablation: l2, l-infinity), HBM-bound.
 // A row of head_dim elements is read by a group of lanes, 16 bytes per lane, so that a
 // wavefront's load covers consecutive rows as one contiguous span.
 #include "vatp_device.h"
@@ -8,7 +8,7 @@ namespace vatp {
 template <typename T, int D>
 __global__ __launch_bounds__(256) void l1norm_kernel(const T *__restrict__ V,
                                                      float *__restrict__ nrm, BatchMeta meta,
-                                                     int n_heads, int cap)
+                                                     int n_heads, int cap, int norm)
 {
     constexpr int kE = Elt<T>::kPer16B;          // elements per 16-byte lane load
     constexpr int kLanesPerRow = D / kE;         // 8, 16 or 32
@@ -34,11 +34,11 @@ __global__ __launch_bounds__(256) void l1norm_kernel(const T *__restrict__ V,
             float x[kE];
             Elt<T>::unpack(raw, x);
 #pragma unroll
-            for (int e = 0; e < kE; ++e) acc += fabsf(x[e]);
+            for (int e = 0; e < kE; ++e) acc = norm_accum(norm, acc, x[e]);
         }
 #pragma unroll
-        for (int off = kLanesPerRow / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
-        if (sub == 0 && r < len) nu[r] = acc;
+        for (int off = kLanesPerRow / 2; off > 0; off >>= 1) acc = norm_combine(norm, acc, __shfl_xor(acc, off));
+        if (sub == 0 && r < len) nu[r] = norm_finish(norm, acc);
     }
 }
 
@@ -49,7 +49,7 @@ hipError_t launch_l1norm(int dtype, int head_dim, const void *V, float *nrm,
     dim3 grid((g.max_len + 255) / 256, g.n_heads, g.batch), block(256);
 #define VATP_L1(T, D)                                                                        \
     hipLaunchKernelGGL((l1norm_kernel<T, D>), grid, block, 0, st, static_cast<const T *>(V), \
-                       nrm, meta, g.n_heads, g.cap)
+                       nrm, meta, g.n_heads, g.cap, g.norm)
     if (dtype == VATP_F32 && head_dim == 64) VATP_L1(float, 64);
     else if (dtype == VATP_F32) VATP_L1(float, 128);
     else if (head_dim == 64) VATP_L1(bf16_t, 64);

@@ -22,7 +22,18 @@ struct Geometry {
     int32_t n_sink, recent;
     float   scale_log2;            // c * log2(e): logits are kept in the base-2 domain
     int32_t max_len;               // max over the batch of len (decode: len + 1)
+    int32_t norm;                  // VATP_NORM_*: value-row norm of the importance (paper Eq. 4, Table 2)
 };
+
+// Value-row norm in three steps: lane-local accumulation, combination across the row's lanes,
+// final map.  l1 (the paper's metric), l2 and l-infinity (its ablation, Table 2).
+__device__ __forceinline__ float norm_accum(int kind, float acc, float x) {
+    return kind == VATP_NORM_L1 ? acc + fabsf(x) : kind == VATP_NORM_L2 ? fmaf(x, x, acc) : fmaxf(acc, fabsf(x));
+}
+__device__ __forceinline__ float norm_combine(int kind, float a, float b) {
+    return kind == VATP_NORM_LINF ? fmaxf(a, b) : a + b;
+}
+__device__ __forceinline__ float norm_finish(int kind, float a) { return kind == VATP_NORM_L2 ? sqrtf(a) : a; }
 
 constexpr int kDecodeChunk = 128;  // rows of one unit handled by one workgroup of the decode GEMV
 

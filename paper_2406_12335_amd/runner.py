@@ -17,10 +17,10 @@ from . import binding as B
 class PrunedKVCache:
     def __init__(self, batch: int, n_heads: int, head_dim: int, dtype: torch.dtype, n_sink: int, recent: int,
                  budgets: Sequence[int], device, cap_cache: Optional[int] = None, track_pos: bool = True,
-                 ctx=None):
+                 ctx=None, norm: int = 0):
         self.device = torch.device(device)
         self.batch, self.n_heads, self.head_dim, self.dtype = batch, n_heads, head_dim, dtype
-        self.n_sink, self.recent = n_sink, recent
+        self.n_sink, self.recent, self.norm = n_sink, recent, norm
         self.budgets = [int(x) for x in budgets]
         self.cap = int(cap_cache) if cap_cache else max(self.budgets) + 1
         self._own_ctx = ctx is None
@@ -35,7 +35,8 @@ class PrunedKVCache:
         self.kept_idx = mk(*shape, dt=torch.int32)
         self.cur = 0
         self.lens: List[int] = [0] * batch
-        self._p_dec = B.Params(batch, n_heads, head_dim, dtype, n_sink, recent, self.cap, self.lens, self.budgets)
+        self._p_dec = B.Params(batch, n_heads, head_dim, dtype, n_sink, recent, self.cap, self.lens, self.budgets,
+                               norm=norm)
         # sized for the fullest cache a decode step may meet (cap - 1 rows plus the new one)
         self._p_dec.set_len([self.cap - 1] * batch)
         nbytes = B.vatp_workspace_bytes(self.ctx, self._p_dec, B.CALL_DECODE_STEP)
@@ -52,7 +53,8 @@ class PrunedKVCache:
     def prefill_score(self, Q, K, V, lens: Sequence[int], stream=None):
         """vatp_prefill_score on [b, H, cap_p, d] prompt tensors; results kept in S_prompt / nrm_prompt."""
         b, H, cap_p, d = Q.shape
-        p = B.Params(b, H, d, self.dtype, self.n_sink, self.recent, cap_p, lens, self.budgets, cap_out=self.cap)
+        p = B.Params(b, H, d, self.dtype, self.n_sink, self.recent, cap_p, lens, self.budgets, cap_out=self.cap,
+                     norm=self.norm)
         need = B.vatp_workspace_bytes(self.ctx, p, B.CALL_PREFILL_SCORE)
         if getattr(self, "_ws_prompt", None) is None or self._ws_prompt.numel() < need:
             self._ws_prompt = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)

@@ -84,7 +84,7 @@ def _vec(t: torch.Tensor) -> np.ndarray:
 
 def run_trajectory(inp, device, units: Optional[Sequence[Tuple[int, int]]] = None, steps: Optional[int] = None,
                    n_sink: Optional[int] = None, check_every: int = 1, cap_cache: Optional[int] = None,
-                   full_prefill_check: bool = True) -> TrajectoryReport:
+                   full_prefill_check: bool = True, norm_kind: int = 0) -> TrajectoryReport:
     """Prompt pass -> prune -> decode/prune steps on the GPU, mirrored by OracleHead on the chosen units."""
     cfg = inp.cfg
     b, H, d = cfg.batch, cfg.n_heads, cfg.head_dim
@@ -98,7 +98,7 @@ def run_trajectory(inp, device, units: Optional[Sequence[Tuple[int, int]]] = Non
     dev = lambda t: t.to(device)
     Q, K, V = dev(inp.Q), dev(inp.K), dev(inp.V)
     qd, kd, vd = dev(inp.qd), dev(inp.kd), dev(inp.vd)
-    cache = PrunedKVCache(b, H, d, cfg.torch_dtype(), F, R, inp.budgets, device, cap_cache=cap_cache)
+    cache = PrunedKVCache(b, H, d, cfg.torch_dtype(), F, R, inp.budgets, device, cap_cache=cap_cache, norm=norm_kind)
     try:
         cache.prefill_score(Q, K, V, inp.lens)
         torch.cuda.synchronize()
@@ -110,9 +110,9 @@ def run_trajectory(inp, device, units: Optional[Sequence[Tuple[int, int]]] = Non
         S_or = orc.prefill_scores_units(Qh, Kh, [inp.lens[bb] for bb, _ in units]) if full_prefill_check else None
         for ui, (bb, hh) in enumerate(units):
             L = inp.lens[bb]
-            o = orc.OracleHead(d)
+            o = orc.OracleHead(d, norm_kind=norm_kind)
             o.K, o.V = Kh[ui, :L].copy(), _unit_rows(inp.V, bb, hh, L)
-            o.nrm = orc.l1norm(o.V)
+            o.nrm = orc.vnorm(o.V, norm_kind)
             o.pos = np.arange(L, dtype=np.int64)
             S_gpu = _unit_rows(cache.S_prompt, bb, hh, L)
             if full_prefill_check:

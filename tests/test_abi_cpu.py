@@ -89,3 +89,10 @@ def test_create_without_device_is_an_error_not_a_crash():
     lib = vatp.load()
     assert lib.vatp_create(None, 0) == binding.E_NULL
     lib.vatp_destroy(None)
+
+
+def test_validate_rejects_unknown_norm():
+    assert vatp.vatp_validate(_params(norm=3), 0) == binding.E_SHAPE
+    assert vatp.vatp_validate(_params(norm=-1), 0) == binding.E_SHAPE
+    for kind in (vatp.NORM_L1, vatp.NORM_L2, vatp.NORM_LINF):
+        assert vatp.vatp_validate(_params(norm=kind), 0) == binding.OK

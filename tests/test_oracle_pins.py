@@ -273,3 +273,34 @@ def test_tail_scores_equal_the_tail_of_the_full_pass():
     np.testing.assert_allclose(orc.prefill_scores_tail(Q, K, 60), full[60:], rtol=1e-13)
     np.testing.assert_array_equal(orc.prefill_scores_tail(Q, K, 0), full)
     np.testing.assert_array_equal(orc.prefill_scores_units(Q[None], K[None], [L])[0], full)
+
+
+# ---------------------------------------------------------------- norm ablation (Table 2)
+
+def test_value_norms_match_numpy_and_their_inequalities():
+    rng = np.random.default_rng(41)
+    V = _rand(rng, 50, 16) * np.exp(_rand(rng, 50, 1))
+    n1, n2, ninf = orc.vnorm(V, 0), orc.vnorm(V, 1), orc.vnorm(V, 2)
+    np.testing.assert_array_equal(n1, orc.l1norm(V))
+    np.testing.assert_allclose(n1, np.linalg.norm(V, 1, axis=1), rtol=1e-14)
+    np.testing.assert_allclose(n2, np.linalg.norm(V, 2, axis=1), rtol=1e-14)
+    np.testing.assert_allclose(ninf, np.linalg.norm(V, np.inf, axis=1), rtol=0)
+    assert np.all(ninf <= n2 * (1 + 1e-15)) and np.all(n2 <= n1 * (1 + 1e-15)) and np.all(n1 <= 4.0 * n2 * (1 + 1e-15))
+    onehot = np.eye(16)[[3, 7]] * np.array([[2.5], [-4.0]])
+    for kind in (0, 1, 2):
+        np.testing.assert_array_equal(orc.vnorm(onehot, kind), [2.5, 4.0])      # all three agree on one-hot rows
+
+
+def test_norm_choice_changes_the_kept_set_only_through_the_norm():
+    rng = np.random.default_rng(42)
+    L, d, B, F, R = 120, 8, 40, 2, 8
+    Q, K, V = _rand(rng, L, d) * 2, _rand(rng, L, d) * 2, _rand(rng, L, d) * np.exp(_rand(rng, L, 1))
+    sets = []
+    for kind in (0, 1, 2):
+        h = orc.OracleHead(d, norm_kind=kind)
+        h.prefill(Q, K, V)
+        np.testing.assert_array_equal(h.nrm, orc.vnorm(V, kind))
+        kept = h.prune(B, F, R)
+        assert kept.tolist() == orc.select(orc.importance(orc.prefill_scores(Q, K), orc.vnorm(V, kind)), B, F, R).tolist()
+        sets.append(kept.tolist())
+    assert sets[0] != sets[2]                       # l1 and l-infinity rank differently on this data
