@@ -103,6 +103,17 @@ vatp_status vatp_prefill_score(vatp_ctx *ctx, const vatp_params *p,
                                void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * The same prompt pass when the row log-sum-exp of the causal softmax is already known, as a
+ * fused attention kernel returns it: lse[j] = ln sum_{i<=j} exp(c <q_j, k_i>), device float32
+ * [batch, n_heads, cap], rows < len[b].  The row-statistics pass is skipped (half of the
+ * matrix work of Eq. 1/2); S and nrm are as above.  lse must be finite for rows < len[b].
+ */
+vatp_status vatp_prefill_score_lse(vatp_ctx *ctx, const vatp_params *p,
+                                   const void *Q, const void *K, const void *V, const float *lse,
+                                   float *S, float *nrm,
+                                   void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * One decode step (Eq. 2 taken incrementally; order of operations as in Fig. 2).
  * For every unit with n0 = len[b] rows: the new token's k, v are stored as row n0 of the
  * K, V caches, nrm[n0] = |v| (same norm), pos[n0] = new_pos[b]; the new query attends over the

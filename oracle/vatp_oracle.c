@@ -58,6 +58,46 @@ void vatp_oracle_prefill_scores(const double *Q, const double *K, int64_t L, int
 }
 
 /*
+ * Row log-sum-exp of the causal softmax of Eq. 1, natural logarithm:
+ *     lse_j = ln sum_{i<=j} exp(c <q_j, k_i>),
+ * the by-product a fused attention kernel hands back.  Q, K: [L, d] -> lse: [L].
+ */
+void vatp_oracle_row_lse(const double *Q, const double *K, int64_t L, int64_t d, double c,
+                         double *lse, double *scratch)
+{
+    for (int64_t j = 0; j < L; ++j) {
+        double m = -INFINITY;
+        for (int64_t i = 0; i <= j; ++i) {
+            double dot = 0.0;
+            for (int64_t x = 0; x < d; ++x) dot += Q[j * d + x] * K[i * d + x];
+            scratch[i] = c * dot;
+            if (scratch[i] > m) m = scratch[i];
+        }
+        double denom = 0.0;
+        for (int64_t i = 0; i <= j; ++i) denom += exp(scratch[i] - m);
+        lse[j] = m + log(denom);
+    }
+}
+
+/*
+ * Eq. 2 after the prompt when the normalisers are given:  a_i^j = exp(c <q_j,k_i> - lse_j),
+ *     S_i = sum_{j=i}^{L-1} a_i^j .
+ */
+void vatp_oracle_prefill_scores_given_lse(const double *Q, const double *K, const double *lse,
+                                          int64_t L, int64_t d, double c, double *S)
+{
+    for (int64_t i = 0; i < L; ++i) {
+        double s = 0.0;
+        for (int64_t j = i; j < L; ++j) {
+            double dot = 0.0;
+            for (int64_t x = 0; x < d; ++x) dot += Q[j * d + x] * K[i * d + x];
+            s += exp(c * dot - lse[j]);
+        }
+        S[i] = s;
+    }
+}
+
+/*
  * One decode step of Eq. 2: the new query attends over all n rows currently in the
  * cache (the row of the new token included), and every row's accumulated score
  * grows by the attention weight it received:  S_r += a_r.

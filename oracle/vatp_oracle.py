@@ -49,6 +49,10 @@ def lib():
         L.vatp_oracle_prefill_scores.restype = None
         L.vatp_oracle_prefill_scores_from.argtypes = [_f64p, _f64p, _i64, _i64, ctypes.c_double, _i64, _f64p, _f64p]
         L.vatp_oracle_prefill_scores_from.restype = None
+        L.vatp_oracle_row_lse.argtypes = [_f64p, _f64p, _i64, _i64, ctypes.c_double, _f64p, _f64p]
+        L.vatp_oracle_row_lse.restype = None
+        L.vatp_oracle_prefill_scores_given_lse.argtypes = [_f64p, _f64p, _f64p, _i64, _i64, ctypes.c_double, _f64p]
+        L.vatp_oracle_prefill_scores_given_lse.restype = None
         L.vatp_oracle_decode_scores.argtypes = [_f64p, _f64p, _i64, _i64, ctypes.c_double, _f64p, _f64p, _f64p]
         L.vatp_oracle_decode_scores.restype = None
         L.vatp_oracle_l1norm.argtypes = [_f64p, _i64, _i64, _f64p]
@@ -118,6 +122,25 @@ def prefill_scores_units(Q, K, lens, c: Optional[float] = None) -> np.ndarray:
     S = np.zeros((units, cap), dtype=np.float64)
     lib().vatp_oracle_prefill_scores_units(_p(Q), _p(K), units, cap, lens.ctypes.data_as(_i64p), d,
                                            default_scale(d) if c is None else c, _p(S))
+    return S
+
+
+def row_lse(Q, K, c: Optional[float] = None) -> np.ndarray:
+    """lse_j = ln sum_{i<=j} exp(c <q_j, k_i>): what a fused attention kernel returns per query row."""
+    Q, K = _f64(Q), _f64(K)
+    L, d = Q.shape
+    out = np.zeros(L, dtype=np.float64)
+    scratch = np.zeros(max(L, 1), dtype=np.float64)
+    lib().vatp_oracle_row_lse(_p(Q), _p(K), L, d, default_scale(d) if c is None else c, _p(out), _p(scratch))
+    return out
+
+
+def prefill_scores_given_lse(Q, K, lse, c: Optional[float] = None) -> np.ndarray:
+    """S_i = sum_{j>=i} exp(c <q_j,k_i> - lse_j): Eq. 2 after the prompt with the row normalisers given."""
+    Q, K, lse = _f64(Q), _f64(K), _f64(lse)
+    L, d = Q.shape
+    S = np.zeros(L, dtype=np.float64)
+    lib().vatp_oracle_prefill_scores_given_lse(_p(Q), _p(K), _p(lse), L, d, default_scale(d) if c is None else c, _p(S))
     return S
 
 

@@ -23,7 +23,7 @@ VATP_MAX_BATCH, VATP_MAX_UNITS = 64, 16384
 OK, E_NULL, E_SHAPE, E_DTYPE, E_BUDGET, E_WORKSPACE, E_DEVICE = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = ("vatp_create", "vatp_destroy", "vatp_strerror", "vatp_validate", "vatp_workspace_bytes",
-           "vatp_prefill_score", "vatp_decode_step", "vatp_select_compact")
+           "vatp_prefill_score", "vatp_prefill_score_lse", "vatp_decode_step", "vatp_select_compact")
 
 
 class VatpError(RuntimeError):
@@ -66,6 +66,8 @@ def load() -> ctypes.CDLL:
     L.vatp_workspace_bytes.restype = ctypes.c_size_t
     L.vatp_prefill_score.argtypes = [_vp, pp] + [_vp] * 5 + [_vp, ctypes.c_size_t, _vp]
     L.vatp_prefill_score.restype = ctypes.c_int
+    L.vatp_prefill_score_lse.argtypes = [_vp, pp] + [_vp] * 6 + [_vp, ctypes.c_size_t, _vp]
+    L.vatp_prefill_score_lse.restype = ctypes.c_int
     L.vatp_decode_step.argtypes = [_vp, pp] + [_vp] * 8 + [ctypes.POINTER(ctypes.c_int32), _vp, ctypes.c_size_t, _vp]
     L.vatp_decode_step.restype = ctypes.c_int
     L.vatp_select_compact.argtypes = [_vp, pp] + [_vp] * 11 + [_vp, ctypes.c_size_t, _vp]
@@ -142,6 +144,12 @@ def vatp_prefill_score(ctx, p: Params, Q, K, V, S, nrm, ws, stream=None) -> None
     _check(load().vatp_prefill_score(ctx, p.ref(), _ptr(Q), _ptr(K), _ptr(V), _ptr(S), _ptr(nrm),
                                      _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0,
                                      _stream(stream)), "vatp_prefill_score")
+
+
+def vatp_prefill_score_lse(ctx, p: Params, Q, K, V, lse, S, nrm, ws, stream=None) -> None:
+    _check(load().vatp_prefill_score_lse(ctx, p.ref(), _ptr(Q), _ptr(K), _ptr(V), _ptr(lse), _ptr(S), _ptr(nrm),
+                                         _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0,
+                                         _stream(stream)), "vatp_prefill_score_lse")
 
 
 def vatp_decode_step(ctx, p: Params, q, k, v, K, V, S, nrm, pos, new_pos: Optional[Sequence[int]], ws,

@@ -143,11 +143,15 @@ size_t vatp_workspace_bytes(const vatp_ctx *, const vatp_params *p, int which_ca
     }
 }
 
-vatp_status vatp_prefill_score(vatp_ctx *ctx, const vatp_params *p, const void *Q, const void *K,
-                               const void *V, float *S, float *nrm, void *ws, size_t ws_bytes,
+}  // extern "C" (reopened below)
+
+namespace {
+
+vatp_status prefill_score_impl(vatp_ctx *ctx, const vatp_params *p, const void *Q, const void *K, const void *V,
+                               const float *lse, bool have_lse, float *S, float *nrm, void *ws, size_t ws_bytes,
                                void *hip_stream)
 {
-    if (!ctx || !Q || !K || !V || !S || !nrm) return VATP_E_NULL;
+    if (!ctx || !Q || !K || !V || !S || !nrm || (have_lse && !lse)) return VATP_E_NULL;
     const vatp_status st = check_params(p, VATP_CALL_PREFILL_SCORE);
     if (st != VATP_OK) return st;
     if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16)) return VATP_E_SHAPE;
@@ -156,14 +160,34 @@ vatp_status vatp_prefill_score(vatp_ctx *ctx, const vatp_params *p, const void *
     Prepared pr;
     prepare(p, VATP_CALL_PREFILL_SCORE, nullptr, &pr);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    float *lse2 = static_cast<float *>(ws);
     if (launch_l1norm(p->dtype, p->head_dim, V, nrm, pr.meta, pr.g, stream) != hipSuccess) return VATP_E_DEVICE;
+    if (have_lse && launch_lse_to_base2(lse, lse2, pr.meta, pr.g, stream) != hipSuccess) return VATP_E_DEVICE;
     // bf16 with head_dim 128 runs on the matrix cores; everything else on the fp32 FMA kernels
     const hipError_t e = (p->dtype == VATP_BF16 && p->head_dim == 128)
-                             ? launch_prefill_mfma(Q, K, S, static_cast<float *>(ws), pr.meta, pr.g, stream)
-                             : launch_prefill_generic(p->dtype, p->head_dim, Q, K, S, static_cast<float *>(ws),
-                                                      pr.meta, pr.g, stream);
+                             ? launch_prefill_mfma(Q, K, S, lse2, have_lse, pr.meta, pr.g, stream)
+                             : launch_prefill_generic(p->dtype, p->head_dim, Q, K, S, lse2, have_lse, pr.meta, pr.g,
+                                                      stream);
     if (e != hipSuccess) return VATP_E_DEVICE;
     return VATP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+vatp_status vatp_prefill_score(vatp_ctx *ctx, const vatp_params *p, const void *Q, const void *K,
+                               const void *V, float *S, float *nrm, void *ws, size_t ws_bytes,
+                               void *hip_stream)
+{
+    return prefill_score_impl(ctx, p, Q, K, V, nullptr, false, S, nrm, ws, ws_bytes, hip_stream);
+}
+
+vatp_status vatp_prefill_score_lse(vatp_ctx *ctx, const vatp_params *p, const void *Q, const void *K,
+                                   const void *V, const float *lse, float *S, float *nrm, void *ws,
+                                   size_t ws_bytes, void *hip_stream)
+{
+    return prefill_score_impl(ctx, p, Q, K, V, lse, true, S, nrm, ws, ws_bytes, hip_stream);
 }
 
 vatp_status vatp_decode_step(vatp_ctx *ctx, const vatp_params *p, const void *q, const void *k,

@@ -181,19 +181,40 @@ __global__ __launch_bounds__(256) void prefill_colsum_generic(const T *__restric
     }
 }
 
+// Row log-sum-exp handed in by an upstream attention kernel (natural logarithm) -> base 2.
+__global__ __launch_bounds__(256) void lse_to_base2_kernel(const float *__restrict__ lse,
+                                                           float *__restrict__ lse2, BatchMeta meta,
+                                                           int n_heads, int cap)
+{
+    const int b = blockIdx.z, h = blockIdx.y;
+    const int r = blockIdx.x * 256 + threadIdx.x;
+    const size_t unit = static_cast<size_t>(b) * n_heads + h;
+    if (r < meta.len[b]) lse2[unit * cap + r] = lse[unit * cap + r] * 1.44269504088896340736f;
+}
+
 }  // namespace
 
+hipError_t launch_lse_to_base2(const float *lse, float *lse2, const BatchMeta &meta, const Geometry &g,
+                               hipStream_t st)
+{
+    if (g.max_len <= 0) return hipSuccess;
+    hipLaunchKernelGGL(lse_to_base2_kernel, dim3((g.max_len + 255) / 256, g.n_heads, g.batch), dim3(256), 0, st, lse,
+                       lse2, meta, g.n_heads, g.cap);
+    return hipGetLastError();
+}
+
 hipError_t launch_prefill_generic(int dtype, int head_dim, const void *Q, const void *K,
-                                  float *S, float *lse2, const BatchMeta &meta,
+                                  float *S, float *lse2, bool have_lse, const BatchMeta &meta,
                                   const Geometry &g, hipStream_t st)
 {
     if (g.max_len <= 0) return hipSuccess;
     dim3 grid((g.max_len + kTile - 1) / kTile, g.n_heads, g.batch), block(256);
 #define VATP_PF(T, D)                                                                          \
     do {                                                                                       \
-        hipLaunchKernelGGL((prefill_rowstat_generic<T, D>), grid, block, 0, st,                \
-                           static_cast<const T *>(Q), static_cast<const T *>(K), lse2, meta,   \
-                           g.n_heads, g.cap, g.scale_log2);                                    \
+        if (!have_lse)                                                                         \
+            hipLaunchKernelGGL((prefill_rowstat_generic<T, D>), grid, block, 0, st,            \
+                               static_cast<const T *>(Q), static_cast<const T *>(K), lse2,     \
+                               meta, g.n_heads, g.cap, g.scale_log2);                          \
         hipLaunchKernelGGL((prefill_colsum_generic<T, D>), grid, block, 0, st,                 \
                            static_cast<const T *>(Q), static_cast<const T *>(K), lse2, S,      \
                            meta, g.n_heads, g.cap, g.scale_log2);                              \

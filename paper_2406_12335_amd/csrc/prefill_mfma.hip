@@ -404,7 +404,7 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t *__restr
 
 }  // namespace
 
-hipError_t launch_prefill_mfma(const void *Q, const void *K, float *S, float *lse2,
+hipError_t launch_prefill_mfma(const void *Q, const void *K, float *S, float *lse2, bool have_lse,
                                const BatchMeta &meta, const Geometry &g, hipStream_t st)
 {
     if (g.max_len <= 0) return hipSuccess;
@@ -412,9 +412,10 @@ hipError_t launch_prefill_mfma(const void *Q, const void *K, float *S, float *ls
     const int n_units = g.batch * g.n_heads;
     const int n_pairs = (n_blocks + 1) / 2;
     dim3 grid(8u * n_pairs * ((n_units + 7) / 8)), block(256);
-    hipLaunchKernelGGL((prefill_mfma_kernel<false>), grid, block, 0, st, static_cast<const bf16_t *>(Q),
-                       static_cast<const bf16_t *>(K), lse2, S, meta, g.n_heads, n_units, g.cap, n_blocks,
-                       g.scale_log2);
+    if (!have_lse)      // row statistics are computed here unless the caller supplied them
+        hipLaunchKernelGGL((prefill_mfma_kernel<false>), grid, block, 0, st, static_cast<const bf16_t *>(Q),
+                           static_cast<const bf16_t *>(K), lse2, S, meta, g.n_heads, n_units, g.cap, n_blocks,
+                           g.scale_log2);
     hipLaunchKernelGGL((prefill_mfma_kernel<true>), grid, block, 0, st, static_cast<const bf16_t *>(Q),
                        static_cast<const bf16_t *>(K), lse2, S, meta, g.n_heads, n_units, g.cap, n_blocks,
                        g.scale_log2);

@@ -64,10 +64,13 @@ hipError_t launch_l1norm(int dtype, int head_dim, const void *V, float *nrm,
                          const BatchMeta &meta, const Geometry &g, hipStream_t st);
 
 hipError_t launch_prefill_generic(int dtype, int head_dim, const void *Q, const void *K,
-                                  float *S, float *lse2, const BatchMeta &meta,
+                                  float *S, float *lse2, bool have_lse, const BatchMeta &meta,
                                   const Geometry &g, hipStream_t st);
 
-hipError_t launch_prefill_mfma(const void *Q, const void *K, float *S, float *lse2,
+hipError_t launch_lse_to_base2(const float *lse, float *lse2, const BatchMeta &meta, const Geometry &g,
+                               hipStream_t st);
+
+hipError_t launch_prefill_mfma(const void *Q, const void *K, float *S, float *lse2, bool have_lse,
                                const BatchMeta &meta, const Geometry &g, hipStream_t st);
 
 hipError_t launch_decode(int dtype, int head_dim, const void *q, const void *k, const void *v,

@@ -27,3 +27,40 @@ def test_norm_ablation_trajectories(gpu_device, norm_kind, dtype, d):
     _say("norm kind %d %s d=%d" % (norm_kind, dtype, d))
     rep = parity.run_trajectory(vs.make_inputs(cfg, seed=50 + norm_kind), gpu_device, norm_kind=norm_kind)
     _say("report %r" % rep)
+
+
+@pytest.mark.parametrize("dtype,d,lens", [("bf16", 128, [700, 64, 257]), ("fp32", 64, [130, 1, 99]), ("bf16", 64, [300, 5, 77])])
+def test_prompt_scores_from_given_row_lse(gpu_device, dtype, d, lens):
+    """vatp_prefill_score_lse: only the column-sum pass runs; the oracle supplies ln-sum-exp per row."""
+    cfg = vs.scaled(vs.CONFIGS["llama7b_layer"], batch=len(lens), n_heads=2, head_dim=d, dtype=dtype,
+                    prompt_len=max(lens), decode_steps=0)
+    inp = vs.make_inputs(cfg, seed=61)
+    inp.lens = lens
+    _say("lse-in %s d=%d lens=%s" % (dtype, d, lens))
+    cap = max(lens)
+    lse = torch.zeros(len(lens), 2, cap)
+    want = {}
+    for b, L in enumerate(lens):
+        for h in range(2):
+            Qh, Kh = inp.Q[b, h, :L].double().numpy(), inp.K[b, h, :L].double().numpy()
+            l = orc.row_lse(Qh, Kh)
+            lse[b, h, :L] = torch.from_numpy(l).float()
+            # the GPU is handed the float32-rounded normalisers: so is the oracle
+            want[(b, h)] = orc.prefill_scores_given_lse(Qh, Kh, lse[b, h, :L].double().numpy())
+    dev = gpu_device
+    ctx = vatp.vatp_create(0)
+    try:
+        p = vatp.Params(len(lens), 2, d, cfg.torch_dtype(), 0, 0, cap, lens, None)
+        ws = torch.empty(max(256, vatp.vatp_workspace_bytes(ctx, p, vatp.CALL_PREFILL_SCORE)), dtype=torch.uint8, device=dev)
+        S = torch.full((len(lens), 2, cap), -3.0, device=dev)
+        nrm = torch.full((len(lens), 2, cap), -3.0, device=dev)
+        vatp.vatp_prefill_score_lse(ctx, p, inp.Q.to(dev), inp.K.to(dev), inp.V.to(dev), lse.to(dev), S, nrm, ws)
+        torch.cuda.synchronize()
+    finally:
+        vatp.vatp_destroy(ctx)
+    rtol = parity.rtol_for(cfg.torch_dtype())
+    for b, L in enumerate(lens):
+        for h in range(2):
+            parity.assert_scores_close(S[b, h, :L].cpu().numpy(), want[(b, h)], rtol, "S from lse (%d,%d)" % (b, h))
+            parity.assert_scores_close(nrm[b, h, :L].cpu().numpy(), orc.l1norm(inp.V[b, h, :L].double().numpy()), rtol, "nrm")
+        assert torch.all(S[b, :, L:] == -3.0)

@@ -304,3 +304,22 @@ def test_norm_choice_changes_the_kept_set_only_through_the_norm():
         assert kept.tolist() == orc.select(orc.importance(orc.prefill_scores(Q, K), orc.vnorm(V, kind)), B, F, R).tolist()
         sets.append(kept.tolist())
     assert sets[0] != sets[2]                       # l1 and l-infinity rank differently on this data
+
+
+# ---------------------------------------------------------------- scores from given row normalisers
+
+def test_row_lse_matches_torch_logsumexp_and_closes_the_loop():
+    g = torch.Generator().manual_seed(51)
+    L, d = 150, 16
+    Q = torch.randn(L, d, generator=g, dtype=torch.float64) * 1.7
+    K = torch.randn(L, d, generator=g, dtype=torch.float64)
+    logits = (Q @ K.T) / math.sqrt(d)
+    logits = logits.masked_fill(torch.triu(torch.ones(L, L, dtype=torch.bool), 1), float("-inf"))
+    lse = orc.row_lse(Q.numpy(), K.numpy())
+    np.testing.assert_allclose(lse, torch.logsumexp(logits, dim=-1).numpy(), rtol=1e-13)
+    S = orc.prefill_scores_given_lse(Q.numpy(), K.numpy(), lse)
+    np.testing.assert_allclose(S, orc.prefill_scores(Q.numpy(), K.numpy()), rtol=1e-12)
+    np.testing.assert_allclose(S, torch.exp(logits - torch.from_numpy(lse)[:, None]).sum(0).numpy(), rtol=1e-12)
+    # a shifted normaliser scales every weight of that row: S is linear in exp(-lse)
+    S2 = orc.prefill_scores_given_lse(Q.numpy(), K.numpy(), lse + math.log(2.0))
+    np.testing.assert_allclose(S2, S / 2.0, rtol=1e-12)
