@@ -52,7 +52,8 @@ typedef enum {
 
 enum { VATP_F32 = 0, VATP_BF16 = 1 };
 enum { VATP_NORM_L1 = 0, VATP_NORM_L2 = 1, VATP_NORM_LINF = 2 };
-enum { VATP_CALL_PREFILL_SCORE = 0, VATP_CALL_DECODE_STEP = 1, VATP_CALL_SELECT_COMPACT = 2 };
+enum { VATP_CALL_PREFILL_SCORE = 0, VATP_CALL_DECODE_STEP = 1, VATP_CALL_SELECT_COMPACT = 2,
+       VATP_CALL_DECODE_ATTEND_STEP = 3 };
 
 typedef struct {
     int32_t batch;          /* 1 .. VATP_MAX_BATCH                                         */
@@ -80,7 +81,7 @@ const char *vatp_strerror(vatp_status st);
 
 /*
  * Checks `p` for call `which_call` (a VATP_CALL_* value) exactly as that call does before
- * it launches anything; touches no device.  For VATP_CALL_DECODE_STEP, len[b] + 1 <= cap
+ * it launches anything; touches no device.  For the two decode calls, len[b] + 1 <= cap
  * is required (room for the appended row).
  */
 vatp_status vatp_validate(const vatp_params *p, int which_call);
@@ -127,6 +128,19 @@ vatp_status vatp_decode_step(vatp_ctx *ctx, const vatp_params *p,
                              void *K, void *V, float *S, float *nrm, int32_t *pos,
                              const int32_t *new_pos,
                              void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * vatp_decode_step that also returns the attention output of the new token (Eq. 1),
+ *     out[x] = sum_{r<=n0} a_r V[r][x],
+ * from the same pass over the cache (the probabilities are already there; this adds one read
+ * of the V rows).  out: device float32 [batch, n_heads, head_dim].  Workspace size:
+ * vatp_workspace_bytes(..., VATP_CALL_DECODE_ATTEND_STEP).
+ */
+vatp_status vatp_decode_attend_step(vatp_ctx *ctx, const vatp_params *p,
+                                    const void *q, const void *k, const void *v,
+                                    void *K, void *V, float *S, float *nrm, int32_t *pos,
+                                    const int32_t *new_pos, float *out,
+                                    void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
  * Budgeted selection and compaction (Eq. 4; forced prefix, budget and local window from

@@ -126,6 +126,40 @@ void vatp_oracle_decode_scores(const double *q, const double *K, int64_t n, int6
     }
 }
 
+/*
+ * Attention output of one query over a cache of n rows (Eq. 1):
+ *     out[x] = sum_r a_r V[r][x],   a = softmax_r(c <q, K_r>).
+ * q: [d].  K, V: [n, d].  out: [d].  abs_out (may be NULL): sum_r a_r |V[r][x]|, the scale a
+ * comparison of out should be judged against, since the signed sum can cancel.
+ */
+void vatp_oracle_attention_output(const double *q, const double *K, const double *V, int64_t n,
+                                  int64_t d, double c, double *out, double *abs_out,
+                                  double *scratch)
+{
+    double m = -INFINITY;
+    for (int64_t r = 0; r < n; ++r) {
+        double dot = 0.0;
+        for (int64_t x = 0; x < d; ++x) dot += q[x] * K[r * d + x];
+        scratch[r] = c * dot;
+        if (scratch[r] > m) m = scratch[r];
+    }
+    double denom = 0.0;
+    for (int64_t r = 0; r < n; ++r) {
+        scratch[r] = exp(scratch[r] - m);
+        denom += scratch[r];
+    }
+    for (int64_t x = 0; x < d; ++x) {
+        double s = 0.0, sa = 0.0;
+        for (int64_t r = 0; r < n; ++r) {
+            double a = scratch[r] / denom;
+            s += a * V[r * d + x];
+            sa += a * fabs(V[r * d + x]);
+        }
+        out[x] = s;
+        if (abs_out) abs_out[x] = sa;
+    }
+}
+
 /* l1 norm of each value row (the norm used in Eq. 4).  V: [n, d] -> nrm: [n]. */
 void vatp_oracle_l1norm(const double *V, int64_t n, int64_t d, double *nrm)
 {

@@ -55,6 +55,8 @@ def lib():
         L.vatp_oracle_prefill_scores_given_lse.restype = None
         L.vatp_oracle_decode_scores.argtypes = [_f64p, _f64p, _i64, _i64, ctypes.c_double, _f64p, _f64p, _f64p]
         L.vatp_oracle_decode_scores.restype = None
+        L.vatp_oracle_attention_output.argtypes = [_f64p, _f64p, _f64p, _i64, _i64, ctypes.c_double, _f64p, _f64p, _f64p]
+        L.vatp_oracle_attention_output.restype = None
         L.vatp_oracle_l1norm.argtypes = [_f64p, _i64, _i64, _f64p]
         L.vatp_oracle_l1norm.restype = None
         L.vatp_oracle_vnorm.argtypes = [_f64p, _i64, _i64, ctypes.c_int, _f64p]
@@ -155,6 +157,17 @@ def decode_scores(q, K, S, c: Optional[float] = None):
     lib().vatp_oracle_decode_scores(_p(q), _p(K), n, d, default_scale(d) if c is None else c,
                                     _p(S), _p(a), _p(scratch))
     return S, a
+
+
+def attention_output(q, K, V, c: Optional[float] = None):
+    """Eq. 1 for one query: (sum_r a_r V_r, sum_r a_r |V_r|) over the n rows of K, V."""
+    q, K, V = _f64(q), _f64(K), _f64(V)
+    n, d = K.shape
+    out, abs_out = np.zeros(d), np.zeros(d)
+    scratch = np.zeros(max(n, 1), dtype=np.float64)
+    lib().vatp_oracle_attention_output(_p(q), _p(K), _p(V), n, d, default_scale(d) if c is None else c,
+                                       _p(out), _p(abs_out), _p(scratch))
+    return out, abs_out
 
 
 def l1norm(V) -> np.ndarray:

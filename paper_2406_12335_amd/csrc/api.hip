@@ -25,7 +25,7 @@ vatp_status check_params(const vatp_params *p, int which_call)
 {
     if (!p || !p->len) return VATP_E_NULL;
     if (which_call == VATP_CALL_SELECT_COMPACT && !p->budget) return VATP_E_NULL;
-    if (which_call < VATP_CALL_PREFILL_SCORE || which_call > VATP_CALL_SELECT_COMPACT) return VATP_E_SHAPE;
+    if (which_call < VATP_CALL_PREFILL_SCORE || which_call > VATP_CALL_DECODE_ATTEND_STEP) return VATP_E_SHAPE;
     if (p->dtype != VATP_F32 && p->dtype != VATP_BF16) return VATP_E_DTYPE;
     if (p->batch < 1 || p->batch > VATP_MAX_BATCH || p->n_heads < 1) return VATP_E_SHAPE;
     if (static_cast<int64_t>(p->batch) * p->n_heads > VATP_MAX_UNITS) return VATP_E_SHAPE;
@@ -42,7 +42,8 @@ vatp_status check_params(const vatp_params *p, int which_call)
     for (int b = 0; b < p->batch; ++b) {
         const int len = p->len[b];
         if (len < 0 || len > p->cap) return VATP_E_SHAPE;
-        if (which_call == VATP_CALL_DECODE_STEP && len + 1 > p->cap) return VATP_E_SHAPE;
+        const bool decode = which_call == VATP_CALL_DECODE_STEP || which_call == VATP_CALL_DECODE_ATTEND_STEP;
+        if (decode && len + 1 > p->cap) return VATP_E_SHAPE;
         if (which_call == VATP_CALL_SELECT_COMPACT) {
             const int B = p->budget[b];
             if (B < 0 || B < p->n_sink + p->recent) return VATP_E_BUDGET;
@@ -71,7 +72,7 @@ void prepare(const vatp_params *p, int which_call, const int32_t *new_pos, Prepa
         const int len = p->len[b];
         out->meta.len[b] = len;
         int extent = len;
-        if (which_call == VATP_CALL_DECODE_STEP) {
+        if (which_call == VATP_CALL_DECODE_STEP || which_call == VATP_CALL_DECODE_ATTEND_STEP) {
             out->meta.aux[b] = new_pos ? new_pos[b] : 0;
             extent = len + 1;
         } else if (which_call == VATP_CALL_SELECT_COMPACT) {
@@ -138,6 +139,11 @@ size_t vatp_workspace_bytes(const vatp_ctx *, const vatp_params *p, int which_ca
         const size_t chunks = (static_cast<size_t>(p->cap) + kDecodeChunk - 1) / kDecodeChunk;
         return align_up(units * p->cap * sizeof(float)) + align_up(units * chunks * sizeof(float2));
     }
+    case VATP_CALL_DECODE_ATTEND_STEP: {    // ... + per-chunk partial attention outputs [units, chunks, d]
+        const size_t chunks = (static_cast<size_t>(p->cap) + kDecodeChunk - 1) / kDecodeChunk;
+        return align_up(units * p->cap * sizeof(float)) + align_up(units * chunks * sizeof(float2)) +
+               align_up(units * chunks * p->head_dim * sizeof(float));
+    }
     default:
         return 0;
     }
@@ -190,26 +196,57 @@ vatp_status vatp_prefill_score_lse(vatp_ctx *ctx, const vatp_params *p, const vo
     return prefill_score_impl(ctx, p, Q, K, V, lse, true, S, nrm, ws, ws_bytes, hip_stream);
 }
 
+}  // extern "C" (reopened below)
+
+namespace {
+
+vatp_status decode_step_impl(vatp_ctx *ctx, const vatp_params *p, int which_call, const void *q, const void *k,
+                             const void *v, void *K, void *V, float *S, float *nrm, int32_t *pos,
+                             const int32_t *new_pos, float *out, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    if (!ctx || !q || !k || !v || !K || !V || !S || !nrm) return VATP_E_NULL;
+    if (which_call == VATP_CALL_DECODE_ATTEND_STEP && !out) return VATP_E_NULL;
+    if (pos && !new_pos) return VATP_E_NULL;
+    const vatp_status st = check_params(p, which_call);
+    if (st != VATP_OK) return st;
+    if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(K, 16) || misaligned(V, 16))
+        return VATP_E_SHAPE;
+    const size_t need = vatp_workspace_bytes(ctx, p, which_call);
+    if (!ws || ws_bytes < need || misaligned(ws, kAlign)) return VATP_E_WORKSPACE;
+    Prepared pr;
+    prepare(p, which_call, pos ? new_pos : nullptr, &pr);
+    const size_t units = static_cast<size_t>(p->batch) * p->n_heads;
+    const size_t chunks = (static_cast<size_t>(p->cap) + kDecodeChunk - 1) / kDecodeChunk;
+    char *base = static_cast<char *>(ws);
+    float *ws_logit = reinterpret_cast<float *>(base);
+    float2 *ws_part = reinterpret_cast<float2 *>(base + align_up(units * p->cap * sizeof(float)));
+    float *ws_out = reinterpret_cast<float *>(base + align_up(units * p->cap * sizeof(float)) +
+                                              align_up(units * chunks * sizeof(float2)));
+    if (launch_decode(p->dtype, p->head_dim, q, k, v, K, V, S, nrm, pos, ws_logit, ws_part, out ? ws_out : nullptr,
+                      out, pr.meta, pr.g, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return VATP_E_DEVICE;
+    return VATP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
 vatp_status vatp_decode_step(vatp_ctx *ctx, const vatp_params *p, const void *q, const void *k,
                              const void *v, void *K, void *V, float *S, float *nrm, int32_t *pos,
                              const int32_t *new_pos, void *ws, size_t ws_bytes, void *hip_stream)
 {
-    if (!ctx || !q || !k || !v || !K || !V || !S || !nrm) return VATP_E_NULL;
-    if (pos && !new_pos) return VATP_E_NULL;
-    const vatp_status st = check_params(p, VATP_CALL_DECODE_STEP);
-    if (st != VATP_OK) return st;
-    if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(K, 16) || misaligned(V, 16))
-        return VATP_E_SHAPE;
-    const size_t need = vatp_workspace_bytes(ctx, p, VATP_CALL_DECODE_STEP);
-    if (!ws || ws_bytes < need || misaligned(ws, kAlign)) return VATP_E_WORKSPACE;
-    Prepared pr;
-    prepare(p, VATP_CALL_DECODE_STEP, pos ? new_pos : nullptr, &pr);
-    const size_t units = static_cast<size_t>(p->batch) * p->n_heads;
-    float2 *ws_part = reinterpret_cast<float2 *>(static_cast<char *>(ws) + align_up(units * p->cap * sizeof(float)));
-    if (launch_decode(p->dtype, p->head_dim, q, k, v, K, V, S, nrm, pos, static_cast<float *>(ws), ws_part, pr.meta,
-                      pr.g, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
-        return VATP_E_DEVICE;
-    return VATP_OK;
+    return decode_step_impl(ctx, p, VATP_CALL_DECODE_STEP, q, k, v, K, V, S, nrm, pos, new_pos, nullptr, ws, ws_bytes,
+                            hip_stream);
+}
+
+vatp_status vatp_decode_attend_step(vatp_ctx *ctx, const vatp_params *p, const void *q, const void *k,
+                                    const void *v, void *K, void *V, float *S, float *nrm, int32_t *pos,
+                                    const int32_t *new_pos, float *out, void *ws, size_t ws_bytes,
+                                    void *hip_stream)
+{
+    return decode_step_impl(ctx, p, VATP_CALL_DECODE_ATTEND_STEP, q, k, v, K, V, S, nrm, pos, new_pos, out, ws,
+                            ws_bytes, hip_stream);
 }
 
 vatp_status vatp_select_compact(vatp_ctx *ctx, const vatp_params *p, const void *K, const void *V,

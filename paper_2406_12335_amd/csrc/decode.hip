@@ -9,6 +9,8 @@
 //           workgroup's loads in flight before the first is used.  The workgroup leaves its
 //           logits (base-2 domain, t = c*log2(e)*<q,k>) and its chunk's (max, sum of 2^(t-max))
 //           in the workspace, and the one that owns the new row appends k, v, |v|_1 and pos.
+//           With an output pointer (vatp_decode_attend_step) it also reads the V rows and leaves
+//           the chunk's unnormalised share of the attention output (Eq. 1) in the workspace.
 //   finish  same grid, one row per thread: every workgroup merges the unit's few chunk
 //           statistics into log2 sum 2^t and applies S += 2^(t - lse2); 12 bytes per row, a
 //           tiny launch ordered after the first by the stream.
@@ -18,12 +20,12 @@ namespace vatp {
 
 namespace {
 
-template <typename T, int D>
+template <typename T, int D, bool kAttend>
 __global__ __launch_bounds__(256) void decode_logits_kernel(
     const T *__restrict__ q, const T *__restrict__ k_new, const T *__restrict__ v_new,
     T *__restrict__ K, T *__restrict__ V, float *__restrict__ nrm, int32_t *__restrict__ pos,
-    float *__restrict__ ws_logit, float2 *__restrict__ ws_part, BatchMeta meta, int n_heads,
-    int cap, int chunks_alloc, float scale_log2, int norm)
+    float *__restrict__ ws_logit, float2 *__restrict__ ws_part, float *__restrict__ ws_out,
+    BatchMeta meta, int n_heads, int cap, int chunks_alloc, float scale_log2, int norm)
 {
     constexpr int kE = Elt<T>::kPer16B;
     constexpr int kLanesPerRow = D / kE;
@@ -109,11 +111,51 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(
     __syncthreads();
     if (tid == 0)
         ws_part[unit * chunks_alloc + chunk] = make_float2(mx, s_red[4] + s_red[5] + s_red[6] + s_red[7]);
+
+    if constexpr (kAttend) {
+        // this chunk's share of the attention output (paper Eq. 1), unnormalised and relative to the
+        // chunk maximum:  o_c = sum_r 2^(t_r - max_c) v_r ; the finish launch rescales and adds the chunks
+        __shared__ float s_o[kRowsPerPass][D];
+        const uint4 *Vu = reinterpret_cast<const uint4 *>(V + unit * cap * D);
+        const uint4 *vnew = reinterpret_cast<const uint4 *>(v_new + unit * D);
+        float oacc[kE];
+#pragma unroll
+        for (int e = 0; e < kE; ++e) oacc[e] = 0.f;
+#pragma unroll
+        for (int p0 = 0; p0 < kPasses; p0 += kGroup) {
+            uint4 raw[kGroup];
+#pragma unroll
+            for (int u = 0; u < kGroup; ++u) {
+                const int r = row0 + (p0 + u) * kRowsPerPass + rloc;
+                const uint4 *src = (r == n0) ? vnew + sub : Vu + static_cast<size_t>(r) * kLanesPerRow + sub;
+                raw[u] = (r < n) ? *src : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int u = 0; u < kGroup; ++u) {
+                const float p = exp2f(s_logit[(p0 + u) * kRowsPerPass + rloc] - mx);   // 0 past the end
+                float vf[kE];
+                Elt<T>::unpack(raw[u], vf);
+#pragma unroll
+                for (int e = 0; e < kE; ++e) oacc[e] = fmaf(p, vf[e], oacc[e]);
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < kE; ++e) s_o[rloc][sub * kE + e] = oacc[e];
+        __syncthreads();
+        if (tid < D) {
+            float o = 0.f;
+#pragma unroll
+            for (int g = 0; g < kRowsPerPass; ++g) o += s_o[g][tid];
+            ws_out[(unit * chunks_alloc + chunk) * D + tid] = o;
+        }
+    }
 }
 
 __global__ __launch_bounds__(256) void decode_finish_kernel(float *__restrict__ S,
                                                             const float *__restrict__ ws_logit,
                                                             const float2 *__restrict__ ws_part,
+                                                            const float *__restrict__ ws_out,
+                                                            float *__restrict__ out, int head_dim,
                                                             BatchMeta meta, int n_heads, int cap,
                                                             int chunks_alloc)
 {
@@ -136,29 +178,40 @@ __global__ __launch_bounds__(256) void decode_finish_kernel(float *__restrict__ 
     for (int c = 0; c < n_chunks; ++c) L += part[c].y * exp2f(part[c].x - M);
     const float lse2 = M + log2f(L);
     if (r < n) S[unit * cap + r] = s_old + exp2f(logit - lse2);
+    // attention output of the new token: the chunks' partial sums, rescaled to the common maximum
+    if (out && blockIdx.x == 0 && threadIdx.x < head_dim) {
+        float o = 0.f;
+        for (int c = 0; c < n_chunks; ++c)
+            o += ws_out[(unit * chunks_alloc + c) * head_dim + threadIdx.x] * exp2f(part[c].x - M);
+        out[unit * head_dim + threadIdx.x] = o / L;
+    }
 }
 
 }  // namespace
 
 hipError_t launch_decode(int dtype, int head_dim, const void *q, const void *k, const void *v,
                          void *K, void *V, float *S, float *nrm, int32_t *pos, float *ws_logit,
-                         float2 *ws_part, const BatchMeta &meta, const Geometry &g, hipStream_t st)
+                         float2 *ws_part, float *ws_out, float *out, const BatchMeta &meta,
+                         const Geometry &g, hipStream_t st)
 {
     const int chunks_alloc = (g.cap + kDecodeChunk - 1) / kDecodeChunk;
     const unsigned units = static_cast<unsigned>(g.batch) * g.n_heads;
     dim3 grid((g.max_len + kDecodeChunk - 1) / kDecodeChunk, units), block(256);
-#define VATP_DEC(T, D)                                                                             \
-    hipLaunchKernelGGL((decode_logits_kernel<T, D>), grid, block, 0, st, static_cast<const T *>(q), \
-                       static_cast<const T *>(k), static_cast<const T *>(v), static_cast<T *>(K),  \
-                       static_cast<T *>(V), nrm, pos, ws_logit, ws_part, meta, g.n_heads, g.cap,   \
-                       chunks_alloc, g.scale_log2, g.norm)
-    if (dtype == VATP_F32 && head_dim == 64) VATP_DEC(float, 64);
-    else if (dtype == VATP_F32) VATP_DEC(float, 128);
-    else if (head_dim == 64) VATP_DEC(bf16_t, 64);
-    else VATP_DEC(bf16_t, 128);
+    const bool attend = out != nullptr;
+#define VATP_DEC(T, D, A)                                                                              \
+    hipLaunchKernelGGL((decode_logits_kernel<T, D, A>), grid, block, 0, st, static_cast<const T *>(q),  \
+                       static_cast<const T *>(k), static_cast<const T *>(v), static_cast<T *>(K),      \
+                       static_cast<T *>(V), nrm, pos, ws_logit, ws_part, ws_out, meta, g.n_heads,      \
+                       g.cap, chunks_alloc, g.scale_log2, g.norm)
+#define VATP_DEC2(T, D) do { if (attend) VATP_DEC(T, D, true); else VATP_DEC(T, D, false); } while (0)
+    if (dtype == VATP_F32 && head_dim == 64) VATP_DEC2(float, 64);
+    else if (dtype == VATP_F32) VATP_DEC2(float, 128);
+    else if (head_dim == 64) VATP_DEC2(bf16_t, 64);
+    else VATP_DEC2(bf16_t, 128);
+#undef VATP_DEC2
 #undef VATP_DEC
     hipLaunchKernelGGL(decode_finish_kernel, dim3((g.max_len + 255) / 256, units), block, 0, st, S, ws_logit, ws_part,
-                       meta, g.n_heads, g.cap, chunks_alloc);
+                       ws_out, out, head_dim, meta, g.n_heads, g.cap, chunks_alloc);
     return hipGetLastError();
 }
 

@@ -75,8 +75,8 @@ hipError_t launch_prefill_mfma(const void *Q, const void *K, float *S, float *ls
 
 hipError_t launch_decode(int dtype, int head_dim, const void *q, const void *k, const void *v,
                          void *K, void *V, float *S, float *nrm, int32_t *pos,
-                         float *ws_logit, float2 *ws_part, const BatchMeta &meta, const Geometry &g,
-                         hipStream_t st);
+                         float *ws_logit, float2 *ws_part, float *ws_out, float *out, const BatchMeta &meta,
+                         const Geometry &g, hipStream_t st);
 
 hipError_t launch_select(const float *S, const float *nrm, int32_t *kept_idx,
                          const BatchMeta &meta, const Geometry &g, hipStream_t st);

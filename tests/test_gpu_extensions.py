@@ -64,3 +64,50 @@ def test_prompt_scores_from_given_row_lse(gpu_device, dtype, d, lens):
             parity.assert_scores_close(S[b, h, :L].cpu().numpy(), want[(b, h)], rtol, "S from lse (%d,%d)" % (b, h))
             parity.assert_scores_close(nrm[b, h, :L].cpu().numpy(), orc.l1norm(inp.V[b, h, :L].double().numpy()), rtol, "nrm")
         assert torch.all(S[b, :, L:] == -3.0)
+
+
+@pytest.mark.parametrize("dtype,d,n0s", [("bf16", 128, [2048, 0, 130]), ("fp32", 64, [300, 127, 128]), ("bf16", 64, [1000, 5, 257]),
+                                         ("fp32", 128, [129, 1, 64])])
+def test_decode_step_with_attention_output(gpu_device, dtype, d, n0s):
+    """vatp_decode_attend_step: same cache update as vatp_decode_step plus out = sum_r a_r V_r (Eq. 1)."""
+    H = 2
+    tdt = torch.float32 if dtype == "fp32" else torch.bfloat16
+    cap = max(n0s) + 1
+    g = torch.Generator().manual_seed(71)
+    K = (torch.randn(len(n0s), H, cap, d, generator=g) * 1.2).to(tdt)
+    V = (torch.randn(len(n0s), H, cap, d, generator=g) * torch.exp(0.5 * torch.randn(len(n0s), H, cap, 1, generator=g))).to(tdt)
+    S0 = torch.rand(len(n0s), H, cap, generator=g) + 0.1
+    q, k, v = ((torch.randn(len(n0s), H, d, generator=g) * 1.5).to(tdt) for _ in range(3))
+    _say("attend %s d=%d n0=%s" % (dtype, d, n0s))
+    dev = gpu_device
+    ctx = vatp.vatp_create(0)
+    try:
+        p = vatp.Params(len(n0s), H, d, tdt, 0, 0, cap, n0s, None)
+        res = []
+        for attend in (False, True):
+            Kd, Vd, Sd = K.to(dev).clone(), V.to(dev).clone(), S0.to(dev).clone()
+            Nd = torch.zeros(len(n0s), H, cap, device=dev)
+            out = torch.full((len(n0s), H, d), 9.0, device=dev)
+            call = vatp.CALL_DECODE_ATTEND_STEP if attend else vatp.CALL_DECODE_STEP
+            ws = torch.empty(vatp.vatp_workspace_bytes(ctx, p, call), dtype=torch.uint8, device=dev)
+            if attend:
+                vatp.vatp_decode_attend_step(ctx, p, q.to(dev), k.to(dev), v.to(dev), Kd, Vd, Sd, Nd, None, None, out, ws)
+            else:
+                vatp.vatp_decode_step(ctx, p, q.to(dev), k.to(dev), v.to(dev), Kd, Vd, Sd, Nd, None, None, ws)
+            torch.cuda.synchronize()
+            res.append((Kd.cpu(), Vd.cpu(), Sd.cpu(), Nd.cpu(), out.cpu()))
+    finally:
+        vatp.vatp_destroy(ctx)
+    rtol = parity.rtol_for(tdt)
+    (Ka, Va, Sa, Na, _), (Kb, Vb, Sb, Nb, out) = res
+    for b, n0 in enumerate(n0s):
+        n = n0 + 1
+        # the cache update is bit-identical to the plain decode step
+        assert torch.equal(Ka[b, :, :n], Kb[b, :, :n]) and torch.equal(Va[b, :, :n], Vb[b, :, :n])
+        assert torch.equal(Sa[b, :, :n], Sb[b, :, :n]) and torch.equal(Na[b, :, n0], Nb[b, :, n0])
+        for h in range(H):
+            Kfull = torch.cat([K[b, h, :n0], k[b, h][None]], 0).double().numpy()
+            Vfull = torch.cat([V[b, h, :n0], v[b, h][None]], 0).double().numpy()
+            want, scale = orc.attention_output(q[b, h].double().numpy(), Kfull, Vfull)
+            err = np.abs(out[b, h].double().numpy() - want)
+            assert np.all(err <= rtol * scale + 1e-12), "attention output unit (%d,%d): max err %.3g" % (b, h, err.max())

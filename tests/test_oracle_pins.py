@@ -323,3 +323,25 @@ def test_row_lse_matches_torch_logsumexp_and_closes_the_loop():
     # a shifted normaliser scales every weight of that row: S is linear in exp(-lse)
     S2 = orc.prefill_scores_given_lse(Q.numpy(), K.numpy(), lse + math.log(2.0))
     np.testing.assert_allclose(S2, S / 2.0, rtol=1e-12)
+
+
+# ---------------------------------------------------------------- attention output (Eq. 1)
+
+def test_attention_output_matches_torch_and_simple_cases():
+    g = torch.Generator().manual_seed(61)
+    n, d = 77, 16
+    K = torch.randn(n, d, generator=g, dtype=torch.float64)
+    V = torch.randn(n, d, generator=g, dtype=torch.float64)
+    q = torch.randn(d, generator=g, dtype=torch.float64) * 2
+    a = torch.softmax(K @ q / math.sqrt(d), dim=0)
+    out, abs_out = orc.attention_output(q.numpy(), K.numpy(), V.numpy())
+    np.testing.assert_allclose(out, (a[:, None] * V).sum(0).numpy(), rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(abs_out, (a[:, None] * V.abs()).sum(0).numpy(), rtol=1e-12)
+    # uniform attention (q = 0) averages the value rows; one row returns that row
+    out0, _ = orc.attention_output(np.zeros(d), K.numpy(), V.numpy())
+    np.testing.assert_allclose(out0, V.mean(0).numpy(), rtol=1e-12, atol=1e-15)
+    out1, _ = orc.attention_output(q.numpy(), K[:1].numpy(), V[:1].numpy())
+    np.testing.assert_array_equal(out1, V[0].numpy())
+    # the weights are those of the decode score update
+    _, a_dec = orc.decode_scores(q.numpy(), K.numpy(), np.zeros(n))
+    np.testing.assert_allclose(out, a_dec @ V.numpy(), rtol=1e-12, atol=1e-15)
