@@ -53,6 +53,7 @@ typedef __attribute__((address_space(3))) char lds_char;
 constexpr int kD = 128;            // head_dim
 constexpr int kStage = 64;         // streamed rows per LDS stage
 constexpr int kRing = 4;           // LDS stage buffers
+constexpr unsigned kComputeUnits = 256;
 constexpr int kAhead = kRing - 1;  // stages in flight beyond the one being consumed
 constexpr int kWaveCols = 64;      // stationary rows per wavefront
 constexpr int kBlockCols = 256;    // stationary rows per workgroup
@@ -121,9 +122,10 @@ struct Epilogue {
             for (int cb = 0; cb < 2; ++cb) part[cb] += fast_exp2(fmaf(p.acc[cb][i], scale, -p.lse[i]));
         } else {
             if (i < 2) {                                   // tile maximum of column block i
-                float t = fmaxf(p.acc[i][0], p.acc[i][1]);
+                // a linear chain, so that every two steps fuse into one three-operand maximum
+                float t = p.acc[i][0];
 #pragma unroll
-                for (int v = 2; v < 16; v += 2) t = fmaxf(t, fmaxf(p.acc[i][v], p.acc[i][v + 1]));
+                for (int v = 1; v < 16; ++v) t = fmaxf(t, p.acc[i][v]);
                 tmax[i] = t;
             } else if (i == 2) {
 #pragma unroll
@@ -159,16 +161,23 @@ struct Epilogue {
     }
 };
 
-template <bool kColsum>
-__global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t *__restrict__ Q,
+template <bool kColsum, int kHalves>
+__global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_t *__restrict__ Q,
                                                            const bf16_t *__restrict__ K,
                                                            float *__restrict__ lse2,
                                                            float *__restrict__ S, BatchMeta meta,
                                                            int n_heads, int n_units, int cap,
                                                            int n_blocks, float scale_log2)
 {
-    __shared__ uint4 stage[kRing][kStage * kChunksPerRow];      // 4 x 16 KiB, filled by the load unit
-    __shared__ __attribute__((aligned(16))) float lse_stage[kRing][kStage];
+    // A ring slot holds kHalves sub-stages of 64 streamed rows; wavefront w works on sub-stage
+    // w / 4 of every slot for the 64 stationary rows of column group w % 4.  With kHalves = 2
+    // a workgroup has two wavefronts per SIMD (used when the grid has too few workgroups for
+    // two of them to share a compute unit).
+    constexpr int kSlotRows = kStage * kHalves;
+    constexpr int kSlotBytes = kStageBytes * kHalves;
+    __shared__ uint4 stage[kRing][kSlotRows * kChunksPerRow];   // filled by the load unit
+    __shared__ __attribute__((aligned(16))) float lse_stage[kRing][kSlotRows];
+    __shared__ float merge_buf[kHalves == 2 ? 2 : 1][kBlockCols];
 
     // Workgroups are handed to the 8 XCDs round-robin by linear id.  All block pairs of one
     // (batch, head) unit are given ids that are equal mod 8, so the unit's streamed matrix is
@@ -187,12 +196,13 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t *__restr
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int cw = wave & 3, half = wave >> 2;      // column group, sub-stage
     const int lane = tid & 63, g = lane >> 5, n = lane & 31;
 
     const unsigned lds_stage0 = static_cast<unsigned>(reinterpret_cast<size_t>((lds_char *)(char *)&stage[0][0]));
     const unsigned lds_lse0 = static_cast<unsigned>(reinterpret_cast<size_t>((lds_char *)(char *)&lse_stage[0][0]));
 
-    // Copy stage t (64 streamed rows) into ring slot `slot`.  This wavefront moves rows
+    // Copy stage t (kSlotRows streamed rows) into ring slot `slot`.  This wavefront moves rows
     // 16*wave .. 16*wave+15, four rows (1 KiB) per instruction.  Rows past the end of the
     // sequence are redirected to its last row (any finite data: they are masked later).
     auto copy_stage = [&](int t, int slot) {
@@ -200,34 +210,33 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t *__restr
         for (int i = 0; i < 4; ++i) {
             const int r = 16 * wave + 4 * i + (lane >> 4);           // row inside the stage
             const int c = (lane & 15) ^ (r & 15);                    // global chunk for LDS chunk lane&15
-            const int grow = min(t * kStage + r, len - 1);
+            const int grow = min(t * kSlotRows + r, len - 1);
             const unsigned voff = static_cast<unsigned>(grow) * (kD * 2) + c * 16;
-            const unsigned m0v = lds_stage0 + slot * kStageBytes + (16 * wave + 4 * i) * (kD * 2);
+            const unsigned m0v = lds_stage0 + slot * kSlotBytes + (16 * wave + 4 * i) * (kD * 2);
             asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0v), "v"(voff), "s"(strm)
                          : "memory");
         }
-        if (kColsum && wave == 0) {
-            const int grow = min(t * kStage + lane, len - 1);
+        if (kColsum && cw == 0) {
+            const int grow = min(t * kSlotRows + kStage * half + lane, len - 1);
             const unsigned voff = static_cast<unsigned>(grow) * 4;
-            const unsigned m0v = lds_lse0 + slot * kStage * 4;
+            const unsigned m0v = lds_lse0 + (slot * kSlotRows + kStage * half) * 4;
             asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2" ::"s"(m0v), "v"(voff), "s"(lse_u)
                          : "memory");
         }
     };
-    // copies per stage issued by this wavefront (wavefront 0 also brings the lse values)
-    const bool extra_copy = kColsum && wave == 0;
-
+    // copies per stage issued by this wavefront (column group 0 also brings the lse values)
+    const bool extra_copy = kColsum && cw == 0;
     for (int job = 0; job < 2; ++job) {
         const int blk = job == 0 ? pair : n_blocks - 1 - pair;
         if (job == 1 && blk == pair) break;               // odd count: the middle block once
         const int base0 = blk * kBlockCols;
         if (base0 >= len) continue;
-        const int w0 = base0 + wave * kWaveCols;       // first stationary row of this wavefront
+        const int w0 = base0 + cw * kWaveCols;         // first stationary row of this wavefront
 
         // stages of streamed rows this workgroup walks through
-        const int t_begin = kColsum ? base0 / kStage : 0;
+        const int t_begin = kColsum ? base0 / kSlotRows : 0;
         const int last_row = kColsum ? len - 1 : min(base0 + kBlockCols - 1, len - 1);
-        const int t_end = last_row / kStage;               // inclusive
+        const int t_end = last_row / kSlotRows;            // inclusive
 
 #pragma unroll
         for (int k = 0; k < kAhead; ++k)
@@ -253,7 +262,6 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t *__restr
         for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
             for (int s = 0; s < 8; ++s) asm volatile("" ::"v"(Bf[cb][s]));
-
         Running<kColsum> run;
         run.m[0] = run.m[1] = -1e30f;
         run.l[0] = run.l[1] = 0.f;
@@ -290,7 +298,7 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t *__restr
                 auto do_stage = [&](int t, auto masked_tag) {
                     constexpr bool kMasked = decltype(masked_tag)::value;
                     const int slot = (t - t_begin) & (kRing - 1);
-                    const int s0 = t * kStage;                  // first streamed row of the stage
+                    const int s0 = t * kSlotRows + kStage * half;   // first streamed row of the sub-stage
                     // the two instantiations must not share a hoisted prefix: the pending pair's
                     // exponentials belong next to this stage's MFMAs (the scale is re-read through
                     // an opaque asm so nothing that uses it can move up)
@@ -298,8 +306,8 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t *__restr
                     asm volatile("; stage variant %1" : "+s"(scale) : "n"(kMasked ? 1 : 0));
 #pragma unroll
                     for (int kb = 0; kb < 2; ++kb) {
-                        const int ar = 32 * kb + n;            // this lane's row of the streamed tile
                         Pending<kColsum> next;
+                        const int ar = kStage * half + 32 * kb + n;   // this lane's row of the streamed tile
                         bf16x8 a[8];
 #pragma unroll
                         for (int s = 0; s < 8; ++s)
@@ -308,7 +316,7 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t *__restr
 #pragma unroll
                             for (int q4 = 0; q4 < 4; ++q4) {
                                 const float4 x =
-                                    *reinterpret_cast<const float4 *>(&lse_stage[slot][32 * kb + 8 * q4 + 4 * g]);
+                                    *reinterpret_cast<const float4 *>(&lse_stage[slot][kStage * half + 32 * kb + 8 * q4 + 4 * g]);
                                 next.lse[4 * q4 + 0] = x.x; next.lse[4 * q4 + 1] = x.y;
                                 next.lse[4 * q4 + 2] = x.z; next.lse[4 * q4 + 3] = x.w;
                             }
@@ -357,24 +365,30 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t *__restr
                 };
                 // Every wavefront walks the same stages (same number of barriers) but spends them
                 // differently: full stages, its one diagonal stage, and stages it only waits through.
-                const int t_diag = w0 / kStage;
+                // Sub-stage u = t * kHalves + half holds streamed rows 64u .. 64u+63; the one that
+                // crosses this wavefront's diagonal is u_diag.  t_first is the first stage whose
+                // sub-stage is at or past the diagonal; it is the diagonal itself iff on_diag.
+                const int u_diag = w0 / kStage;
+                const int du = u_diag - half;
+                const int t_first = du < 0 ? 0 : (du + kHalves - 1) / kHalves;
+                const bool on_diag = du >= 0 && du % kHalves == 0;
                 int t = t_begin;
                 if (w0 >= len) {
                     for (; t <= t_end; ++t) stage_sync(t);              // no valid stationary row
                 } else if constexpr (!kColsum) {
-                    for (; t < t_diag; ++t) { stage_sync(t); do_stage(t, std::false_type{}); }
-                    stage_sync(t); do_stage(t, std::true_type{}); ++t;   // t_diag <= t_end here
+                    for (; t < t_first; ++t) { stage_sync(t); do_stage(t, std::false_type{}); }
+                    if (on_diag) { stage_sync(t); do_stage(t, std::true_type{}); ++t; }   // t <= t_end here
                     for (; t <= t_end; ++t) stage_sync(t);               // keys past the diagonal
                 } else {
-                    const int t_full_end = len / kStage - 1;             // last stage with 64 valid rows
-                    for (; t < t_diag; ++t) stage_sync(t);               // queries before the diagonal
-                    stage_sync(t); do_stage(t, std::true_type{}); ++t;
-                    for (; t <= t_full_end; ++t) { stage_sync(t); do_stage(t, std::false_type{}); }
+                    // last stage whose sub-stage has 64 valid rows: 64u + 63 < len
+                    const int t_full_end = (len / kStage - 1 - half + kHalves) / kHalves - 1;
+                    for (; t < t_first && t <= t_end; ++t) stage_sync(t);   // queries before the diagonal
+                    if (on_diag && t <= t_end) { stage_sync(t); do_stage(t, std::true_type{}); ++t; }
+                    for (; t <= min(t_full_end, t_end); ++t) { stage_sync(t); do_stage(t, std::false_type{}); }
                     for (; t <= t_end; ++t) { stage_sync(t); do_stage(t, std::true_type{}); }   // ragged tail
                 }
             }
         }
-
         // the last pair still waits for its exponentials
         {
             Epilogue<kColsum> epi;
@@ -383,26 +397,73 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(const bf16_t *__restr
             epi.finish(pend, run, scale_log2);
         }
 
-        // merge the two lane halves (same stationary column, complementary streamed rows)
+        // merge the two lane halves (same stationary column, complementary streamed rows), then,
+        // with two sub-stages, the two wavefronts of a column group through LDS
+        float fin_m[2], fin_l[2];
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) {
-            const int idx = w0 + 32 * cb + n;
             if (!kColsum) {
                 const float m_o = __shfl_xor(run.m[cb], 32), l_o = __shfl_xor(run.l[cb], 32);
-                const float m = fmaxf(run.m[cb], m_o);
-                const float l = run.l[cb] * fast_exp2(run.m[cb] - m) + l_o * fast_exp2(m_o - m);
-                if (g == 0 && idx < len) lse_u[idx] = m + __log2f(l);
+                fin_m[cb] = fmaxf(run.m[cb], m_o);
+                fin_l[cb] = run.l[cb] * fast_exp2(run.m[cb] - fin_m[cb]) + l_o * fast_exp2(m_o - fin_m[cb]);
             } else {
-                const float s = run.col[cb] + __shfl_xor(run.col[cb], 32);
-                if (g == 0 && idx < len) S[unit * cap + idx] = s;
+                fin_m[cb] = 0.f;
+                fin_l[cb] = run.col[cb] + __shfl_xor(run.col[cb], 32);
             }
         }
-        // every wavefront must be done reading the ring before the next job refills it
-        wait_copies_then_barrier<0>();
+        if constexpr (kHalves == 2) {
+            if (half == 1 && g == 0) {
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb) {
+                    merge_buf[0][cw * kWaveCols + 32 * cb + n] = fin_l[cb];
+                    if (!kColsum) merge_buf[1][cw * kWaveCols + 32 * cb + n] = fin_m[cb];
+                }
+            }
+            __syncthreads();
+            if (half == 0) {
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb) {
+                    const float l_o = merge_buf[0][cw * kWaveCols + 32 * cb + n];
+                    if (!kColsum) {
+                        const float m_o = merge_buf[1][cw * kWaveCols + 32 * cb + n];
+                        const float m = fmaxf(fin_m[cb], m_o);
+                        fin_l[cb] = fin_l[cb] * fast_exp2(fin_m[cb] - m) + l_o * fast_exp2(m_o - m);
+                        fin_m[cb] = m;
+                    } else {
+                        fin_l[cb] += l_o;
+                    }
+                }
+            }
+        }
+        if (half == 0 && g == 0) {
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb) {
+                const int idx = w0 + 32 * cb + n;
+                if (idx < len) {
+                    if (!kColsum) lse_u[idx] = fin_m[cb] + __log2f(fin_l[cb]);
+                    else S[unit * cap + idx] = fin_l[cb];
+                }
+            }
+        }
+        // every wavefront must be done reading the ring before the next job refills it (all
+        // copies have landed by now; the result stores need not have)
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     }
 }
 
 }  // namespace
+
+template <int kHalves>
+static void launch_both(const bf16_t *Q, const bf16_t *K, float *S, float *lse2, bool have_lse, const BatchMeta &meta,
+                        const Geometry &g, int n_units, int n_blocks, dim3 grid, hipStream_t st)
+{
+    const dim3 block(256 * kHalves);
+    if (!have_lse)      // row statistics are computed here unless the caller supplied them
+        hipLaunchKernelGGL((prefill_mfma_kernel<false, kHalves>), grid, block, 0, st, Q, K, lse2, S, meta, g.n_heads,
+                           n_units, g.cap, n_blocks, g.scale_log2);
+    hipLaunchKernelGGL((prefill_mfma_kernel<true, kHalves>), grid, block, 0, st, Q, K, lse2, S, meta, g.n_heads,
+                       n_units, g.cap, n_blocks, g.scale_log2);
+}
 
 hipError_t launch_prefill_mfma(const void *Q, const void *K, float *S, float *lse2, bool have_lse,
                                const BatchMeta &meta, const Geometry &g, hipStream_t st)
@@ -411,14 +472,13 @@ hipError_t launch_prefill_mfma(const void *Q, const void *K, float *S, float *ls
     const int n_blocks = (g.max_len + kBlockCols - 1) / kBlockCols;
     const int n_units = g.batch * g.n_heads;
     const int n_pairs = (n_blocks + 1) / 2;
-    dim3 grid(8u * n_pairs * ((n_units + 7) / 8)), block(256);
-    if (!have_lse)      // row statistics are computed here unless the caller supplied them
-        hipLaunchKernelGGL((prefill_mfma_kernel<false>), grid, block, 0, st, static_cast<const bf16_t *>(Q),
-                           static_cast<const bf16_t *>(K), lse2, S, meta, g.n_heads, n_units, g.cap, n_blocks,
-                           g.scale_log2);
-    hipLaunchKernelGGL((prefill_mfma_kernel<true>), grid, block, 0, st, static_cast<const bf16_t *>(Q),
-                       static_cast<const bf16_t *>(K), lse2, S, meta, g.n_heads, n_units, g.cap, n_blocks,
-                       g.scale_log2);
+    const unsigned n_wg = 8u * n_pairs * ((n_units + 7) / 8);
+    const bf16_t *q = static_cast<const bf16_t *>(Q), *k = static_cast<const bf16_t *>(K);
+    // Two wavefronts per SIMD either way: two 4-wavefront workgroups per compute unit when
+    // the grid is large enough to keep pairs of them resident, else 8-wavefront workgroups.
+    const int halves = n_wg >= 2u * kComputeUnits ? 1 : 2;
+    if (halves == 2) launch_both<2>(q, k, S, lse2, have_lse, meta, g, n_units, n_blocks, dim3(n_wg), st);
+    else launch_both<1>(q, k, S, lse2, have_lse, meta, g, n_units, n_blocks, dim3(n_wg), st);
     return hipGetLastError();
 }
 
