@@ -2,9 +2,11 @@
 
 One "step" is one pass of the whole hot path over one batch of synthetic input that is
 already resident in HBM: prompt scoring (vatp_prefill_score), the prompt prune
-(vatp_select_compact), then T decode steps of vatp_decode_step + vatp_select_compact, for
-every layer of the workload.  Prints ONE JSON line (see the design doc for the byte and flop
-formulas behind `roofline`).
+(vatp_select_compact), then T decode steps, each followed by the eviction back to the budget,
+for every layer of the workload: by default through vatp_decode_prune_step (two launches, only
+the rows that changed are rewritten), with --decode-route separate through vatp_decode_step +
+vatp_select_compact (three launches, the whole cache is copied every step).  Prints ONE JSON
+line (see the design doc for the byte and flop formulas behind `roofline`).
 """
 from __future__ import annotations
 
@@ -43,6 +45,15 @@ def algorithmic_bytes_decode(cfg, n_rows, budget):
     return score, select + compact
 
 
+def algorithmic_bytes_fused(cfg, n_rows, budget, rows_moved):
+    """vatp_decode_prune_step for one unit: K read once, S and nrm read, the new scores written, and
+    only the rows from the first changed one on copied to the other cache set (K, V, nrm, pos)."""
+    elt = 4 if cfg.dtype == "fp32" else 2
+    row = cfg.head_dim * elt
+    keep = min(n_rows, budget)
+    return n_rows * row + 8 * n_rows + 4 * keep + rows_moved * (4 * row + 16)
+
+
 def run(args):
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (got --gpus %d)" % args.gpus, file=sys.stderr)
@@ -64,10 +75,13 @@ def run(args):
     T = cfg.decode_steps
     layers = [vs.make_inputs(cfg, seed=args.seed, layer=l, device=dev) for l in range(cfg.layers)]
     lens, budgets = layers[0].lens, layers[0].budgets
+    for inp in layers:      # per-step views of the new tokens, made once (indexing costs host time per call)
+        inp.step_qkv = [(inp.qd[t], inp.kd[t], inp.vd[t]) for t in range(T)]
     ctx = vatp.vatp_create(0)
     caches = [PrunedKVCache(cfg.batch, cfg.n_heads, cfg.head_dim, cfg.torch_dtype(), cfg.n_sink_keep, cfg.recent,
                             budgets, dev, ctx=ctx) for _ in layers]
     new_pos = [[L + t for L in lens] for t in range(T)]
+    fused = args.decode_route == "fused"
 
     def one_step(ev=None):
         """ev: optional dict of event lists, filled with (start, end) pairs per phase."""
@@ -87,8 +101,11 @@ def run(args):
         e3 = mark() if ev is not None else None
         for t in range(T):
             for inp, cache in zip(layers, caches):
-                cache.decode_step(inp.qd[t], inp.kd[t], inp.vd[t], new_pos[t])
-                cache.prune()
+                if fused:
+                    cache.decode_prune_step(*inp.step_qkv[t], new_pos[t], want_kept_idx=False)
+                else:
+                    cache.decode_step(*inp.step_qkv[t], new_pos[t])
+                    cache.prune()
         if ev is not None:
             ev["decode_loop"].append((e3, mark()))
 
@@ -126,7 +143,7 @@ def run(args):
     for t in range(T):
         for inp, cache in zip(layers, caches):
             a = torch.cuda.Event(enable_timing=True); a.record()
-            cache.decode_step(inp.qd[t], inp.kd[t], inp.vd[t], new_pos[t])
+            cache.decode_step(*inp.step_qkv[t], new_pos[t])
             b = torch.cuda.Event(enable_timing=True); b.record()
             cache.prune()
             c = torch.cuda.Event(enable_timing=True); c.record()
@@ -136,6 +153,35 @@ def run(args):
     n_calls = max(1, T * cfg.layers)
     dec_call_ms = total_ms(split["decode_step"]) / n_calls
     sel_call_ms = total_ms(split["select_compact"]) / n_calls
+
+    # second replay: the fused route, timed per call; the per-head count of rows it had to move is
+    # read back after every step (min of the two `synced` arrays = first rewritten row)
+    fused_pairs, fused_bytes, fused_rows_moved = [], 0, 0
+    for readback in (False, True):          # first pass: timing only; second pass: rows moved, with syncs
+        for inp, cache in zip(layers, caches):
+            cache.prefill_score(inp.Q, inp.K, inp.V, lens)
+            cache.prune_prompt(inp.K, inp.V)
+        t_host = time.perf_counter()
+        for t in range(T):
+            for inp, cache in zip(layers, caches):
+                n_after = [n + 1 for n in cache.lens]
+                if not readback:
+                    a = torch.cuda.Event(enable_timing=True); a.record()
+                cache.decode_prune_step(*inp.step_qkv[t], new_pos[t], want_kept_idx=False)
+                if not readback:
+                    b = torch.cuda.Event(enable_timing=True); b.record()
+                    fused_pairs.append((a, b))
+                    continue
+                first = torch.minimum(cache.synced[0], cache.synced[1]).view(cfg.batch, cfg.n_heads).cpu()
+                for bb in range(cfg.batch):
+                    keep = min(n_after[bb], budgets[bb])
+                    moved = (keep - first[bb]).clamp_(min=0)
+                    fused_rows_moved += int(moved.sum())
+                    fused_bytes += sum(algorithmic_bytes_fused(cfg, n_after[bb], budgets[bb], int(m)) for m in moved)
+        if not readback:
+            host_us_per_call = (time.perf_counter() - t_host) * 1e6 / n_calls    # enqueue only, no sync yet
+        torch.cuda.synchronize()
+    fused_call_ms = total_ms(fused_pairs) / n_calls
 
     # algorithmic work
     flops = algorithmic_flops_prefill(cfg, lens)
@@ -160,7 +206,15 @@ def run(args):
                     "achieved": round(prefill_tflops, 3), "peak": peak_tf, "unit": "TFLOP/s",
                     "frac": round(prefill_tflops / peak_tf, 5), "traffic": traffic.get("prefill_score"),
                     "avg_launch_ms": round(prefill_ms / cfg.layers, 5)}
-    decode_gbps = (dec_bytes + sel_bytes) / (decode_ms * 1e-3) / 1e9 if decode_ms > 0 and T else 0.0
+    loop_bytes = fused_bytes if fused else dec_bytes + sel_bytes
+    decode_gbps = loop_bytes / (decode_ms * 1e-3) / 1e9 if decode_ms > 0 and T else 0.0
+    fused_gbps = fused_bytes / n_calls / (fused_call_ms * 1e-3) / 1e9 if T and fused_call_ms > 0 else 0.0
+    roof_fused = {"kernel": "vatp_decode_prune_step = decode_logits_kernel + decode_prune_kernel", "bound": "hbm",
+                  "achieved": round(fused_gbps, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                  "frac": round(fused_gbps / HBM_PEAK_GBPS, 5), "traffic": traffic.get("decode_prune_step"),
+                  "avg_launch_ms": round(fused_call_ms, 5),
+                  "host_enqueue_us_per_call": round(host_us_per_call, 2),
+                  "rows_moved_per_head_step": round(fused_rows_moved / max(1, n_calls * cfg.batch * cfg.n_heads), 2)}
     dec_k_gbps = dec_bytes / n_calls / (dec_call_ms * 1e-3) / 1e9 if T and dec_call_ms > 0 else 0.0
     sel_k_gbps = sel_bytes / n_calls / (sel_call_ms * 1e-3) / 1e9 if T and sel_call_ms > 0 else 0.0
     roof_decode = {"kernel": "vatp_decode_step = decode_logits_kernel + decode_finish_kernel", "bound": "hbm",
@@ -171,9 +225,15 @@ def run(args):
                    "achieved": round(sel_k_gbps, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                    "frac": round(sel_k_gbps / HBM_PEAK_GBPS, 5), "traffic": traffic.get("select_compact"),
                    "avg_launch_ms": round(sel_call_ms, 5)}
-    phases = {"prefill_score": prefill_ms, "decode_step": dec_call_ms * n_calls, "select_compact": sel_call_ms * n_calls}
+    if fused:
+        phases = {"prefill_score": prefill_ms, "decode_prune_step": fused_call_ms * n_calls}
+    else:
+        phases = {"prefill_score": prefill_ms, "decode_step": dec_call_ms * n_calls,
+                  "select_compact": sel_call_ms * n_calls}
     dominant = max(phases, key=phases.get)
-    roofline = {"prefill_score": roof_prefill, "decode_step": roof_decode, "select_compact": roof_gather}[dominant]
+    roofline_all = {"prefill_score": roof_prefill, "decode_prune_step": roof_fused, "decode_step": roof_decode,
+                    "select_compact": roof_gather}
+    roofline = roofline_all[dominant]
 
     out = {
         "metric": "prefill scoring tokens/s (% MFMA peak) + decode prune step GB/s (% HBM peak)",
@@ -186,13 +246,16 @@ def run(args):
         "config": {"workload": cfg.name, "batch": cfg.batch, "layers": cfg.layers, "n_heads": cfg.n_heads,
                    "head_dim": cfg.head_dim, "prompt_len": lens if cfg.ragged else cfg.prompt_len,
                    "budget_pct": cfg.budget_pct, "recent": cfg.recent, "n_sink": cfg.n_sink_keep,
-                   "decode_steps": T},
+                   "decode_steps": T, "decode_route": args.decode_route},
         "prefill_ms": round(prefill_ms, 4), "prompt_prune_ms": round(prune_ms, 4), "decode_loop_ms": round(decode_ms, 4),
         "prefill_pct_mfma_peak": round(100 * roof_prefill["frac"], 3) if mfma else None,
         "decode_prune_GBps": round(decode_gbps, 2),
         "decode_prune_pct_hbm_peak": round(100 * decode_gbps / HBM_PEAK_GBPS, 3),
         "roofline": roofline,
-        "roofline_all": {"prefill_score": roof_prefill, "decode_step": roof_decode, "select_compact": roof_gather},
+        "roofline_all": roofline_all,
+        # the same decode loop through the other route (per-call event times of the replays)
+        "decode_loop_ms_by_route": {"fused": round(fused_call_ms * n_calls / 1, 4),
+                                    "separate": round((dec_call_ms + sel_call_ms) * n_calls, 4)},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, layers[0], args.cpu_seconds)
@@ -271,6 +334,8 @@ def main():
     ap.add_argument("--workload", default="llama7b_layer", choices=sorted(vs.CONFIGS))
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers of the workload")
     ap.add_argument("--decode-steps", type=int, default=None)
+    ap.add_argument("--decode-route", default="fused", choices=["fused", "separate"],
+                    help="fused: vatp_decode_prune_step; separate: vatp_decode_step + vatp_select_compact")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)

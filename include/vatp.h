@@ -53,7 +53,7 @@ typedef enum {
 enum { VATP_F32 = 0, VATP_BF16 = 1 };
 enum { VATP_NORM_L1 = 0, VATP_NORM_L2 = 1, VATP_NORM_LINF = 2 };
 enum { VATP_CALL_PREFILL_SCORE = 0, VATP_CALL_DECODE_STEP = 1, VATP_CALL_SELECT_COMPACT = 2,
-       VATP_CALL_DECODE_ATTEND_STEP = 3 };
+       VATP_CALL_DECODE_ATTEND_STEP = 3, VATP_CALL_DECODE_PRUNE_STEP = 4 };
 
 typedef struct {
     int32_t batch;          /* 1 .. VATP_MAX_BATCH                                         */
@@ -161,6 +161,40 @@ vatp_status vatp_select_compact(vatp_ctx *ctx, const vatp_params *p,
                                 void *K_out, void *V_out, float *S_out, float *nrm_out,
                                 int32_t *pos_out, int32_t *kept_idx,
                                 void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * The steady state of generation in one call: vatp_decode_step (or vatp_decode_attend_step
+ * when out is not NULL) followed by vatp_select_compact, for caches that hold at most
+ * budget[b] rows before the step, so that at most one row per head leaves (Fig. 2: the new
+ * token is added, the least important unprotected one removed; Eq. 2 incrementally, Eq. 4).
+ * The results are bit-identical to the two separate calls; two launches instead of three, and
+ * the rows that both cache sets already share are not copied again.
+ *
+ * The caller keeps two cache sets and alternates them: (K, V, S, nrm, pos) is the current set
+ * with len[b] rows, (K_out, V_out, S_out, nrm_out, pos_out) the other one.  The call appends the
+ * new row to K, V, nrm, pos (as vatp_decode_step does; S is only read), and makes the *_out set
+ * the pruned state with min(len[b] + 1, budget[b]) rows, which is the current set of the next
+ * call.  synced_in / synced_out: two distinct device int32 arrays [batch * n_heads].
+ * synced_in[u] is the number of leading rows of K_out, V_out, nrm_out, pos_out that already
+ * equal the leading rows of K, V, nrm, pos: 0 before the first call (or whenever the other set
+ * was written by anything but this call), afterwards the array the previous call returned in
+ * synced_out -- the caller swaps the two arrays together with the cache sets and must leave
+ * the other set untouched in between.  synced_out[u] receives the row removed from head u
+ * (len[b] + 1 if none), which is that count for the next call.  Rows from
+ * min(synced_in[u], synced_out[u]) on are rewritten; S_out is rewritten in full.
+ * kept_idx ([batch, n_heads, cap_out], may be NULL) receives the source row of each survivor,
+ * out (device float32 [batch, n_heads, head_dim], may be NULL) the attention output.
+ * Requires len[b] <= budget[b] (VATP_E_BUDGET otherwise) and len[b] + 1 <= cap.
+ * Workspace size: vatp_workspace_bytes(..., VATP_CALL_DECODE_PRUNE_STEP).  new_pos: HOST.
+ */
+vatp_status vatp_decode_prune_step(vatp_ctx *ctx, const vatp_params *p,
+                                   const void *q, const void *k, const void *v,
+                                   void *K, void *V, const float *S, float *nrm, int32_t *pos,
+                                   const int32_t *new_pos,
+                                   void *K_out, void *V_out, float *S_out, float *nrm_out,
+                                   int32_t *pos_out, int32_t *kept_idx,
+                                   const int32_t *synced_in, int32_t *synced_out, float *out,
+                                   void *ws, size_t ws_bytes, void *hip_stream);
 
 #ifdef __cplusplus
 }

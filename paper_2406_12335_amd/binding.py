@@ -18,12 +18,13 @@ LIB_PATH = os.path.join(_HERE, "libvatp.so")
 
 VATP_F32, VATP_BF16 = 0, 1
 NORM_L1, NORM_L2, NORM_LINF = 0, 1, 2
-CALL_PREFILL_SCORE, CALL_DECODE_STEP, CALL_SELECT_COMPACT, CALL_DECODE_ATTEND_STEP = 0, 1, 2, 3
+CALL_PREFILL_SCORE, CALL_DECODE_STEP, CALL_SELECT_COMPACT, CALL_DECODE_ATTEND_STEP, CALL_DECODE_PRUNE_STEP = 0, 1, 2, 3, 4
 VATP_MAX_BATCH, VATP_MAX_UNITS = 64, 16384
 OK, E_NULL, E_SHAPE, E_DTYPE, E_BUDGET, E_WORKSPACE, E_DEVICE = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = ("vatp_create", "vatp_destroy", "vatp_strerror", "vatp_validate", "vatp_workspace_bytes",
-           "vatp_prefill_score", "vatp_prefill_score_lse", "vatp_decode_step", "vatp_decode_attend_step", "vatp_select_compact")
+           "vatp_prefill_score", "vatp_prefill_score_lse", "vatp_decode_step", "vatp_decode_attend_step", "vatp_select_compact",
+           "vatp_decode_prune_step")
 
 
 class VatpError(RuntimeError):
@@ -73,6 +74,9 @@ def load() -> ctypes.CDLL:
     L.vatp_decode_attend_step.argtypes = [_vp, pp] + [_vp] * 8 + [ctypes.POINTER(ctypes.c_int32), _vp, _vp, ctypes.c_size_t,
                                                           _vp]
     L.vatp_decode_attend_step.restype = ctypes.c_int
+    L.vatp_decode_prune_step.argtypes = [_vp, pp] + [_vp] * 8 + [ctypes.POINTER(ctypes.c_int32)] + [_vp] * 9 + \
+        [_vp, ctypes.c_size_t, _vp]
+    L.vatp_decode_prune_step.restype = ctypes.c_int
     L.vatp_select_compact.argtypes = [_vp, pp] + [_vp] * 11 + [_vp, ctypes.c_size_t, _vp]
     L.vatp_select_compact.restype = ctypes.c_int
     _lib = L
@@ -171,6 +175,16 @@ def vatp_decode_attend_step(ctx, p: Params, q, k, v, K, V, S, nrm, pos, new_pos:
                                           _ptr(nrm), _ptr(pos), npos, _ptr(out), _ptr(ws),
                                           ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)),
            "vatp_decode_attend_step")
+
+
+def vatp_decode_prune_step(ctx, p: Params, q, k, v, K, V, S, nrm, pos, new_pos: Optional[Sequence[int]], K_out, V_out,
+                           S_out, nrm_out, pos_out, kept_idx, synced_in, synced_out, out, ws, stream=None) -> None:
+    npos = (ctypes.c_int32 * len(new_pos))(*[int(x) for x in new_pos]) if new_pos is not None else None
+    _check(load().vatp_decode_prune_step(ctx, p.ref(), _ptr(q), _ptr(k), _ptr(v), _ptr(K), _ptr(V), _ptr(S), _ptr(nrm),
+                                         _ptr(pos), npos, _ptr(K_out), _ptr(V_out), _ptr(S_out), _ptr(nrm_out),
+                                         _ptr(pos_out), _ptr(kept_idx), _ptr(synced_in), _ptr(synced_out), _ptr(out),
+                                         _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0,
+                                         _stream(stream)), "vatp_decode_prune_step")
 
 
 def vatp_select_compact(ctx, p: Params, K, V, S, nrm, pos, K_out, V_out, S_out, nrm_out, pos_out, kept_idx,

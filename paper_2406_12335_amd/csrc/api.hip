@@ -24,8 +24,11 @@ struct Prepared {
 vatp_status check_params(const vatp_params *p, int which_call)
 {
     if (!p || !p->len) return VATP_E_NULL;
-    if (which_call == VATP_CALL_SELECT_COMPACT && !p->budget) return VATP_E_NULL;
-    if (which_call < VATP_CALL_PREFILL_SCORE || which_call > VATP_CALL_DECODE_ATTEND_STEP) return VATP_E_SHAPE;
+    const bool prunes = which_call == VATP_CALL_SELECT_COMPACT || which_call == VATP_CALL_DECODE_PRUNE_STEP;
+    const bool decodes = which_call == VATP_CALL_DECODE_STEP || which_call == VATP_CALL_DECODE_ATTEND_STEP ||
+                         which_call == VATP_CALL_DECODE_PRUNE_STEP;
+    if (prunes && !p->budget) return VATP_E_NULL;
+    if (which_call < VATP_CALL_PREFILL_SCORE || which_call > VATP_CALL_DECODE_PRUNE_STEP) return VATP_E_SHAPE;
     if (p->dtype != VATP_F32 && p->dtype != VATP_BF16) return VATP_E_DTYPE;
     if (p->batch < 1 || p->batch > VATP_MAX_BATCH || p->n_heads < 1) return VATP_E_SHAPE;
     if (static_cast<int64_t>(p->batch) * p->n_heads > VATP_MAX_UNITS) return VATP_E_SHAPE;
@@ -42,13 +45,14 @@ vatp_status check_params(const vatp_params *p, int which_call)
     for (int b = 0; b < p->batch; ++b) {
         const int len = p->len[b];
         if (len < 0 || len > p->cap) return VATP_E_SHAPE;
-        const bool decode = which_call == VATP_CALL_DECODE_STEP || which_call == VATP_CALL_DECODE_ATTEND_STEP;
-        if (decode && len + 1 > p->cap) return VATP_E_SHAPE;
-        if (which_call == VATP_CALL_SELECT_COMPACT) {
+        if (decodes && len + 1 > p->cap) return VATP_E_SHAPE;
+        if (prunes) {
             const int B = p->budget[b];
+            const int n = decodes ? len + 1 : len;         // rows the selection sees
             if (B < 0 || B < p->n_sink + p->recent) return VATP_E_BUDGET;
-            const int n_keep = len < B ? len : B;
+            const int n_keep = n < B ? n : B;
             if (n_keep > cap_out) return VATP_E_BUDGET;
+            if (decodes && n > B + 1) return VATP_E_BUDGET;    // the fused step removes one row at most
         }
     }
     return VATP_OK;
@@ -72,7 +76,8 @@ void prepare(const vatp_params *p, int which_call, const int32_t *new_pos, Prepa
         const int len = p->len[b];
         out->meta.len[b] = len;
         int extent = len;
-        if (which_call == VATP_CALL_DECODE_STEP || which_call == VATP_CALL_DECODE_ATTEND_STEP) {
+        if (which_call == VATP_CALL_DECODE_STEP || which_call == VATP_CALL_DECODE_ATTEND_STEP ||
+            which_call == VATP_CALL_DECODE_PRUNE_STEP) {
             out->meta.aux[b] = new_pos ? new_pos[b] : 0;
             extent = len + 1;
         } else if (which_call == VATP_CALL_SELECT_COMPACT) {
@@ -97,7 +102,7 @@ const char *vatp_strerror(vatp_status st)
     case VATP_E_NULL: return "a required pointer is NULL";
     case VATP_E_SHAPE: return "shape out of range (batch, heads, head_dim, cap or len)";
     case VATP_E_DTYPE: return "unsupported dtype";
-    case VATP_E_BUDGET: return "budget smaller than n_sink + recent, or larger than cap_out";
+    case VATP_E_BUDGET: return "budget smaller than n_sink + recent, larger than cap_out, or exceeded by more than one row in the fused step";
     case VATP_E_WORKSPACE: return "workspace missing, too small or misaligned";
     case VATP_E_DEVICE: return "HIP error";
     }
@@ -139,6 +144,7 @@ size_t vatp_workspace_bytes(const vatp_ctx *, const vatp_params *p, int which_ca
         const size_t chunks = (static_cast<size_t>(p->cap) + kDecodeChunk - 1) / kDecodeChunk;
         return align_up(units * p->cap * sizeof(float)) + align_up(units * chunks * sizeof(float2));
     }
+    case VATP_CALL_DECODE_PRUNE_STEP:
     case VATP_CALL_DECODE_ATTEND_STEP: {    // ... + per-chunk partial attention outputs [units, chunks, d]
         const size_t chunks = (static_cast<size_t>(p->cap) + kDecodeChunk - 1) / kDecodeChunk;
         return align_up(units * p->cap * sizeof(float)) + align_up(units * chunks * sizeof(float2)) +
@@ -223,7 +229,7 @@ vatp_status decode_step_impl(vatp_ctx *ctx, const vatp_params *p, int which_call
     float *ws_out = reinterpret_cast<float *>(base + align_up(units * p->cap * sizeof(float)) +
                                               align_up(units * chunks * sizeof(float2)));
     if (launch_decode(p->dtype, p->head_dim, q, k, v, K, V, S, nrm, pos, ws_logit, ws_part, out ? ws_out : nullptr,
-                      out, pr.meta, pr.g, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+                      out, true, pr.meta, pr.g, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
         return VATP_E_DEVICE;
     return VATP_OK;
 }
@@ -247,6 +253,61 @@ vatp_status vatp_decode_attend_step(vatp_ctx *ctx, const vatp_params *p, const v
 {
     return decode_step_impl(ctx, p, VATP_CALL_DECODE_ATTEND_STEP, q, k, v, K, V, S, nrm, pos, new_pos, out, ws,
                             ws_bytes, hip_stream);
+}
+
+vatp_status vatp_decode_prune_step(vatp_ctx *ctx, const vatp_params *p, const void *q, const void *k,
+                                   const void *v, void *K, void *V, const float *S, float *nrm, int32_t *pos,
+                                   const int32_t *new_pos, void *K_out, void *V_out, float *S_out,
+                                   float *nrm_out, int32_t *pos_out, int32_t *kept_idx,
+                                   const int32_t *synced_in, int32_t *synced_out, float *out, void *ws,
+                                   size_t ws_bytes, void *hip_stream)
+{
+    if (!ctx || !q || !k || !v || !K || !V || !S || !nrm || !K_out || !V_out || !S_out || !nrm_out || !synced_in ||
+        !synced_out)
+        return VATP_E_NULL;
+    if ((pos == nullptr) != (pos_out == nullptr) || (pos && !new_pos)) return VATP_E_NULL;
+    const vatp_status st = check_params(p, VATP_CALL_DECODE_PRUNE_STEP);
+    if (st != VATP_OK) return st;
+    if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(K, 16) || misaligned(V, 16) ||
+        misaligned(K_out, 16) || misaligned(V_out, 16))
+        return VATP_E_SHAPE;
+    if (K_out == K || V_out == V || S_out == S || nrm_out == nrm || (pos && pos_out == pos) || synced_in == synced_out)
+        return VATP_E_SHAPE;
+    const size_t need = vatp_workspace_bytes(ctx, p, VATP_CALL_DECODE_PRUNE_STEP);
+    if (!ws || ws_bytes < need || misaligned(ws, kAlign)) return VATP_E_WORKSPACE;
+    Prepared pr;
+    prepare(p, VATP_CALL_DECODE_PRUNE_STEP, pos ? new_pos : nullptr, &pr);
+    const size_t units = static_cast<size_t>(p->batch) * p->n_heads;
+    const size_t chunks = (static_cast<size_t>(p->cap) + kDecodeChunk - 1) / kDecodeChunk;
+    char *base = static_cast<char *>(ws);
+    float *ws_logit = reinterpret_cast<float *>(base);
+    float2 *ws_part = reinterpret_cast<float2 *>(base + align_up(units * p->cap * sizeof(float)));
+    float *ws_out = reinterpret_cast<float *>(base + align_up(units * p->cap * sizeof(float)) +
+                                              align_up(units * chunks * sizeof(float2)));
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    BatchMeta budgets = pr.meta;
+    for (int b = 0; b < p->batch; ++b) budgets.aux[b] = p->budget[b];
+    // One launch with a workgroup per head when there are enough heads to fill the chip that way and
+    // each is short enough for a single workgroup to stream quickly (measured: 19.9 against 22.3 us per
+    // step at 256 heads x 820 rows; slower than two launches at 32 heads x 2049 rows, 23 against 14 us).
+    const bool one = !out && units >= 128 && pr.g.max_len <= 1024 && pr.g.max_len <= decode_prune_one_max_rows();
+    if (one) {
+        if (launch_decode_prune_one(p->dtype, p->head_dim, q, k, v, K, V, S, nrm, pos, K_out, V_out, S_out, nrm_out,
+                                    pos_out, kept_idx, synced_in, synced_out, pr.meta, budgets, pr.g, stream) !=
+            hipSuccess)
+            return VATP_E_DEVICE;
+        return VATP_OK;
+    }
+    // first launch: append the row, logits and chunk statistics (S is not touched)
+    if (launch_decode(p->dtype, p->head_dim, q, k, v, K, V, nullptr, nrm, pos, ws_logit, ws_part,
+                      out ? ws_out : nullptr, out, false, pr.meta, pr.g, stream) != hipSuccess)
+        return VATP_E_DEVICE;
+    // second launch: new scores, the evicted row, the out-of-date rows of the other set
+    if (launch_decode_prune(p->dtype, p->head_dim, K, V, S, nrm, pos, K_out, V_out, S_out, nrm_out, pos_out, kept_idx,
+                            synced_in, synced_out, ws_logit, ws_part, out ? ws_out : nullptr, out, budgets, pr.g,
+                            stream) != hipSuccess)
+        return VATP_E_DEVICE;
+    return VATP_OK;
 }
 
 vatp_status vatp_select_compact(vatp_ctx *ctx, const vatp_params *p, const void *K, const void *V,

@@ -11,9 +11,9 @@
 //           in the workspace, and the one that owns the new row appends k, v, |v|_1 and pos.
 //           With an output pointer (vatp_decode_attend_step) it also reads the V rows and leaves
 //           the chunk's unnormalised share of the attention output (Eq. 1) in the workspace.
-//   finish  same grid, one row per thread: every workgroup merges the unit's few chunk
-//           statistics into log2 sum 2^t and applies S += 2^(t - lse2); 12 bytes per row, a
-//           tiny launch ordered after the first by the stream.
+//   finish  one row per thread: every wavefront merges the unit's few chunk statistics into
+//           log2 sum 2^t and applies S += 2^(t - lse2); 12 bytes per row, a tiny launch
+//           ordered after the first by the stream.
 #include "vatp_device.h"
 
 namespace vatp {
@@ -169,35 +169,30 @@ __global__ __launch_bounds__(256) void decode_finish_kernel(float *__restrict__ 
         logit = ws_logit[unit * cap + r];
         if (r != n0) s_old = S[unit * cap + r];
     }
-    // every thread merges the unit's few chunk statistics itself
+    // the softmax denominator from the unit's chunk statistics (per wavefront, one round trip)
     const int n_chunks = (n + kDecodeChunk - 1) / kDecodeChunk;
     const float2 *part = ws_part + unit * chunks_alloc;
-    float M = -INFINITY;
-    for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, part[c].x);
-    float L = 0.f;
-    for (int c = 0; c < n_chunks; ++c) L += part[c].y * exp2f(part[c].x - M);
+    float M, L;
+    merge_chunk_stats(part, n_chunks, M, L);
     const float lse2 = M + log2f(L);
     if (r < n) S[unit * cap + r] = s_old + exp2f(logit - lse2);
     // attention output of the new token: the chunks' partial sums, rescaled to the common maximum
-    if (out && blockIdx.x == 0 && threadIdx.x < head_dim) {
-        float o = 0.f;
-        for (int c = 0; c < n_chunks; ++c)
-            o += ws_out[(unit * chunks_alloc + c) * head_dim + threadIdx.x] * exp2f(part[c].x - M);
-        out[unit * head_dim + threadIdx.x] = o / L;
-    }
+    if (out && blockIdx.x == 0 && threadIdx.x < head_dim)
+        out[unit * head_dim + threadIdx.x] = merge_chunk_outputs(ws_out + unit * chunks_alloc * head_dim, part, n_chunks,
+                                                                 head_dim, threadIdx.x, M, L);
 }
 
 }  // namespace
 
 hipError_t launch_decode(int dtype, int head_dim, const void *q, const void *k, const void *v,
                          void *K, void *V, float *S, float *nrm, int32_t *pos, float *ws_logit,
-                         float2 *ws_part, float *ws_out, float *out, const BatchMeta &meta,
+                         float2 *ws_part, float *ws_out, float *out, bool finish, const BatchMeta &meta,
                          const Geometry &g, hipStream_t st)
 {
     const int chunks_alloc = (g.cap + kDecodeChunk - 1) / kDecodeChunk;
     const unsigned units = static_cast<unsigned>(g.batch) * g.n_heads;
     dim3 grid((g.max_len + kDecodeChunk - 1) / kDecodeChunk, units), block(256);
-    const bool attend = out != nullptr;
+    const bool attend = ws_out != nullptr;
 #define VATP_DEC(T, D, A)                                                                              \
     hipLaunchKernelGGL((decode_logits_kernel<T, D, A>), grid, block, 0, st, static_cast<const T *>(q),  \
                        static_cast<const T *>(k), static_cast<const T *>(v), static_cast<T *>(K),      \
@@ -210,8 +205,9 @@ hipError_t launch_decode(int dtype, int head_dim, const void *q, const void *k, 
     else VATP_DEC2(bf16_t, 128);
 #undef VATP_DEC2
 #undef VATP_DEC
-    hipLaunchKernelGGL(decode_finish_kernel, dim3((g.max_len + 255) / 256, units), block, 0, st, S, ws_logit, ws_part,
-                       ws_out, out, head_dim, meta, g.n_heads, g.cap, chunks_alloc);
+    if (finish)     // (the fused decode-and-evict step has its own second launch)
+        hipLaunchKernelGGL(decode_finish_kernel, dim3((g.max_len + 255) / 256, units), block, 0, st, S, ws_logit,
+                           ws_part, ws_out, out, head_dim, meta, g.n_heads, g.cap, chunks_alloc);
     return hipGetLastError();
 }
 

@@ -1,0 +1,374 @@
+// Second launch of the fused decode-and-evict step: finishes the softmax of the new query,
+// adds the attention weights to the running scores (paper Eq. 2, incrementally), finds the one
+// row per head that has to leave (smallest S * nrm among the rows that are neither sink nor
+// recent, Eq. 4; the highest index among equals) and brings the other cache set up to date.
+//
+// The two cache sets alternate as input and output.  After a step that removed input row e,
+// the old input set still agrees with the new state in its rows 0 .. e-1, so the next step
+// (which writes into it) only has to rewrite rows from min(synced, e') on, where e' is its own
+// evicted row.  The per-head count `synced` travels in a small device array.  Rows that have
+// just left the recent window carry the smallest accumulated scores, so in practice only about
+// `recent` rows move per step instead of the whole cache; the scores themselves change in
+// every row and are rewritten in full.
+//
+// Grid: (G, units).  Each of a head's G workgroups repeats the cheap part (12 bytes per row
+// from L2: logit, S, nrm) to learn the evicted row by itself, then takes a 1/G share of the
+// stores, so the launch needs no exchange between workgroups and no second pass.
+//
+// Arithmetic is the same, operation for operation, as decode_finish_kernel followed by the
+// evict-one gather, so both routes give identical bits.
+#include "vatp_device.h"
+
+namespace vatp {
+
+namespace {
+
+constexpr int kThreads = 512;
+
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void decode_prune_kernel(
+    const T *__restrict__ K, const T *__restrict__ V, const float *__restrict__ S,
+    const float *__restrict__ nrm, const int32_t *__restrict__ pos, T *__restrict__ K_out,
+    T *__restrict__ V_out, float *__restrict__ S_out, float *__restrict__ nrm_out,
+    int32_t *__restrict__ pos_out, int32_t *__restrict__ kept_idx, const int32_t *__restrict__ synced_in,
+    int32_t *__restrict__ synced_out, const float *__restrict__ ws_logit, const float2 *__restrict__ ws_part,
+    const float *__restrict__ ws_out, float *__restrict__ out, BatchMeta meta, int n_heads, int cap,
+    int cap_out, int chunks_alloc, int n_sink, int recent)
+{
+    constexpr int kE = Elt<T>::kPer16B;
+    constexpr int kLanesPerRow = D / kE;
+    constexpr int kRowsPerPass = kThreads / kLanesPerRow;
+
+    __shared__ unsigned long long s_min[kThreads / 64];
+
+    const size_t unit = blockIdx.y;
+    const int g = blockIdx.x, G = gridDim.x;
+    const int b = static_cast<int>(unit / n_heads);
+    const int n0 = meta.len[b], n = n0 + 1, B = meta.aux[b];
+    const int n_keep = n < B ? n : B;
+    const int tid = threadIdx.x;
+    const float *Su = S + unit * cap;
+    const float *Nu = nrm + unit * cap;
+    const float *Lu = ws_logit + unit * cap;
+
+    const int synced = synced_in[unit];
+    const int lo = n_sink, hi = n - recent;                // rows [lo, hi) may leave
+
+    // the unprotected rows this thread looks at (logit, old score, norm), requested before the
+    // denominator is known so that both round trips to memory overlap
+    constexpr int kScan = 4;
+    float t_r[kScan], s_r[kScan], w_r[kScan];
+#pragma unroll
+    for (int u = 0; u < kScan; ++u) {
+        const int r = lo + tid + u * kThreads;
+        const bool ok = n > B && r < hi;
+        t_r[u] = ok ? Lu[r] : 0.f;
+        s_r[u] = ok && r != n0 ? Su[r] : 0.f;
+        w_r[u] = ok ? Nu[r] : 0.f;
+    }
+
+    // log2 of the softmax denominator from the chunk statistics
+    const int n_chunks = (n + kDecodeChunk - 1) / kDecodeChunk;
+    const float2 *part = ws_part + unit * chunks_alloc;
+    float M, L;
+    merge_chunk_stats(part, n_chunks, M, L);
+    const float lse2 = M + log2f(L);
+
+    auto new_score = [&](int r) { return (r != n0 ? Su[r] : 0.f) + exp2f(Lu[r] - lse2); };
+
+    // the row that leaves: minimise (importance bits, ~row) over the unprotected rows
+    int evicted = n;                                       // n <= B: nothing leaves
+    if (n > B) {
+        unsigned long long best = ~0ull;
+        auto consider = [&](int r, float score, float w) {
+            const unsigned key = __float_as_uint(__fmul_rn(score, w));
+            const unsigned long long c =
+                (static_cast<unsigned long long>(key) << 32) | static_cast<unsigned>(~static_cast<unsigned>(r));
+            best = c < best ? c : best;
+        };
+#pragma unroll
+        for (int u = 0; u < kScan; ++u) {
+            const int r = lo + tid + u * kThreads;
+            if (r < hi) consider(r, s_r[u] + exp2f(t_r[u] - lse2), w_r[u]);
+        }
+        for (int r = lo + tid + kScan * kThreads; r < hi; r += kThreads) consider(r, new_score(r), Nu[r]);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            const unsigned long long o = __shfl_xor(best, off);
+            best = o < best ? o : best;
+        }
+        if ((tid & 63) == 0) s_min[tid >> 6] = best;
+        __syncthreads();
+        best = s_min[0];
+#pragma unroll
+        for (int w = 1; w < kThreads / 64; ++w) best = s_min[w] < best ? s_min[w] : best;
+        evicted = static_cast<int>(~static_cast<unsigned>(best & 0xffffffffull));
+    }
+
+    // scores and source indices of this workgroup's share of the surviving rows
+    {
+        const int share = (n_keep + G - 1) / G;
+        const int o_end = min(n_keep, (g + 1) * share);
+        for (int o = g * share + tid; o < o_end; o += kThreads) {
+            const int src = o + (o >= evicted ? 1 : 0);
+            S_out[unit * cap_out + o] = new_score(src);
+            if (kept_idx) kept_idx[unit * cap_out + o] = src;
+        }
+    }
+
+    // rows of the other set that are out of date: from the first row in which it differs from
+    // the input set, or from the evicted row if that comes earlier
+    const int first = min(synced, evicted);
+    if (g == 0 && tid == 0) synced_out[unit] = evicted;
+    {
+        const uint4 *Ku = reinterpret_cast<const uint4 *>(K + unit * cap * D);
+        const uint4 *Vu = reinterpret_cast<const uint4 *>(V + unit * cap * D);
+        uint4 *Ko = reinterpret_cast<uint4 *>(K_out + unit * cap_out * D);
+        uint4 *Vo = reinterpret_cast<uint4 *>(V_out + unit * cap_out * D);
+        const int sub = tid % kLanesPerRow;
+        const int rloc = tid / kLanesPerRow;
+        for (int o = first + g * kRowsPerPass + rloc; o < n_keep; o += G * kRowsPerPass) {
+            const int src = o + (o >= evicted ? 1 : 0);
+            const uint4 kr = Ku[static_cast<size_t>(src) * kLanesPerRow + sub];
+            const uint4 vr = Vu[static_cast<size_t>(src) * kLanesPerRow + sub];
+            Ko[static_cast<size_t>(o) * kLanesPerRow + sub] = kr;
+            Vo[static_cast<size_t>(o) * kLanesPerRow + sub] = vr;
+            if (sub == 0) {
+                nrm_out[unit * cap_out + o] = Nu[src];
+                if (pos_out) pos_out[unit * cap_out + o] = pos[unit * cap + src];
+            }
+        }
+    }
+
+    // attention output of the new token (optional): the chunks' partial sums on a common maximum
+    if (out && g == 0 && tid < D)
+        out[unit * D + tid] = merge_chunk_outputs(ws_out + unit * chunks_alloc * D, part, n_chunks, D, tid, M, L);
+}
+
+// The whole step in one launch, one workgroup of 16 wavefronts per head: logits of the new query
+// over the head's rows (they stay in LDS), softmax statistics, new scores, the evicted row, and
+// the rows of the other cache set that are out of date.  Used when every head's rows fit the LDS
+// buffer; no workspace traffic and no second launch.  The per-chunk statistics are formed
+// exactly as decode_logits_kernel forms them (128-row chunks, the same butterflies), so the
+// result has the same bits as the two-launch route.
+constexpr int kOneThreads = 1024;
+constexpr int kOneMaxRows = 8192;                          // logits kept in LDS (32 KiB)
+
+template <typename T, int D>
+__global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
+    const T *__restrict__ q, const T *__restrict__ k_new, const T *__restrict__ v_new, T *__restrict__ K,
+    T *__restrict__ V, const float *__restrict__ S, float *__restrict__ nrm, int32_t *__restrict__ pos,
+    T *__restrict__ K_out, T *__restrict__ V_out, float *__restrict__ S_out, float *__restrict__ nrm_out,
+    int32_t *__restrict__ pos_out, int32_t *__restrict__ kept_idx, const int32_t *__restrict__ synced_in,
+    int32_t *__restrict__ synced_out, BatchMeta len_pos, BatchMeta len_budget, int n_heads, int cap, int cap_out,
+    int n_sink, int recent, float scale_log2, int norm)
+{
+    constexpr int kE = Elt<T>::kPer16B;
+    constexpr int kLanesPerRow = D / kE;
+    constexpr int kRowsPerPass = kOneThreads / kLanesPerRow;
+    constexpr int kGroup = 8;                              // row loads in flight per thread
+    constexpr int kWaves = kOneThreads / 64;
+
+    __shared__ float s_logit[kOneMaxRows];
+    __shared__ float2 s_part[kOneMaxRows / kDecodeChunk];
+    __shared__ float s_wave[kWaves];
+    __shared__ float s_new_norm;
+    __shared__ unsigned long long s_min[kWaves];
+
+    const size_t unit = blockIdx.x;
+    const int b = static_cast<int>(unit / n_heads);
+    const int n0 = len_pos.len[b], n = n0 + 1, B = len_budget.aux[b];
+    const int n_keep = n < B ? n : B;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int sub = tid % kLanesPerRow, rloc = tid / kLanesPerRow;
+    const float *Su = S + unit * cap;
+    float *Nu = nrm + unit * cap;
+    const uint4 *Ku = reinterpret_cast<const uint4 *>(K + unit * cap * D);
+    const uint4 *Vu = reinterpret_cast<const uint4 *>(V + unit * cap * D);
+    const uint4 *knew = reinterpret_cast<const uint4 *>(k_new + unit * D);
+    const int synced = synced_in[unit];
+
+    float qf[kE];
+    Elt<T>::unpack(reinterpret_cast<const uint4 *>(q + unit * D)[sub], qf);
+
+    // append the new row: k, v, |v|, pos
+    if (tid < kLanesPerRow) {
+        const uint4 kraw = knew[sub];
+        const uint4 vraw = reinterpret_cast<const uint4 *>(v_new + unit * D)[sub];
+        reinterpret_cast<uint4 *>(K + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = kraw;
+        reinterpret_cast<uint4 *>(V + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = vraw;
+        float vf[kE], a = 0.f;
+        Elt<T>::unpack(vraw, vf);
+#pragma unroll
+        for (int e = 0; e < kE; ++e) a = norm_accum(norm, a, vf[e]);
+#pragma unroll
+        for (int off = kLanesPerRow / 2; off > 0; off >>= 1) a = norm_combine(norm, a, __shfl_xor(a, off));
+        if (sub == 0) {
+            const float new_norm = norm_finish(norm, a);
+            s_new_norm = new_norm;
+            Nu[n0] = new_norm;
+            if (pos) pos[unit * cap + n0] = len_pos.aux[b];
+        }
+    }
+
+    // logits of all rows into LDS; the new row is read from the step's input, not from the cache
+    for (int r0 = 0; r0 < n; r0 += kGroup * kRowsPerPass) {
+        uint4 raw[kGroup];
+#pragma unroll
+        for (int u = 0; u < kGroup; ++u) {
+            const int r = r0 + u * kRowsPerPass + rloc;
+            const uint4 *src = (r == n0) ? knew + sub : Ku + static_cast<size_t>(r) * kLanesPerRow + sub;
+            raw[u] = (r < n) ? *src : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < kGroup; ++u) {
+            const int r = r0 + u * kRowsPerPass + rloc;
+            float kf[kE], dot = 0.f;
+            Elt<T>::unpack(raw[u], kf);
+#pragma unroll
+            for (int e = 0; e < kE; ++e) dot = fmaf(qf[e], kf[e], dot);
+#pragma unroll
+            for (int off = kLanesPerRow / 2; off > 0; off >>= 1) dot += __shfl_xor(dot, off);
+            if (sub == 0 && r < n) s_logit[r] = dot * scale_log2;
+        }
+    }
+    __syncthreads();
+
+    // statistics of every 128-row chunk: two wavefronts per chunk, lane = row within the wavefront's 64
+    const int n_chunks = (n + kDecodeChunk - 1) / kDecodeChunk;
+    for (int base = 0; base < n; base += kOneThreads) {
+        const int r = base + tid;
+        const float t = r < n ? s_logit[r] : -INFINITY;
+        float mx = t;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+        if (lane == 0) s_wave[wave] = mx;
+        __syncthreads();
+        mx = fmaxf(s_wave[wave & ~1], s_wave[wave | 1]);
+        float e = exp2f(t - mx);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) e += __shfl_xor(e, off);
+        __syncthreads();
+        if (lane == 0) s_wave[wave] = e;
+        __syncthreads();
+        const int chunk = (base >> 7) + (wave >> 1);
+        if (lane == 0 && (wave & 1) == 0 && chunk < n_chunks) s_part[chunk] = make_float2(mx, s_wave[wave] + s_wave[wave + 1]);
+        __syncthreads();
+    }
+    float M, L;
+    merge_chunk_stats(s_part, n_chunks, M, L);
+    const float lse2 = M + log2f(L);
+
+    auto new_score = [&](int r) { return (r != n0 ? Su[r] : 0.f) + exp2f(s_logit[r] - lse2); };
+    // (the norm of the row appended above is taken from LDS, not from this launch's own store)
+    auto row_norm = [&](int r) { return r == n0 ? s_new_norm : Nu[r]; };
+
+    // the row that leaves: minimise (importance bits, ~row) over the unprotected rows
+    int evicted = n;
+    if (n > B) {
+        unsigned long long best = ~0ull;
+        for (int r = n_sink + tid; r < n - recent; r += kOneThreads) {
+            const unsigned key = __float_as_uint(__fmul_rn(new_score(r), row_norm(r)));
+            const unsigned long long c =
+                (static_cast<unsigned long long>(key) << 32) | static_cast<unsigned>(~static_cast<unsigned>(r));
+            best = c < best ? c : best;
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            const unsigned long long o = __shfl_xor(best, off);
+            best = o < best ? o : best;
+        }
+        if (lane == 0) s_min[wave] = best;
+        __syncthreads();
+        best = s_min[0];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) best = s_min[w] < best ? s_min[w] : best;
+        evicted = static_cast<int>(~static_cast<unsigned>(best & 0xffffffffull));
+    }
+
+    for (int o = tid; o < n_keep; o += kOneThreads) {
+        const int src = o + (o >= evicted ? 1 : 0);
+        S_out[unit * cap_out + o] = new_score(src);
+        if (kept_idx) kept_idx[unit * cap_out + o] = src;
+    }
+
+    const int first = min(synced, evicted);
+    if (tid == 0) synced_out[unit] = evicted;
+    // The appended row is read back below by other threads than the ones that stored it: make the
+    // stores visible inside the workgroup first.
+    __threadfence_block();
+    __syncthreads();
+    {
+        uint4 *Ko = reinterpret_cast<uint4 *>(K_out + unit * cap_out * D);
+        uint4 *Vo = reinterpret_cast<uint4 *>(V_out + unit * cap_out * D);
+        for (int o = first + rloc; o < n_keep; o += kRowsPerPass) {
+            const int src = o + (o >= evicted ? 1 : 0);
+            const uint4 kr = Ku[static_cast<size_t>(src) * kLanesPerRow + sub];
+            const uint4 vr = Vu[static_cast<size_t>(src) * kLanesPerRow + sub];
+            Ko[static_cast<size_t>(o) * kLanesPerRow + sub] = kr;
+            Vo[static_cast<size_t>(o) * kLanesPerRow + sub] = vr;
+            if (sub == 0) {
+                nrm_out[unit * cap_out + o] = Nu[src];
+                if (pos_out) pos_out[unit * cap_out + o] = pos[unit * cap + src];
+            }
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_decode_prune(int dtype, int head_dim, const void *K, const void *V, const float *S,
+                               const float *nrm, const int32_t *pos, void *K_out, void *V_out, float *S_out,
+                               float *nrm_out, int32_t *pos_out, int32_t *kept_idx, const int32_t *synced_in,
+                               int32_t *synced_out, const float *ws_logit, const float2 *ws_part,
+                               const float *ws_out, float *out, const BatchMeta &meta, const Geometry &g,
+                               hipStream_t st)
+{
+    const int chunks_alloc = (g.cap + kDecodeChunk - 1) / kDecodeChunk;
+    const unsigned units = static_cast<unsigned>(g.batch) * g.n_heads;
+    // enough workgroups per head to occupy the chip once (4 of these fit a compute unit)
+    unsigned G = 1024u / units;
+    G = G < 1u ? 1u : (G > 16u ? 16u : G);
+    dim3 grid(G, units), block(kThreads);
+#define VATP_DP(T, D)                                                                                          \
+    hipLaunchKernelGGL((decode_prune_kernel<T, D>), grid, block, 0, st, static_cast<const T *>(K),               \
+                       static_cast<const T *>(V), S, nrm, pos, static_cast<T *>(K_out), static_cast<T *>(V_out), \
+                       S_out, nrm_out, pos_out, kept_idx, synced_in, synced_out, ws_logit, ws_part, ws_out, out, \
+                       meta, g.n_heads, g.cap, g.cap_out, chunks_alloc, g.n_sink, g.recent)
+    if (dtype == VATP_F32 && head_dim == 64) VATP_DP(float, 64);
+    else if (dtype == VATP_F32) VATP_DP(float, 128);
+    else if (head_dim == 64) VATP_DP(bf16_t, 64);
+    else VATP_DP(bf16_t, 128);
+#undef VATP_DP
+    return hipGetLastError();
+}
+
+}  // namespace vatp
+
+namespace vatp {
+
+int decode_prune_one_max_rows() { return kOneMaxRows; }
+
+hipError_t launch_decode_prune_one(int dtype, int head_dim, const void *q, const void *k, const void *v, void *K,
+                                   void *V, const float *S, float *nrm, int32_t *pos, void *K_out, void *V_out,
+                                   float *S_out, float *nrm_out, int32_t *pos_out, int32_t *kept_idx,
+                                   const int32_t *synced_in, int32_t *synced_out, const BatchMeta &len_pos,
+                                   const BatchMeta &len_budget, const Geometry &g, hipStream_t st)
+{
+    const unsigned units = static_cast<unsigned>(g.batch) * g.n_heads;
+    dim3 grid(units), block(kOneThreads);
+#define VATP_DP1(T, D)                                                                                           \
+    hipLaunchKernelGGL((decode_prune_one_kernel<T, D>), grid, block, 0, st, static_cast<const T *>(q),            \
+                       static_cast<const T *>(k), static_cast<const T *>(v), static_cast<T *>(K),                \
+                       static_cast<T *>(V), S, nrm, pos, static_cast<T *>(K_out), static_cast<T *>(V_out), S_out, \
+                       nrm_out, pos_out, kept_idx, synced_in, synced_out, len_pos, len_budget, g.n_heads, g.cap, \
+                       g.cap_out, g.n_sink, g.recent, g.scale_log2, g.norm)
+    if (dtype == VATP_F32 && head_dim == 64) VATP_DP1(float, 64);
+    else if (dtype == VATP_F32) VATP_DP1(float, 128);
+    else if (head_dim == 64) VATP_DP1(bf16_t, 64);
+    else VATP_DP1(bf16_t, 128);
+#undef VATP_DP1
+    return hipGetLastError();
+}
+
+}  // namespace vatp

@@ -59,6 +59,46 @@ template <> struct Elt<bf16_t> {
     }
 };
 
+// Softmax denominator of one decode step from the per-chunk statistics (max_c, sum_c of
+// 2^(t - max_c)) that the logits launch left behind: M = max_c max_c and
+// L = sum_c sum_c * 2^(max_c - M).  Every wavefront computes both by itself: lanes take chunks
+// lane, lane + 64, ... (one round trip to memory, not one per chunk) and combine with a
+// butterfly, which gives every lane the same bits.  The kernels that finish a decode step all
+// call this one function, so they agree bit for bit.
+__device__ __forceinline__ void merge_chunk_stats(const float2 *__restrict__ part, int n_chunks, float &M, float &L)
+{
+    const int lane = threadIdx.x & 63;
+    float2 mine = make_float2(-INFINITY, 0.f);
+    if (lane < n_chunks) mine = part[lane];
+    float m = mine.x;
+    for (int c = lane + 64; c < n_chunks; c += 64) m = fmaxf(m, part[c].x);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    float l = mine.y * exp2f(mine.x - m);                 // 0 * 2^(-inf) = 0 for lanes without a chunk
+    for (int c = lane + 64; c < n_chunks; c += 64) l += part[c].y * exp2f(part[c].x - m);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) l += __shfl_xor(l, off);
+    M = m;
+    L = l;
+}
+
+// Component x of the attention output (paper Eq. 1) from the chunks' unnormalised partial sums,
+// each relative to its chunk maximum: four independent running sums, so four loads are in flight.
+__device__ __forceinline__ float merge_chunk_outputs(const float *__restrict__ ws_out_unit,
+                                                     const float2 *__restrict__ part, int n_chunks, int head_dim,
+                                                     int x, float M, float L)
+{
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int c0 = 0; c0 < n_chunks; c0 += 4) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int c = c0 + u;
+            if (c < n_chunks) acc[u] += ws_out_unit[static_cast<size_t>(c) * head_dim + x] * exp2f(part[c].x - M);
+        }
+    }
+    return ((acc[0] + acc[1]) + (acc[2] + acc[3])) / L;
+}
+
 // ---- host-side launchers, one per source file --------------------------------------
 hipError_t launch_l1norm(int dtype, int head_dim, const void *V, float *nrm,
                          const BatchMeta &meta, const Geometry &g, hipStream_t st);
@@ -75,8 +115,25 @@ hipError_t launch_prefill_mfma(const void *Q, const void *K, float *S, float *ls
 
 hipError_t launch_decode(int dtype, int head_dim, const void *q, const void *k, const void *v,
                          void *K, void *V, float *S, float *nrm, int32_t *pos,
-                         float *ws_logit, float2 *ws_part, float *ws_out, float *out, const BatchMeta &meta,
-                         const Geometry &g, hipStream_t st);
+                         float *ws_logit, float2 *ws_part, float *ws_out, float *out, bool finish,
+                         const BatchMeta &meta, const Geometry &g, hipStream_t st);
+
+// second launch of the fused decode-and-evict step; meta.aux holds the budgets
+hipError_t launch_decode_prune(int dtype, int head_dim, const void *K, const void *V, const float *S,
+                               const float *nrm, const int32_t *pos, void *K_out, void *V_out, float *S_out,
+                               float *nrm_out, int32_t *pos_out, int32_t *kept_idx, const int32_t *synced_in,
+                               int32_t *synced_out, const float *ws_logit, const float2 *ws_part,
+                               const float *ws_out, float *out, const BatchMeta &meta, const Geometry &g,
+                               hipStream_t st);
+
+// the same step in one launch, one workgroup per head; usable while every head has at most
+// decode_prune_one_max_rows() rows after the append
+int decode_prune_one_max_rows();
+hipError_t launch_decode_prune_one(int dtype, int head_dim, const void *q, const void *k, const void *v, void *K,
+                                   void *V, const float *S, float *nrm, int32_t *pos, void *K_out, void *V_out,
+                                   float *S_out, float *nrm_out, int32_t *pos_out, int32_t *kept_idx,
+                                   const int32_t *synced_in, int32_t *synced_out, const BatchMeta &len_pos,
+                                   const BatchMeta &len_budget, const Geometry &g, hipStream_t st);
 
 hipError_t launch_select(const float *S, const float *nrm, int32_t *kept_idx,
                          const BatchMeta &meta, const Geometry &g, hipStream_t st);

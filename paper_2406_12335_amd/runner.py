@@ -7,6 +7,7 @@ It computes nothing itself.
 """
 from __future__ import annotations
 
+import ctypes
 from typing import List, Optional, Sequence
 
 import torch
@@ -33,16 +34,29 @@ class PrunedKVCache:
         self.nrm = [mk(*shape, dt=torch.float32) for _ in range(2)]
         self.pos = [mk(*shape, dt=torch.int32) for _ in range(2)] if track_pos else [None, None]
         self.kept_idx = mk(*shape, dt=torch.int32)
+        # leading rows the two sets share, per head, as the fused step leaves it (two arrays: one is
+        # read while the other is written); synced_cur indexes the valid one
+        self.synced = [torch.zeros(batch * n_heads, dtype=torch.int32, device=self.device) for _ in range(2)]
+        self.synced_cur = 0
+        self._synced_valid = False       # False: the other set holds nothing of the current state
         self.cur = 0
         self.lens: List[int] = [0] * batch
         self._p_dec = B.Params(batch, n_heads, head_dim, dtype, n_sink, recent, self.cap, self.lens, self.budgets,
                                norm=norm)
         # sized for the fullest cache a decode step may meet (cap - 1 rows plus the new one)
         self._p_dec.set_len([self.cap - 1] * batch)
-        nbytes = B.vatp_workspace_bytes(self.ctx, self._p_dec, B.CALL_DECODE_STEP)
+        nbytes = B.vatp_workspace_bytes(self.ctx, self._p_dec, B.CALL_DECODE_ATTEND_STEP)   # the largest of the decode calls
         self._p_dec.set_len(self.lens)
         self.ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.device)
         self.S_prompt = self.nrm_prompt = None
+        # The decode calls are made once per generated token: their device pointers are converted to
+        # ctypes values once, here, instead of on every call.
+        vp = lambda t: ctypes.c_void_p(t.data_ptr()) if t is not None else None
+        self._cp = {name: [vp(x) for x in getattr(self, name)] for name in ("K", "V", "S", "nrm", "pos", "synced")}
+        self._cp_kept, self._cp_ws = vp(self.kept_idx), vp(self.ws)
+        self._ws_bytes = self.ws.numel()
+        self._npos = (ctypes.c_int32 * batch)()
+        self._lib = B.load()
 
     def close(self):
         if self._own_ctx and self.ctx is not None:
@@ -80,20 +94,57 @@ class PrunedKVCache:
         B.vatp_select_compact(self.ctx, p, K, V, self.S_prompt, self.nrm_prompt, pos_in, self.K[0], self.V[0],
                               self.S[0], self.nrm[0], self.pos[0], self.kept_idx, None, stream)
         self.lens = [min(n, bud) for n, bud in zip(self._prompt_lens, self.budgets)]
+        self._synced_valid = False
 
     # -- decode ----------------------------------------------------------------------
+    def _new_pos(self, new_pos):
+        if self.pos[0] is None or new_pos is None:
+            return None
+        for i, x in enumerate(new_pos):
+            self._npos[i] = x
+        return self._npos
+
+    @staticmethod
+    def _qkv(q, k, v):
+        if not (q.is_contiguous() and k.is_contiguous() and v.is_contiguous()):
+            raise ValueError("vatp: tensors must be contiguous")
+        return ctypes.c_void_p(q.data_ptr()), ctypes.c_void_p(k.data_ptr()), ctypes.c_void_p(v.data_ptr())
+
     def decode_step(self, q, k, v, new_pos: Optional[Sequence[int]], stream=None):
-        c = self.cur
+        c, cp = self.cur, self._cp
         self._p_dec.set_len(self.lens)
-        B.vatp_decode_step(self.ctx, self._p_dec, q, k, v, self.K[c], self.V[c], self.S[c], self.nrm[c],
-                           self.pos[c], new_pos if self.pos[c] is not None else None, self.ws, stream)
+        st = self._lib.vatp_decode_step(self.ctx, self._p_dec.ref(), *self._qkv(q, k, v), cp["K"][c], cp["V"][c],
+                                        cp["S"][c], cp["nrm"][c], cp["pos"][c], self._new_pos(new_pos), self._cp_ws,
+                                        self._ws_bytes, B._stream(stream))
+        B._check(st, "vatp_decode_step")
         self.lens = [n + 1 for n in self.lens]
 
     def prune(self, stream=None):
-        c, o = self.cur, 1 - self.cur
+        c, o, cp = self.cur, 1 - self.cur, self._cp
         self._p_dec.set_len(self.lens)
-        B.vatp_select_compact(self.ctx, self._p_dec, self.K[c], self.V[c], self.S[c], self.nrm[c], self.pos[c],
-                              self.K[o], self.V[o], self.S[o], self.nrm[o], self.pos[o], self.kept_idx, None,
-                              stream)
+        st = self._lib.vatp_select_compact(self.ctx, self._p_dec.ref(), cp["K"][c], cp["V"][c], cp["S"][c], cp["nrm"][c],
+                                           cp["pos"][c], cp["K"][o], cp["V"][o], cp["S"][o], cp["nrm"][o], cp["pos"][o],
+                                           self._cp_kept, None, 0, B._stream(stream))
+        B._check(st, "vatp_select_compact")
         self.cur = o
         self.lens = [min(n, bud) for n, bud in zip(self.lens, self.budgets)]
+        self._synced_valid = False                    # not tracked by this route
+
+    def decode_prune_step(self, q, k, v, new_pos: Optional[Sequence[int]], out=None, want_kept_idx: bool = True,
+                          stream=None):
+        """vatp_decode_prune_step: decode_step + prune in two launches, rewriting only the rows that changed."""
+        c, o = self.cur, 1 - self.cur
+        si, so = self.synced_cur, 1 - self.synced_cur
+        if not self._synced_valid:
+            self.synced[si].zero_()
+            self._synced_valid = True
+        self._p_dec.set_len(self.lens)
+        cp = self._cp
+        st = self._lib.vatp_decode_prune_step(
+            self.ctx, self._p_dec.ref(), *self._qkv(q, k, v), cp["K"][c], cp["V"][c], cp["S"][c], cp["nrm"][c],
+            cp["pos"][c], self._new_pos(new_pos), cp["K"][o], cp["V"][o], cp["S"][o], cp["nrm"][o], cp["pos"][o],
+            self._cp_kept if want_kept_idx else None, ctypes.c_void_p(self.synced[si].data_ptr()),
+            ctypes.c_void_p(self.synced[so].data_ptr()), B._ptr(out), self._cp_ws, self._ws_bytes, B._stream(stream))
+        B._check(st, "vatp_decode_prune_step")
+        self.cur, self.synced_cur = o, so
+        self.lens = [min(n + 1, bud) for n, bud in zip(self.lens, self.budgets)]

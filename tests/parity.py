@@ -84,8 +84,11 @@ def _vec(t: torch.Tensor) -> np.ndarray:
 
 def run_trajectory(inp, device, units: Optional[Sequence[Tuple[int, int]]] = None, steps: Optional[int] = None,
                    n_sink: Optional[int] = None, check_every: int = 1, cap_cache: Optional[int] = None,
-                   full_prefill_check: bool = True, norm_kind: int = 0) -> TrajectoryReport:
-    """Prompt pass -> prune -> decode/prune steps on the GPU, mirrored by OracleHead on the chosen units."""
+                   full_prefill_check: bool = True, norm_kind: int = 0, fused: bool = False) -> TrajectoryReport:
+    """Prompt pass -> prune -> decode/prune steps on the GPU, mirrored by OracleHead on the chosen units.
+
+    fused: every decode step and its prune go through vatp_decode_prune_step instead of
+    vatp_decode_step + vatp_select_compact; the state after each step is compared with the oracle's."""
     cfg = inp.cfg
     b, H, d = cfg.batch, cfg.n_heads, cfg.head_dim
     F = cfg.n_sink_keep if n_sink is None else n_sink
@@ -148,7 +151,37 @@ def run_trajectory(inp, device, units: Optional[Sequence[Tuple[int, int]]] = Non
         cache.prune_prompt(K, V)
         check_prune(K, V, cache.S_prompt, cache.nrm_prompt, cache._pos_prompt, n_before)
 
-        for t in range(T):
+        def check_fused_step(t, n_before: List[int], do_check: bool):
+            torch.cuda.synchronize()
+            c = cache.cur
+            for (bb, hh), o in heads.items():
+                n, Bq = n_before[bb], inp.budgets[bb]
+                nk = min(n, Bq)
+                kept_gpu = cache.kept_idx[bb, hh, :nk].cpu().numpy()
+                same, _ = check_kept_set(kept_gpu, o.importance(), n, Bq, F, R, rtol)
+                rep.prune_events += 1
+                rep.admitted_near_ties += 0 if same else 1
+                o.prune(Bq, F, R, forced=kept_gpu)
+                if not do_check:
+                    continue
+                e = assert_scores_close(_unit_rows(cache.S[c], bb, hh, nk), o.S, rtol,
+                                        "fused step %d S unit (%d,%d)" % (t, bb, hh))
+                rep.max_rel_err_decode = max(rep.max_rel_err_decode, e)
+                assert_scores_close(_unit_rows(cache.nrm[c], bb, hh, nk), o.nrm, rtol, "fused nrm")
+                assert np.array_equal(_unit_rows(cache.K[c], bb, hh, nk), o.K), "fused: K rows differ from oracle"
+                assert np.array_equal(_unit_rows(cache.V[c], bb, hh, nk), o.V), "fused: V rows differ from oracle"
+                assert np.array_equal(cache.pos[c][bb, hh, :nk].cpu().numpy(), o.pos), "fused: positions differ"
+
+        for t in range(T if fused else 0):
+            new_pos = [L + t for L in inp.lens]
+            n_before = [n + 1 for n in cache.lens]
+            cache.decode_prune_step(qd[t], kd[t], vd[t], new_pos)
+            for (bb, hh), o in heads.items():
+                o.append_and_score(_vec(inp.qd[t, bb, hh]), _vec(inp.kd[t, bb, hh]), _vec(inp.vd[t, bb, hh]),
+                                   new_pos[bb])
+            check_fused_step(t, n_before, (t % check_every == 0) or t == T - 1)
+
+        for t in range(0 if fused else T):
             c = cache.cur
             new_pos = [L + t for L in inp.lens]
             cache.decode_step(qd[t], kd[t], vd[t], new_pos)

@@ -38,6 +38,7 @@ def test_validate_accepts_good_params():
     for call in (vatp.CALL_PREFILL_SCORE, vatp.CALL_SELECT_COMPACT):
         assert vatp.vatp_validate(_params(), call) == binding.OK
     assert vatp.vatp_validate(_params(len=[63, 10]), vatp.CALL_DECODE_STEP) == binding.OK
+    assert vatp.vatp_validate(_params(len=[32, 10]), vatp.CALL_DECODE_PRUNE_STEP) == binding.OK
 
 
 @pytest.mark.parametrize("kw,call,want", [
@@ -53,6 +54,9 @@ def test_validate_accepts_good_params():
     (dict(cap_out=16), vatp.CALL_SELECT_COMPACT, binding.E_BUDGET),       # survivors do not fit
     (dict(budget=None), vatp.CALL_SELECT_COMPACT, binding.E_NULL),
     (dict(len=None), 0, binding.E_NULL),
+    (dict(len=[33, 10]), vatp.CALL_DECODE_PRUNE_STEP, binding.E_BUDGET),  # two rows would have to leave
+    (dict(len=[64, 10]), vatp.CALL_DECODE_PRUNE_STEP, binding.E_SHAPE),   # no room to append
+    (dict(budget=None), vatp.CALL_DECODE_PRUNE_STEP, binding.E_NULL),
     (dict(scale=float("nan")), 0, binding.E_SHAPE),
     (dict(n_sink=-1), 0, binding.E_SHAPE),
 ])
@@ -76,6 +80,7 @@ def test_entry_points_reject_null_before_any_launch():
     assert lib.vatp_prefill_score(None, p.ref(), None, None, None, None, None, None, 0, None) == binding.E_NULL
     assert lib.vatp_decode_step(None, p.ref(), *([None] * 9), None, 0, None) == binding.E_NULL
     assert lib.vatp_select_compact(None, p.ref(), *([None] * 11), None, 0, None) == binding.E_NULL
+    assert lib.vatp_decode_prune_step(None, p.ref(), *([None] * 18), None, 0, None) == binding.E_NULL
     assert "NULL" in vatp.strerror(binding.E_NULL)
     assert vatp.strerror(-99) == "unknown status"
 

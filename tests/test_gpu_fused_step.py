@@ -1,0 +1,142 @@
+"""GPU parity of vatp_decode_prune_step (decode step + eviction in two launches, rewriting only
+the rows that changed): against the oracle through whole trajectories, and bit for bit
+against the route through vatp_decode_attend_step + vatp_select_compact."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import parity
+import vatp_synth as vs
+import paper_2406_12335_amd as vatp
+from paper_2406_12335_amd.runner import PrunedKVCache
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.mark.parametrize("name,kw", [
+    ("tiny", {}),
+    ("llama7b_layer", dict(n_heads=4, prompt_len=777, decode_steps=24)),
+    ("ragged16", dict(batch=6, n_heads=2, decode_steps=10, recent=8, ragged=(1, 600))),
+    # 128 heads or more with short caches take the single-launch route
+    ("tiny", dict(batch=4, n_heads=32, prompt_len=96, decode_steps=12, recent=8)),
+    ("llama7b_layer", dict(batch=2, n_heads=64, prompt_len=150, decode_steps=8, recent=16)),
+])
+def test_fused_trajectory_against_oracle(gpu_device, name, kw):
+    cfg = vs.scaled(vs.CONFIGS[name], **kw) if kw else vs.CONFIGS[name]
+    _say("fused trajectory %s %r" % (name, kw))
+    inp = vs.make_inputs(cfg, seed=31)
+    # budgets below F + R are not allowed: lift tiny ones
+    inp.budgets = [max(b, cfg.n_sinks + cfg.recent) for b in inp.budgets]
+    _say("lens=%s budgets=%s" % (inp.lens[:8], inp.budgets[:8]))
+    rep = parity.run_trajectory(inp, gpu_device, fused=True)
+    _say("report %r" % rep)
+    assert rep.prune_events > 0
+
+
+def _twin_caches(dev, b, H, d, tdt, F, R, budgets, cap):
+    return [PrunedKVCache(b, H, d, tdt, F, R, budgets, dev, cap_cache=cap) for _ in range(2)]
+
+
+def _seed_state(caches, lens, g, d, tdt, dev, weak_rows=None):
+    """Puts the same synthetic cache state (as if left by a prompt prune) into set 0 of each cache."""
+    a = caches[0]
+    b, H, cap = a.batch, a.n_heads, a.cap
+    K = (torch.randn(b, H, cap, d, generator=g) * 1.2).to(tdt)
+    V = (torch.randn(b, H, cap, d, generator=g) * torch.exp(0.5 * torch.randn(b, H, cap, 1, generator=g))).to(tdt)
+    S = torch.rand(b, H, cap, generator=g) + 0.5
+    if weak_rows:
+        for (bb, hh, r) in weak_rows:       # a row that will lose: almost no value norm
+            V[bb, hh, r] = (V[bb, hh, r].float() * 1e-4).to(tdt)
+    nrm = V.float().abs().sum(-1)
+    pos = torch.arange(cap, dtype=torch.int32).expand(b, H, cap).contiguous()
+    for c in caches:
+        c.K[0].copy_(K.to(dev)); c.V[0].copy_(V.to(dev)); c.S[0].copy_(S.to(dev)); c.nrm[0].copy_(nrm.to(dev))
+        c.pos[0].copy_(pos.to(dev))
+        for t in (c.K[1], c.V[1]):
+            t.fill_(7.0)                    # the other set starts as garbage
+        c.S[1].fill_(-3.0); c.nrm[1].fill_(-3.0); c.pos[1].fill_(-3)
+        c.cur = 0
+        c.lens = list(lens)
+        c._synced_valid = False
+
+
+@pytest.mark.parametrize("dtype,d,H,lens,budgets,R,F,steps", [
+    ("bf16", 128, 3, [300, 290, 64], [300, 300, 70], 16, 2, 14),   # at budget, growing, growing then at budget
+    ("fp32", 64, 3, [129, 40, 128], [129, 129, 129], 8, 0, 10),
+    ("bf16", 64, 3, [513, 512, 100], [513, 513, 513], 32, 4, 9),
+    ("fp32", 128, 3, [70, 70, 3], [70, 70, 70], 5, 1, 8),
+    # 128 heads and more: the steps without attention output take the single-launch route
+    ("bf16", 128, 43, [300, 290, 64], [300, 300, 70], 16, 2, 8),
+    ("fp32", 64, 64, [1000, 129], [1000, 140], 8, 0, 7),
+    ("bf16", 64, 32, [5, 130, 129, 257], [9, 130, 200, 257], 3, 1, 9),
+])
+def test_fused_step_is_bit_identical_to_the_two_call_route(gpu_device, dtype, d, H, lens, budgets, R, F, steps):
+    """Same K, V, S, nrm, pos, kept_idx and attention output as vatp_decode_attend_step followed by
+    vatp_select_compact, step after step; includes heads whose evicted row lies far from the window."""
+    dev = gpu_device
+    tdt = torch.float32 if dtype == "fp32" else torch.bfloat16
+    b = len(lens)
+    cap = max(budgets) + 1
+    g = torch.Generator().manual_seed(5)
+    _say("fused vs two calls %s d=%d lens=%s budgets=%s" % (dtype, d, lens, budgets))
+    classic, fused = _twin_caches(dev, b, H, d, tdt, F, R, budgets, cap)
+    try:
+        weak = [(0, 1, F + 3), (0, 2, lens[0] // 2), (1, 0, F + 1), (1, H - 1, F)]
+        _seed_state([classic, fused], lens, g, d, tdt, dev, weak_rows=weak)
+        ws_att = torch.empty(vatp.vatp_workspace_bytes(classic.ctx, classic._p_dec, vatp.CALL_DECODE_ATTEND_STEP) + 256,
+                             dtype=torch.uint8, device=dev)
+        for t in range(steps):
+            q, k, v = ((torch.randn(b, H, d, generator=g) * 1.5).to(tdt).to(dev) for _ in range(3))
+            new_pos = [1000 + t] * b
+            out_c = torch.zeros(b, H, d, device=dev)
+            out_f = torch.ones(b, H, d, device=dev)
+            # two-call route (with attention output)
+            c = classic.cur
+            classic._p_dec.set_len(classic.lens)
+            vatp.vatp_decode_attend_step(classic.ctx, classic._p_dec, q, k, v, classic.K[c], classic.V[c], classic.S[c],
+                                         classic.nrm[c], classic.pos[c], new_pos, out_c, ws_att)
+            classic.lens = [n + 1 for n in classic.lens]
+            classic.prune()
+            # fused route; every third step without kept_idx and without the attention output
+            plain = t % 3 == 2
+            fused.decode_prune_step(q, k, v, new_pos, out=None if plain else out_f, want_kept_idx=not plain)
+            torch.cuda.synchronize()
+            assert classic.lens == fused.lens
+            cc, fc = classic.cur, fused.cur
+            for bb, n in enumerate(fused.lens):
+                for name in ("K", "V", "S", "nrm", "pos"):
+                    x, y = getattr(classic, name)[cc][bb, :, :n], getattr(fused, name)[fc][bb, :, :n]
+                    assert torch.equal(x, y), "step %d sequence %d: %s differs" % (t, bb, name)
+                if not plain:
+                    assert torch.equal(classic.kept_idx[bb, :, :n], fused.kept_idx[bb, :, :n]), "kept_idx differs"
+            if not plain:
+                assert torch.equal(out_c, out_f), "attention output differs at step %d" % t
+    finally:
+        torch.cuda.synchronize()
+        classic.close(); fused.close()
+
+
+def test_fused_step_rejects_more_than_one_eviction_and_aliases(gpu_device):
+    dev = gpu_device
+    b, H, d, cap = 1, 2, 128, 40
+    c = PrunedKVCache(b, H, d, torch.bfloat16, 1, 4, [30], dev, cap_cache=cap)
+    try:
+        x = torch.zeros(b, H, d, dtype=torch.bfloat16, device=dev)
+        c.lens = [31]                       # 32 rows after the append: two would have to leave
+        with pytest.raises(vatp.VatpError) as e:
+            c.decode_prune_step(x, x, x, [0])
+        assert e.value.status == vatp.binding.E_BUDGET
+        c.lens = [30]
+        c.synced[1] = c.synced[0]           # the two count arrays must be distinct
+        with pytest.raises(vatp.VatpError) as e:
+            c.decode_prune_step(x, x, x, [0])
+        assert e.value.status == vatp.binding.E_SHAPE
+    finally:
+        c.close()
