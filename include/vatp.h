@@ -51,7 +51,7 @@ typedef enum {
 } vatp_status;
 
 enum { VATP_F32 = 0, VATP_BF16 = 1 };
-enum { VATP_NORM_L1 = 0, VATP_NORM_L2 = 1, VATP_NORM_LINF = 2 };
+enum { VATP_NORM_L1 = 0, VATP_NORM_L2 = 1, VATP_NORM_LINF = 2, VATP_NORM_NONE = 3 };
 enum { VATP_CALL_PREFILL_SCORE = 0, VATP_CALL_DECODE_STEP = 1, VATP_CALL_SELECT_COMPACT = 2,
        VATP_CALL_DECODE_ATTEND_STEP = 3, VATP_CALL_DECODE_PRUNE_STEP = 4 };
 
@@ -70,7 +70,8 @@ typedef struct {
     const int32_t *budget;  /* HOST [batch]: B, rows kept per head (F and R included).     */
                             /*   only vatp_select_compact reads it; may be NULL elsewhere  */
     int32_t norm;           /* value-row norm of Eq. 4: VATP_NORM_L1 (0, the paper's choice), */
-                            /*   VATP_NORM_L2 or VATP_NORM_LINF (the ablation of Table 2)      */
+                            /*   VATP_NORM_L2 or VATP_NORM_LINF (the ablation of Table 2), or  */
+                            /*   VATP_NORM_NONE: nrm = 1, the attention-only baseline (H2O)    */
 } vatp_params;
 
 /* Creates a context for HIP device `device` (host memory only).  The device must be the

@@ -184,7 +184,7 @@ void vatp_oracle_vnorm(const double *V, int64_t n, int64_t d, int kind, double *
             else if (kind == 1) s += a * a;
             else if (a > s) s = a;
         }
-        nrm[r] = kind == 1 ? sqrt(s) : s;
+        nrm[r] = kind == 1 ? sqrt(s) : kind == 3 ? 1.0 : s;
     }
 }
 

@@ -179,7 +179,8 @@ def l1norm(V) -> np.ndarray:
 
 
 def vnorm(V, kind: int = 0) -> np.ndarray:
-    """Row norms for the ablation of Table 2: kind 0 = l1, 1 = l2, 2 = l-infinity."""
+    """Row norms for the ablation of Table 2: kind 0 = l1, 1 = l2, 2 = l-infinity; 3 = all ones, the
+    attention-only ranking the paper compares against (H2O)."""
     V = _f64(V)
     n, d = V.shape
     out = np.zeros(n, dtype=np.float64)

@@ -36,7 +36,7 @@ vatp_status check_params(const vatp_params *p, int which_call)
     if (p->cap < 1 || p->cap_out < 0 || p->n_sink < 0 || p->recent < 0) return VATP_E_SHAPE;
     if (p->cap > VATP_MAX_CAP || p->cap_out > VATP_MAX_CAP) return VATP_E_SHAPE;   // 32-bit byte offsets inside a unit
     if (!(p->scale >= 0.f) || isinf(p->scale)) return VATP_E_SHAPE;
-    if (p->norm < VATP_NORM_L1 || p->norm > VATP_NORM_LINF) return VATP_E_SHAPE;
+    if (p->norm < VATP_NORM_L1 || p->norm > VATP_NORM_NONE) return VATP_E_SHAPE;
     // element counts of one buffer stay below 2^40 (indexing is 64-bit, row indices 32-bit)
     if (static_cast<double>(p->batch) * p->n_heads * static_cast<double>(p->cap > p->cap_out ? p->cap : p->cap_out) *
             p->head_dim > 1099511627776.0)

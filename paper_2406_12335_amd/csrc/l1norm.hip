@@ -25,20 +25,28 @@ __global__ __launch_bounds__(256) void l1norm_kernel(const T *__restrict__ V,
 
     const int sub = threadIdx.x % kLanesPerRow;
     const int rloc = threadIdx.x / kLanesPerRow;
-#pragma unroll 4
-    for (int pass = 0; pass < kRowsPerBlock / kRowsPerPass; ++pass) {
-        const int r = row0 + pass * kRowsPerPass + rloc;
-        float acc = 0.f;
-        if (r < len) {
-            const uint4 raw = Vu[static_cast<size_t>(r) * kLanesPerRow + sub];
-            float x[kE];
-            Elt<T>::unpack(raw, x);
+    // all of the workgroup's row loads are issued before the first one is used
+    constexpr int kPasses = kRowsPerBlock / kRowsPerPass;
+    constexpr int kGroup = kPasses < 16 ? kPasses : 16;
 #pragma unroll
-            for (int e = 0; e < kE; ++e) acc = norm_accum(norm, acc, x[e]);
+    for (int p0 = 0; p0 < kPasses; p0 += kGroup) {
+        uint4 raw[kGroup];
+#pragma unroll
+        for (int u = 0; u < kGroup; ++u) {
+            const int r = row0 + (p0 + u) * kRowsPerPass + rloc;
+            raw[u] = r < len ? Vu[static_cast<size_t>(r) * kLanesPerRow + sub] : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
-        for (int off = kLanesPerRow / 2; off > 0; off >>= 1) acc = norm_combine(norm, acc, __shfl_xor(acc, off));
-        if (sub == 0 && r < len) nu[r] = norm_finish(norm, acc);
+        for (int u = 0; u < kGroup; ++u) {
+            const int r = row0 + (p0 + u) * kRowsPerPass + rloc;
+            float x[kE], acc = 0.f;
+            Elt<T>::unpack(raw[u], x);
+#pragma unroll
+            for (int e = 0; e < kE; ++e) acc = norm_accum(norm, acc, x[e]);
+#pragma unroll
+            for (int off = kLanesPerRow / 2; off > 0; off >>= 1) acc = norm_combine(norm, acc, __shfl_xor(acc, off));
+            if (sub == 0 && r < len) nu[r] = norm_finish(norm, acc);
+        }
     }
 }
 

@@ -33,7 +33,9 @@ __device__ __forceinline__ float norm_accum(int kind, float acc, float x) {
 __device__ __forceinline__ float norm_combine(int kind, float a, float b) {
     return kind == VATP_NORM_LINF ? fmaxf(a, b) : a + b;
 }
-__device__ __forceinline__ float norm_finish(int kind, float a) { return kind == VATP_NORM_L2 ? sqrtf(a) : a; }
+__device__ __forceinline__ float norm_finish(int kind, float a) {
+    return kind == VATP_NORM_L2 ? sqrtf(a) : kind == VATP_NORM_NONE ? 1.f : a;     // NONE: attention-only baseline
+}
 
 constexpr int kDecodeChunk = 128;  // rows of one unit handled by one workgroup of the decode GEMV
 

@@ -97,7 +97,7 @@ def test_create_without_device_is_an_error_not_a_crash():
 
 
 def test_validate_rejects_unknown_norm():
-    assert vatp.vatp_validate(_params(norm=3), 0) == binding.E_SHAPE
+    assert vatp.vatp_validate(_params(norm=4), 0) == binding.E_SHAPE
     assert vatp.vatp_validate(_params(norm=-1), 0) == binding.E_SHAPE
-    for kind in (vatp.NORM_L1, vatp.NORM_L2, vatp.NORM_LINF):
+    for kind in (vatp.NORM_L1, vatp.NORM_L2, vatp.NORM_LINF, vatp.NORM_NONE):
         assert vatp.vatp_validate(_params(norm=kind), 0) == binding.OK

@@ -18,10 +18,11 @@ def _say(msg):
     sys.stdout.flush()
 
 
-@pytest.mark.parametrize("norm_kind", [vatp.NORM_L2, vatp.NORM_LINF])
+@pytest.mark.parametrize("norm_kind", [vatp.NORM_L2, vatp.NORM_LINF, vatp.NORM_NONE])
 @pytest.mark.parametrize("dtype,d", [("bf16", 128), ("fp32", 64)])
 def test_norm_ablation_trajectories(gpu_device, norm_kind, dtype, d):
-    """The l2 and l-infinity value norms of the paper's ablation (Table 2) through a whole trajectory."""
+    """The l2 and l-infinity value norms of the paper's ablation (Table 2), and the attention-only
+    baseline (norm switched off), through a whole trajectory."""
     cfg = vs.scaled(vs.CONFIGS["llama7b_layer"], n_heads=3, head_dim=d, prompt_len=333, dtype=dtype,
                     budget_pct=40, recent=32, decode_steps=12)
     _say("norm kind %d %s d=%d" % (norm_kind, dtype, d))

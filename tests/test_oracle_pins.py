@@ -289,6 +289,10 @@ def test_value_norms_match_numpy_and_their_inequalities():
     onehot = np.eye(16)[[3, 7]] * np.array([[2.5], [-4.0]])
     for kind in (0, 1, 2):
         np.testing.assert_array_equal(orc.vnorm(onehot, kind), [2.5, 4.0])      # all three agree on one-hot rows
+    # kind 3 switches the norm off: the ranking is then the accumulated attention score alone
+    np.testing.assert_array_equal(orc.vnorm(V, 3), np.ones(50))
+    S = rng.random(50) + 0.1
+    np.testing.assert_array_equal(orc.select(orc.importance(S, orc.vnorm(V, 3)), 20, 2, 5), orc.select(S, 20, 2, 5))
 
 
 def test_norm_choice_changes_the_kept_set_only_through_the_norm():
