@@ -171,6 +171,42 @@ void vatp_oracle_l1norm(const double *V, int64_t n, int64_t d, double *nrm)
 }
 
 /*
+ * Attention score over a history window of w steps (Eq. 3), after a causal prompt pass
+ * (t = L-1):
+ *     S_i = sum_{j = max(L-1-w, i)}^{L-1} a_i^j ,
+ * with a^j the same softmax rows as above.  Also returns those rows themselves, oldest first:
+ * P[r][i] = a_i^{j0+r}, j0 = max(0, L-1-w), r < n_hist = L - j0 (zero for i > j0+r); a later
+ * step needs them to drop the row that leaves the window.  Q, K: [L, d].  S: [L].
+ * P: [n_hist, L].  scratch: [L].  Returns n_hist.
+ */
+int64_t vatp_oracle_prefill_window(const double *Q, const double *K, int64_t L, int64_t d, double c,
+                                   int64_t w, double *S, double *P, double *scratch)
+{
+    const int64_t j0 = L - 1 - w > 0 ? L - 1 - w : 0;
+    for (int64_t i = 0; i < L; ++i) S[i] = 0.0;
+    for (int64_t j = j0; j < L; ++j) {
+        const double *q = Q + j * d;
+        double *row = P + (j - j0) * L;
+        double m = -INFINITY;
+        for (int64_t i = 0; i <= j; ++i) {
+            const double *k = K + i * d;
+            double dot = 0.0;
+            for (int64_t x = 0; x < d; ++x) dot += q[x] * k[x];
+            scratch[i] = c * dot;
+            if (scratch[i] > m) m = scratch[i];
+        }
+        double denom = 0.0;
+        for (int64_t i = 0; i <= j; ++i) {
+            scratch[i] = exp(scratch[i] - m);
+            denom += scratch[i];
+        }
+        for (int64_t i = 0; i < L; ++i) row[i] = i <= j ? scratch[i] / denom : 0.0;
+        for (int64_t i = 0; i <= j; ++i) S[i] += row[i];
+    }
+    return L - j0;
+}
+
+/*
  * The norm ablation (Table 2): kind 0 = l1 (the paper's choice, same as above),
  * 1 = l2 = sqrt(sum v^2), 2 = l-infinity = max |v|.  V: [n, d] -> nrm: [n].
  */

@@ -14,7 +14,7 @@ from __future__ import annotations
 import ctypes
 import os
 import subprocess
-from typing import Optional, Sequence
+from typing import List, Optional, Sequence
 
 import numpy as np
 
@@ -49,6 +49,8 @@ def lib():
         L.vatp_oracle_prefill_scores.restype = None
         L.vatp_oracle_prefill_scores_from.argtypes = [_f64p, _f64p, _i64, _i64, ctypes.c_double, _i64, _f64p, _f64p]
         L.vatp_oracle_prefill_scores_from.restype = None
+        L.vatp_oracle_prefill_window.argtypes = [_f64p, _f64p, _i64, _i64, ctypes.c_double, _i64, _f64p, _f64p, _f64p]
+        L.vatp_oracle_prefill_window.restype = _i64
         L.vatp_oracle_row_lse.argtypes = [_f64p, _f64p, _i64, _i64, ctypes.c_double, _f64p, _f64p]
         L.vatp_oracle_row_lse.restype = None
         L.vatp_oracle_prefill_scores_given_lse.argtypes = [_f64p, _f64p, _f64p, _i64, _i64, ctypes.c_double, _f64p]
@@ -114,6 +116,22 @@ def prefill_scores_tail(Q, K, j_start: int, c: Optional[float] = None) -> np.nda
     lib().vatp_oracle_prefill_scores_from(_p(Q), _p(K), L, d, default_scale(d) if c is None else c,
                                           int(j_start), _p(S), _p(scratch))
     return S[j_start:]
+
+
+def prefill_window(Q, K, w: int, c: Optional[float] = None):
+    """Eq. 3 after the prompt: (S, P) with S_i = sum of a_i^j over the last w+1 query rows j and
+    P [min(L, w+1), L] those attention rows themselves, oldest first.  Q, K: [L, d]."""
+    Q, K = _f64(Q), _f64(K)
+    L, d = Q.shape
+    S = np.zeros(L, dtype=np.float64)
+    n_hist = min(L, int(w) + 1)
+    P = np.zeros((max(n_hist, 1), max(L, 1)), dtype=np.float64)
+    scratch = np.zeros(max(L, 1), dtype=np.float64)
+    if L:
+        got = lib().vatp_oracle_prefill_window(_p(Q), _p(K), L, d, default_scale(d) if c is None else c, int(w),
+                                               _p(S), _p(P), _p(scratch))
+        assert got == n_hist
+    return S, P[:n_hist, :L]
 
 
 def prefill_scores_units(Q, K, lens, c: Optional[float] = None) -> np.ndarray:
@@ -238,9 +256,13 @@ class OracleHead:
     another implementation after an admissible near-tie difference.
     """
 
-    def __init__(self, d: int, c: Optional[float] = None, norm_kind: int = 0):
+    def __init__(self, d: int, c: Optional[float] = None, norm_kind: int = 0, window: Optional[int] = None):
         self.d = d
         self.norm_kind = norm_kind
+        # window = w: scores are sums over the last w+1 steps only (Eq. 3); `hist` then holds those
+        # steps' attention rows (oldest first, one entry per cached row) and S is their plain sum
+        self.window = window
+        self.hist: List[np.ndarray] = []
         self.c = default_scale(d) if c is None else c
         self.K = np.zeros((0, d))
         self.V = np.zeros((0, d))
@@ -254,7 +276,11 @@ class OracleHead:
 
     def prefill(self, Q, K, V):
         self.K, self.V = _f64(K).copy(), _f64(V).copy()
-        self.S = prefill_scores(Q, self.K, self.c)
+        if self.window is None:
+            self.S = prefill_scores(Q, self.K, self.c)
+        else:
+            self.S, P = prefill_window(Q, self.K, self.window, self.c)
+            self.hist = [row.copy() for row in P]
         self.nrm = l1norm(self.V) if self.norm_kind == 0 else vnorm(self.V, self.norm_kind)
         self.pos = np.arange(self.K.shape[0], dtype=np.int64)
 
@@ -269,6 +295,7 @@ class OracleHead:
         self.S = gather_rows(self.S, kept)
         self.nrm = gather_rows(self.nrm, kept)
         self.pos = self.pos[kept]
+        self.hist = [row[kept] for row in self.hist]
         return kept
 
     def append_and_score(self, q, k, v, new_pos: int) -> np.ndarray:
@@ -279,6 +306,11 @@ class OracleHead:
         self.nrm = np.concatenate([self.nrm, l1norm(new_row) if self.norm_kind == 0 else vnorm(new_row, self.norm_kind)])
         self.pos = np.concatenate([self.pos, np.array([new_pos], dtype=np.int64)])
         self.S, a = decode_scores(q, self.K, self.S, self.c)
+        if self.window is not None:
+            # the new row was not there at earlier steps; the oldest step leaves the window
+            self.hist = [np.concatenate([row, np.zeros(1)]) for row in self.hist] + [a.copy()]
+            self.hist = self.hist[-(self.window + 1):]
+            self.S = np.sum(np.stack(self.hist), axis=0)
         return a
 
 

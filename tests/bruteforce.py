@@ -1,7 +1,7 @@
 """Literal, pure-Python restatement of the paper's equations for tiny inputs.
 
 Used only to pin the C oracle: it materialises the whole causal attention matrix
-(Eq. 1), sums its columns (Eq. 2), multiplies by the value l1 norm (Eq. 4) and sorts.
+(Eq. 1), sums its columns (Eq. 2; over a history window, Eq. 3), multiplies by the value l1 norm (Eq. 4) and sorts.
 No numpy arithmetic, no blocking; lists of Python floats (binary64) or Fractions.
 """
 from __future__ import annotations
@@ -28,6 +28,11 @@ def attention_matrix(Q: Sequence[Sequence[float]], K: Sequence[Sequence[float]],
 def accumulated_scores(A) -> List[float]:
     L = len(A)
     return [math.fsum(A[j][i] for j in range(i, L)) for i in range(L)]
+
+
+def windowed_scores(A, w: int, t: int) -> List[float]:
+    """Eq. 3 read literally off the full attention matrix: S_k^t = sum_{max(t-w,k) <= j <= t} a_k^j, k <= t."""
+    return [math.fsum(A[j][k] for j in range(max(t - w, k), t + 1)) for k in range(t + 1)]
 
 
 def l1(V) -> List[float]:

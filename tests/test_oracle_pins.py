@@ -349,3 +349,92 @@ def test_attention_output_matches_torch_and_simple_cases():
     # the weights are those of the decode score update
     _, a_dec = orc.decode_scores(q.numpy(), K.numpy(), np.zeros(n))
     np.testing.assert_allclose(out, a_dec @ V.numpy(), rtol=1e-12, atol=1e-15)
+
+
+# ---------------------------------------------------------------- history-window scores (Eq. 3)
+
+@pytest.mark.parametrize("L,d,w", [(1, 4, 0), (7, 4, 0), (9, 8, 3), (20, 8, 5), (20, 8, 19), (20, 8, 50), (31, 16, 10)])
+def test_window_scores_match_bruteforce(L, d, w):
+    rng = np.random.default_rng(100 + L + w)
+    Q, K = _rand(rng, L, d) * 1.5, _rand(rng, L, d) * 1.5
+    c = orc.default_scale(d)
+    A = bf.attention_matrix(Q.tolist(), K.tolist(), c)
+    S, P = orc.prefill_window(Q, K, w)
+    np.testing.assert_allclose(S, bf.windowed_scores(A, w, L - 1), rtol=1e-13, atol=1e-300)
+    j0 = max(0, L - 1 - w)
+    assert P.shape == (L - j0, L)
+    np.testing.assert_allclose(P, np.array(A)[j0:], rtol=1e-13, atol=0)
+
+
+def test_window_scores_special_cases():
+    rng = np.random.default_rng(7)
+    L, d = 40, 8
+    Q, K = _rand(rng, L, d), _rand(rng, L, d)
+    # a window that covers the whole prompt is the accumulated score (Eq. 2)
+    for w in (L - 1, L, 10 * L):
+        np.testing.assert_allclose(orc.prefill_window(Q, K, w)[0], orc.prefill_scores(Q, K), rtol=1e-14)
+    # w = 0: only the last query's attention row
+    S0, P0 = orc.prefill_window(Q, K, 0)
+    want = torch.softmax(torch.from_numpy(Q[-1] @ K.T * orc.default_scale(d)), dim=0).numpy()
+    np.testing.assert_allclose(S0, want, rtol=1e-13)
+    assert P0.shape == (1, L)
+    # every attention row sums to one: the scores total the number of rows in the window
+    for w in (0, 3, 17, 39, 100):
+        S, P = orc.prefill_window(Q, K, w)
+        assert abs(S.sum() - min(L, w + 1)) < 1e-12
+        np.testing.assert_allclose(P.sum(axis=1), 1.0, rtol=1e-13)
+        assert np.all(np.triu(P, k=L - P.shape[0] + 1) == 0.0)      # causal: nothing right of the diagonal
+    # a longer window never lowers a score
+    assert np.all(orc.prefill_window(Q, K, 9)[0] >= orc.prefill_window(Q, K, 5)[0] - 1e-15)
+
+
+def test_window_scores_uniform_attention_closed_form():
+    """Identical keys give a_k^j = 1/(j+1): S_k = sum_{j=max(L-1-w,k)}^{L-1} 1/(j+1), exactly."""
+    L, d, w = 25, 4, 6
+    Q = _rand(np.random.default_rng(3), L, d)
+    K = np.tile(np.array([[0.3, -0.2, 0.5, 0.1]]), (L, 1))
+    S, _ = orc.prefill_window(Q, K, w)
+    want = [float(sum(Fraction(1, j + 1) for j in range(max(L - 1 - w, k), L))) for k in range(L)]
+    np.testing.assert_allclose(S, want, rtol=1e-14)
+
+
+def test_window_head_replay_matches_literal_equation_without_pruning():
+    """Prompt + decode steps with a budget that never prunes: after every step the head's scores are
+    Eq. 3 read off the full attention matrix of the whole sequence so far."""
+    rng = np.random.default_rng(11)
+    L, T, d, w = 12, 9, 4, 5
+    Q, K, V = _rand(rng, L + T, d) * 1.3, _rand(rng, L + T, d) * 1.3, _rand(rng, L + T, d)
+    c = orc.default_scale(d)
+    A = bf.attention_matrix(Q.tolist(), K.tolist(), c)
+    h = orc.OracleHead(d, window=w)
+    h.prefill(Q[:L], K[:L], V[:L])
+    np.testing.assert_allclose(h.S, bf.windowed_scores(A, w, L - 1), rtol=1e-13)
+    for t in range(L, L + T):
+        h.append_and_score(Q[t], K[t], V[t], t)
+        np.testing.assert_allclose(h.S, bf.windowed_scores(A, w, t), rtol=1e-12, atol=1e-300)
+        assert len(h.hist) == min(t + 1, w + 1)
+
+
+def test_window_head_with_pruning_keeps_history_aligned():
+    """With pruning: the history columns follow the kept rows, a token's score is the sum of what it
+    received in the last w+1 steps, and a token nobody attends to for w+1 steps drops to the tiny
+    weights it actually got."""
+    rng = np.random.default_rng(12)
+    L, T, d, w, B, F, R = 30, 14, 8, 4, 16, 2, 3
+    Q, K, V = _rand(rng, L + T, d) * 1.5, _rand(rng, L + T, d) * 1.5, _rand(rng, L + T, d) * np.exp(_rand(rng, L + T, 1))
+    h = orc.OracleHead(d, window=w)
+    h.prefill(Q[:L], K[:L], V[:L])
+    kept = h.prune(B, F, R)
+    assert len(kept) == B and all(row.shape == (B,) for row in h.hist)
+    received = {int(p): [] for p in h.pos}          # per surviving token: attention received per decode step
+    for t in range(L, L + T):
+        a = h.append_and_score(Q[t], K[t], V[t], t)
+        for p, ai in zip(h.pos, a):
+            received.setdefault(int(p), []).append(ai)
+        assert abs(a.sum() - 1.0) < 1e-12
+        assert h.S.sum() <= w + 1 + 1e-12 and np.all(h.S >= 0)
+        h.prune(B, F, R)
+        assert all(row.shape == (h.n,) for row in h.hist)
+        if t - L + 1 >= w + 1:                      # the prompt's rows have left the window
+            for p, s in zip(h.pos, h.S):
+                np.testing.assert_allclose(s, sum(received[int(p)][-(w + 1):]), rtol=1e-12, atol=1e-300)
