@@ -197,6 +197,57 @@ vatp_status vatp_decode_prune_step(vatp_ctx *ctx, const vatp_params *p,
                                    const int32_t *synced_in, int32_t *synced_out, float *out,
                                    void *ws, size_t ws_bytes, void *hip_stream);
 
+/*
+ * History-window scores (Eq. 3: S_k^t = sum of a_k^j over the last w+1 steps j only, the score
+ * of the paper's "Scissorhands w/ VATP" variant).  Three calls mirror the three phases.
+ *
+ * vatp_prefill_score_window: as vatp_prefill_score with S_i = sum_{j >= max(len-1-w, i)} a_i^j
+ * (only the prompt's last w+1 query rows are evaluated, a (w+1) x len band instead of the
+ * triangle).  hist (device float32 [batch, n_heads, w+2, cap], may be NULL) receives those
+ * attention rows, a_i^j at ring row j mod (w+2), column i, for i <= j; other entries are left
+ * undefined.  Workspace as for VATP_CALL_PREFILL_SCORE.
+ *
+ * vatp_select_compact_window: vatp_select_compact of the prompt, after which hist_out (device
+ * float32 [batch, n_heads, w+2, cap_hist], cap_hist >= min(len, budget)) holds the history of
+ * the survivors, column o for survivor o, hid_out ([batch, n_heads, cap_out] int32) is set to
+ * o and free_out ([batch * n_heads] int32) to the survivor count.
+ *
+ * vatp_decode_prune_step_window: vatp_decode_prune_step with S_new = S + a^t - a^(t-w-1),
+ * t = new_pos[b] (HOST, required: the index of the new token in its sequence, counted on from
+ * the prompt).  Every cached row owns one history column for its lifetime: hid / hid_out are
+ * per-row int32 like pos / pos_out and move with the rows; the appended row takes column
+ * free_in[u], and free_out[u] receives the column the evicted row gave up (or the next fresh
+ * one while the cache still grows); free_in / free_out are distinct device arrays
+ * [batch * n_heads] that the caller swaps like synced_in / synced_out.  hist is updated in
+ * place: ring row t mod (w+2) is written, row (t+1) mod (w+2) read.  cap_hist >= budget[b] + 1.
+ * fp32 sums that add and later subtract the same weights carry an absolute error of a few
+ * ulps of the largest score a row ever had, times the number of steps.
+ */
+vatp_status vatp_prefill_score_window(vatp_ctx *ctx, const vatp_params *p,
+                                      const void *Q, const void *K, const void *V, int32_t window,
+                                      float *S, float *nrm, float *hist,
+                                      void *ws, size_t ws_bytes, void *hip_stream);
+
+vatp_status vatp_select_compact_window(vatp_ctx *ctx, const vatp_params *p,
+                                       const void *K, const void *V, const float *S,
+                                       const float *nrm, const int32_t *pos, const float *hist,
+                                       int32_t window,
+                                       void *K_out, void *V_out, float *S_out, float *nrm_out,
+                                       int32_t *pos_out, int32_t *kept_idx, float *hist_out,
+                                       int32_t cap_hist, int32_t *hid_out, int32_t *free_out,
+                                       void *ws, size_t ws_bytes, void *hip_stream);
+
+vatp_status vatp_decode_prune_step_window(vatp_ctx *ctx, const vatp_params *p,
+                                          const void *q, const void *k, const void *v,
+                                          void *K, void *V, const float *S, float *nrm,
+                                          int32_t *pos, int32_t *hid, const int32_t *new_pos,
+                                          void *K_out, void *V_out, float *S_out, float *nrm_out,
+                                          int32_t *pos_out, int32_t *hid_out, int32_t *kept_idx,
+                                          const int32_t *synced_in, int32_t *synced_out,
+                                          const int32_t *free_in, int32_t *free_out,
+                                          float *hist, int32_t window, int32_t cap_hist, float *out,
+                                          void *ws, size_t ws_bytes, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -159,11 +159,14 @@ size_t vatp_workspace_bytes(const vatp_ctx *, const vatp_params *p, int which_ca
 
 namespace {
 
+constexpr int kMaxWindow = 1 << 20;
+
 vatp_status prefill_score_impl(vatp_ctx *ctx, const vatp_params *p, const void *Q, const void *K, const void *V,
-                               const float *lse, bool have_lse, float *S, float *nrm, void *ws, size_t ws_bytes,
-                               void *hip_stream)
+                               const float *lse, bool have_lse, int window, float *hist, float *S, float *nrm,
+                               void *ws, size_t ws_bytes, void *hip_stream)
 {
     if (!ctx || !Q || !K || !V || !S || !nrm || (have_lse && !lse)) return VATP_E_NULL;
+    if (window < -1 || window > kMaxWindow) return VATP_E_SHAPE;
     const vatp_status st = check_params(p, VATP_CALL_PREFILL_SCORE);
     if (st != VATP_OK) return st;
     if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16)) return VATP_E_SHAPE;
@@ -175,11 +178,12 @@ vatp_status prefill_score_impl(vatp_ctx *ctx, const vatp_params *p, const void *
     float *lse2 = static_cast<float *>(ws);
     if (launch_l1norm(p->dtype, p->head_dim, V, nrm, pr.meta, pr.g, stream) != hipSuccess) return VATP_E_DEVICE;
     if (have_lse && launch_lse_to_base2(lse, lse2, pr.meta, pr.g, stream) != hipSuccess) return VATP_E_DEVICE;
-    // bf16 with head_dim 128 runs on the matrix cores; everything else on the fp32 FMA kernels
-    const hipError_t e = (p->dtype == VATP_BF16 && p->head_dim == 128)
+    // bf16 with head_dim 128 runs on the matrix cores; everything else, and the history-window scores
+    // (a band of w+1 query rows, a fraction of the full pass), on the fp32 FMA kernels
+    const hipError_t e = (p->dtype == VATP_BF16 && p->head_dim == 128 && window < 0)
                              ? launch_prefill_mfma(Q, K, S, lse2, have_lse, pr.meta, pr.g, stream)
-                             : launch_prefill_generic(p->dtype, p->head_dim, Q, K, S, lse2, have_lse, pr.meta, pr.g,
-                                                      stream);
+                             : launch_prefill_generic(p->dtype, p->head_dim, Q, K, S, lse2, have_lse, window, hist,
+                                                      pr.meta, pr.g, stream);
     if (e != hipSuccess) return VATP_E_DEVICE;
     return VATP_OK;
 }
@@ -192,14 +196,22 @@ vatp_status vatp_prefill_score(vatp_ctx *ctx, const vatp_params *p, const void *
                                const void *V, float *S, float *nrm, void *ws, size_t ws_bytes,
                                void *hip_stream)
 {
-    return prefill_score_impl(ctx, p, Q, K, V, nullptr, false, S, nrm, ws, ws_bytes, hip_stream);
+    return prefill_score_impl(ctx, p, Q, K, V, nullptr, false, -1, nullptr, S, nrm, ws, ws_bytes, hip_stream);
+}
+
+vatp_status vatp_prefill_score_window(vatp_ctx *ctx, const vatp_params *p, const void *Q, const void *K,
+                                      const void *V, int32_t window, float *S, float *nrm, float *hist, void *ws,
+                                      size_t ws_bytes, void *hip_stream)
+{
+    if (window < 0) return VATP_E_SHAPE;
+    return prefill_score_impl(ctx, p, Q, K, V, nullptr, false, window, hist, S, nrm, ws, ws_bytes, hip_stream);
 }
 
 vatp_status vatp_prefill_score_lse(vatp_ctx *ctx, const vatp_params *p, const void *Q, const void *K,
                                    const void *V, const float *lse, float *S, float *nrm, void *ws,
                                    size_t ws_bytes, void *hip_stream)
 {
-    return prefill_score_impl(ctx, p, Q, K, V, lse, true, S, nrm, ws, ws_bytes, hip_stream);
+    return prefill_score_impl(ctx, p, Q, K, V, lse, true, -1, nullptr, S, nrm, ws, ws_bytes, hip_stream);
 }
 
 }  // extern "C" (reopened below)
@@ -255,12 +267,15 @@ vatp_status vatp_decode_attend_step(vatp_ctx *ctx, const vatp_params *p, const v
                             ws_bytes, hip_stream);
 }
 
-vatp_status vatp_decode_prune_step(vatp_ctx *ctx, const vatp_params *p, const void *q, const void *k,
-                                   const void *v, void *K, void *V, const float *S, float *nrm, int32_t *pos,
-                                   const int32_t *new_pos, void *K_out, void *V_out, float *S_out,
-                                   float *nrm_out, int32_t *pos_out, int32_t *kept_idx,
-                                   const int32_t *synced_in, int32_t *synced_out, float *out, void *ws,
-                                   size_t ws_bytes, void *hip_stream)
+}  // extern "C" (reopened below)
+
+namespace {
+
+vatp_status decode_prune_impl(vatp_ctx *ctx, const vatp_params *p, const void *q, const void *k, const void *v,
+                              void *K, void *V, const float *S, float *nrm, int32_t *pos, const int32_t *new_pos,
+                              void *K_out, void *V_out, float *S_out, float *nrm_out, int32_t *pos_out,
+                              int32_t *kept_idx, const int32_t *synced_in, int32_t *synced_out, WindowArgs &win,
+                              float *out, void *ws, size_t ws_bytes, void *hip_stream)
 {
     if (!ctx || !q || !k || !v || !K || !V || !S || !nrm || !K_out || !V_out || !S_out || !nrm_out || !synced_in ||
         !synced_out)
@@ -290,7 +305,7 @@ vatp_status vatp_decode_prune_step(vatp_ctx *ctx, const vatp_params *p, const vo
     // One launch with a workgroup per head when there are enough heads to fill the chip that way and
     // each is short enough for a single workgroup to stream quickly (measured: 19.9 against 22.3 us per
     // step at 256 heads x 820 rows; slower than two launches at 32 heads x 2049 rows, 23 against 14 us).
-    const bool one = !out && units >= 128 && pr.g.max_len <= 1024 && pr.g.max_len <= decode_prune_one_max_rows();
+    const bool one = !out && !win.hist && units >= 128 && pr.g.max_len <= 1024 && pr.g.max_len <= decode_prune_one_max_rows();
     if (one) {
         if (launch_decode_prune_one(p->dtype, p->head_dim, q, k, v, K, V, S, nrm, pos, K_out, V_out, S_out, nrm_out,
                                     pos_out, kept_idx, synced_in, synced_out, pr.meta, budgets, pr.g, stream) !=
@@ -304,8 +319,77 @@ vatp_status vatp_decode_prune_step(vatp_ctx *ctx, const vatp_params *p, const vo
         return VATP_E_DEVICE;
     // second launch: new scores, the evicted row, the out-of-date rows of the other set
     if (launch_decode_prune(p->dtype, p->head_dim, K, V, S, nrm, pos, K_out, V_out, S_out, nrm_out, pos_out, kept_idx,
-                            synced_in, synced_out, ws_logit, ws_part, out ? ws_out : nullptr, out, budgets, pr.g,
-                            stream) != hipSuccess)
+                            synced_in, synced_out, ws_logit, ws_part, out ? ws_out : nullptr, out, win, budgets,
+                            pr.g, stream) != hipSuccess)
+        return VATP_E_DEVICE;
+    return VATP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+vatp_status vatp_decode_prune_step(vatp_ctx *ctx, const vatp_params *p, const void *q, const void *k,
+                                   const void *v, void *K, void *V, const float *S, float *nrm, int32_t *pos,
+                                   const int32_t *new_pos, void *K_out, void *V_out, float *S_out,
+                                   float *nrm_out, int32_t *pos_out, int32_t *kept_idx,
+                                   const int32_t *synced_in, int32_t *synced_out, float *out, void *ws,
+                                   size_t ws_bytes, void *hip_stream)
+{
+    WindowArgs win = {};
+    return decode_prune_impl(ctx, p, q, k, v, K, V, S, nrm, pos, new_pos, K_out, V_out, S_out, nrm_out, pos_out,
+                             kept_idx, synced_in, synced_out, win, out, ws, ws_bytes, hip_stream);
+}
+
+vatp_status vatp_decode_prune_step_window(vatp_ctx *ctx, const vatp_params *p, const void *q, const void *k,
+                                          const void *v, void *K, void *V, const float *S, float *nrm,
+                                          int32_t *pos, int32_t *hid, const int32_t *new_pos, void *K_out,
+                                          void *V_out, float *S_out, float *nrm_out, int32_t *pos_out,
+                                          int32_t *hid_out, int32_t *kept_idx, const int32_t *synced_in,
+                                          int32_t *synced_out, const int32_t *free_in, int32_t *free_out,
+                                          float *hist, int32_t window, int32_t cap_hist, float *out, void *ws,
+                                          size_t ws_bytes, void *hip_stream)
+{
+    if (!p || !hid || !hid_out || !free_in || !free_out || !hist || !new_pos) return VATP_E_NULL;
+    if (window < 0 || window > kMaxWindow || hid == hid_out || free_in == free_out) return VATP_E_SHAPE;
+    if (p->batch < 1 || p->batch > VATP_MAX_BATCH || !p->budget) return p->budget ? VATP_E_SHAPE : VATP_E_NULL;
+    WindowArgs win = {};
+    win.hist = hist;
+    win.hid = hid;
+    win.hid_out = hid_out;
+    win.free_in = free_in;
+    win.free_out = free_out;
+    win.rows = window + 2;
+    win.cap_hist = cap_hist;
+    for (int b = 0; b < p->batch; ++b) {
+        if (new_pos[b] < 0) return VATP_E_SHAPE;
+        if (cap_hist < p->budget[b] + 1) return VATP_E_BUDGET;        // one column per row plus the appended one
+        win.step[b] = new_pos[b];
+    }
+    return decode_prune_impl(ctx, p, q, k, v, K, V, S, nrm, pos, new_pos, K_out, V_out, S_out, nrm_out, pos_out,
+                             kept_idx, synced_in, synced_out, win, out, ws, ws_bytes, hip_stream);
+}
+
+vatp_status vatp_select_compact_window(vatp_ctx *ctx, const vatp_params *p, const void *K, const void *V,
+                                       const float *S, const float *nrm, const int32_t *pos, const float *hist,
+                                       int32_t window, void *K_out, void *V_out, float *S_out, float *nrm_out,
+                                       int32_t *pos_out, int32_t *kept_idx, float *hist_out, int32_t cap_hist,
+                                       int32_t *hid_out, int32_t *free_out, void *ws, size_t ws_bytes,
+                                       void *hip_stream)
+{
+    if (!hist || !hist_out || !hid_out || !free_out) return VATP_E_NULL;
+    if (window < 0 || window > kMaxWindow || hist == hist_out) return VATP_E_SHAPE;
+    vatp_status st = check_params(p, VATP_CALL_SELECT_COMPACT);
+    if (st != VATP_OK) return st;
+    for (int b = 0; b < p->batch; ++b)
+        if (cap_hist < (p->len[b] < p->budget[b] ? p->len[b] : p->budget[b])) return VATP_E_BUDGET;
+    st = vatp_select_compact(ctx, p, K, V, S, nrm, pos, K_out, V_out, S_out, nrm_out, pos_out, kept_idx, ws, ws_bytes,
+                             hip_stream);
+    if (st != VATP_OK) return st;
+    Prepared pr;
+    prepare(p, VATP_CALL_SELECT_COMPACT, nullptr, &pr);
+    if (launch_hist_gather(hist, kept_idx, hist_out, hid_out, free_out, window + 2, cap_hist, pr.meta, pr.g,
+                           static_cast<hipStream_t>(hip_stream)) != hipSuccess)
         return VATP_E_DEVICE;
     return VATP_OK;
 }

@@ -32,8 +32,8 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
     T *__restrict__ V_out, float *__restrict__ S_out, float *__restrict__ nrm_out,
     int32_t *__restrict__ pos_out, int32_t *__restrict__ kept_idx, const int32_t *__restrict__ synced_in,
     int32_t *__restrict__ synced_out, const float *__restrict__ ws_logit, const float2 *__restrict__ ws_part,
-    const float *__restrict__ ws_out, float *__restrict__ out, BatchMeta meta, int n_heads, int cap,
-    int cap_out, int chunks_alloc, int n_sink, int recent)
+    const float *__restrict__ ws_out, float *__restrict__ out, WindowArgs win, BatchMeta meta, int n_heads,
+    int cap, int cap_out, int chunks_alloc, int n_sink, int recent)
 {
     constexpr int kE = Elt<T>::kPer16B;
     constexpr int kLanesPerRow = D / kE;
@@ -54,10 +54,21 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
     const int synced = synced_in[unit];
     const int lo = n_sink, hi = n - recent;                // rows [lo, hi) may leave
 
+    // history window (Eq. 3): the ring row this step writes, the one that leaves the window, and
+    // the column of every row (the appended row takes the free column and has no past)
+    const bool windowed = win.hist != nullptr;
+    const int step = windowed ? win.step[b] : 0;
+    float *h_write = windowed ? win.hist + (unit * win.rows + step % win.rows) * static_cast<size_t>(win.cap_hist) : nullptr;
+    const float *h_leave =
+        windowed ? win.hist + (unit * win.rows + (step + 1) % win.rows) * static_cast<size_t>(win.cap_hist) : nullptr;
+    const int new_col = windowed ? win.free_in[unit] : 0;
+    auto column = [&](int r) { return r == n0 ? new_col : win.hid[unit * cap + r]; };
+    auto leaving = [&](int r) { return windowed && r != n0 ? h_leave[column(r)] : 0.f; };
+
     // the unprotected rows this thread looks at (logit, old score, norm), requested before the
     // denominator is known so that both round trips to memory overlap
     constexpr int kScan = 4;
-    float t_r[kScan], s_r[kScan], w_r[kScan];
+    float t_r[kScan], s_r[kScan], w_r[kScan], x_r[kScan];
 #pragma unroll
     for (int u = 0; u < kScan; ++u) {
         const int r = lo + tid + u * kThreads;
@@ -65,6 +76,7 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
         t_r[u] = ok ? Lu[r] : 0.f;
         s_r[u] = ok && r != n0 ? Su[r] : 0.f;
         w_r[u] = ok ? Nu[r] : 0.f;
+        x_r[u] = ok ? leaving(r) : 0.f;
     }
 
     // log2 of the softmax denominator from the chunk statistics
@@ -74,7 +86,13 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
     merge_chunk_stats(part, n_chunks, M, L);
     const float lse2 = M + log2f(L);
 
-    auto new_score = [&](int r) { return (r != n0 ? Su[r] : 0.f) + exp2f(Lu[r] - lse2); };
+    // new score from the old one, this step's attention weight and (windowed) the weight that leaves;
+    // rounding may leave a windowed sum a hair below zero: it is a sum of non-negative terms
+    auto combine = [&](float s_old, float p, float gone) {
+        const float s = s_old + p;
+        return windowed ? fmaxf(s - gone, 0.f) : s;
+    };
+    auto new_score = [&](int r) { return combine(r != n0 ? Su[r] : 0.f, exp2f(Lu[r] - lse2), leaving(r)); };
 
     // the row that leaves: minimise (importance bits, ~row) over the unprotected rows
     int evicted = n;                                       // n <= B: nothing leaves
@@ -89,7 +107,7 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
 #pragma unroll
         for (int u = 0; u < kScan; ++u) {
             const int r = lo + tid + u * kThreads;
-            if (r < hi) consider(r, s_r[u] + exp2f(t_r[u] - lse2), w_r[u]);
+            if (r < hi) consider(r, combine(s_r[u], exp2f(t_r[u] - lse2), x_r[u]), w_r[u]);
         }
         for (int r = lo + tid + kScan * kThreads; r < hi; r += kThreads) consider(r, new_score(r), Nu[r]);
 #pragma unroll
@@ -113,6 +131,18 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
             const int src = o + (o >= evicted ? 1 : 0);
             S_out[unit * cap_out + o] = new_score(src);
             if (kept_idx) kept_idx[unit * cap_out + o] = src;
+            if (windowed) h_write[column(src)] = exp2f(Lu[src] - lse2);
+        }
+    }
+    if (windowed && g == 0) {
+        // the appended row has received nothing in the steps before this one: clear its column in every
+        // ring row but the one written above and the one that leaves (rewritten in full by the next step)
+        for (int s = tid; s < win.rows; s += kThreads)
+            if (s != step % win.rows && s != (step + 1) % win.rows)
+                win.hist[(unit * win.rows + s) * static_cast<size_t>(win.cap_hist) + new_col] = 0.f;
+        if (tid == 0) {
+            win.hid[unit * cap + n0] = new_col;
+            win.free_out[unit] = evicted < n ? column(evicted) : n;     // a fresh column while the cache grows
         }
     }
 
@@ -136,6 +166,7 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
             if (sub == 0) {
                 nrm_out[unit * cap_out + o] = Nu[src];
                 if (pos_out) pos_out[unit * cap_out + o] = pos[unit * cap + src];
+                if (windowed) win.hid_out[unit * cap_out + o] = column(src);
             }
         }
     }
@@ -321,8 +352,8 @@ hipError_t launch_decode_prune(int dtype, int head_dim, const void *K, const voi
                                const float *nrm, const int32_t *pos, void *K_out, void *V_out, float *S_out,
                                float *nrm_out, int32_t *pos_out, int32_t *kept_idx, const int32_t *synced_in,
                                int32_t *synced_out, const float *ws_logit, const float2 *ws_part,
-                               const float *ws_out, float *out, const BatchMeta &meta, const Geometry &g,
-                               hipStream_t st)
+                               const float *ws_out, float *out, const WindowArgs &win, const BatchMeta &meta,
+                               const Geometry &g, hipStream_t st)
 {
     const int chunks_alloc = (g.cap + kDecodeChunk - 1) / kDecodeChunk;
     const unsigned units = static_cast<unsigned>(g.batch) * g.n_heads;
@@ -334,7 +365,7 @@ hipError_t launch_decode_prune(int dtype, int head_dim, const void *K, const voi
     hipLaunchKernelGGL((decode_prune_kernel<T, D>), grid, block, 0, st, static_cast<const T *>(K),               \
                        static_cast<const T *>(V), S, nrm, pos, static_cast<T *>(K_out), static_cast<T *>(V_out), \
                        S_out, nrm_out, pos_out, kept_idx, synced_in, synced_out, ws_logit, ws_part, ws_out, out, \
-                       meta, g.n_heads, g.cap, g.cap_out, chunks_alloc, g.n_sink, g.recent)
+                       win, meta, g.n_heads, g.cap, g.cap_out, chunks_alloc, g.n_sink, g.recent)
     if (dtype == VATP_F32 && head_dim == 64) VATP_DP(float, 64);
     else if (dtype == VATP_F32) VATP_DP(float, 128);
     else if (head_dim == 64) VATP_DP(bf16_t, 64);

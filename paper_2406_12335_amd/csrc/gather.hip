@@ -114,6 +114,35 @@ __global__ __launch_bounds__(256) void gather_kernel(
     }
 }
 
+// History-window scores (Eq. 3): after the prompt has been pruned, the window's attention rows
+// follow the surviving tokens.  hist_in holds a_i^j at [j mod rows][i] for the prompt's last
+// rows-1 queries j and keys i <= j (what the prompt pass stored; everything else is undefined and
+// reads as 0 here); hist_out receives column kept[o] as column o, and surviving row o is given
+// history column o.
+__global__ __launch_bounds__(256) void hist_gather_kernel(const float *__restrict__ hist_in,
+                                                          const int32_t *__restrict__ kept_idx,
+                                                          float *__restrict__ hist_out, int32_t *__restrict__ hid_out,
+                                                          int32_t *__restrict__ free_out, BatchMeta meta, int n_heads,
+                                                          int cap, int cap_out, int cap_hist, int rows)
+{
+    const size_t unit = blockIdx.y;
+    const int b = static_cast<int>(unit / n_heads);
+    const int n = meta.len[b], B = meta.aux[b];
+    const int n_keep = n < B ? n : B;
+    const int o = blockIdx.x * 256 + threadIdx.x;
+    if (blockIdx.x == 0 && threadIdx.x == 0) free_out[unit] = n_keep;
+    if (o >= n_keep) return;
+    const int src = kept_idx[unit * cap_out + o];
+    hid_out[unit * cap_out + o] = o;
+    const int q_first = max(0, n - (rows - 1));            // first query of the window (w + 1 = rows - 1 of them)
+    for (int s = 0; s < rows; ++s) {
+        const int j = q_first + (s - q_first % rows + rows) % rows;     // the window's query kept in ring row s
+        const bool defined = j < n && src <= j;
+        hist_out[(unit * rows + s) * static_cast<size_t>(cap_hist) + o] =
+            defined ? hist_in[(unit * rows + s) * static_cast<size_t>(cap) + src] : 0.f;
+    }
+}
+
 }  // namespace
 
 hipError_t launch_gather(int dtype, int head_dim, bool evict_one,
@@ -136,6 +165,21 @@ hipError_t launch_gather(int dtype, int head_dim, bool evict_one,
     else VATP_GA2(bf16_t, 128);
 #undef VATP_GA2
 #undef VATP_GA
+    return hipGetLastError();
+}
+
+}  // namespace vatp
+
+namespace vatp {
+
+hipError_t launch_hist_gather(const float *hist_in, const int32_t *kept_idx, float *hist_out, int32_t *hid_out,
+                              int32_t *free_out, int rows, int cap_hist, const BatchMeta &meta, const Geometry &g,
+                              hipStream_t st)
+{
+    const unsigned units = static_cast<unsigned>(g.batch) * g.n_heads;
+    const int max_keep = g.max_len > 0 ? g.max_len : 1;       // max_len: largest surviving row count
+    hipLaunchKernelGGL(hist_gather_kernel, dim3((max_keep + 255) / 256, units), dim3(256), 0, st, hist_in, kept_idx,
+                       hist_out, hid_out, free_out, meta, g.n_heads, g.cap, g.cap_out, cap_hist, rows);
     return hipGetLastError();
 }
 

@@ -11,6 +11,11 @@
 //                     once: no atomics on memory.
 // Both passes work on 64x64 logit tiles, 4x4 per thread, with Q and K staged through LDS in
 // slabs of 32 elements of the head dimension.
+//
+// History-window scores (Eq. 3 after the prompt: only the last w+1 query rows count) use the same
+// two kernels with `window` = w >= 0: query tiles wholly before row len-1-w are skipped, and
+// pass 2 also stores the window's attention rows, p = a_i^j at hist[j mod (w+2)][i], which the
+// decode steps need to drop the row that leaves the window.  window < 0 means no window.
 #include "vatp_device.h"
 
 namespace vatp {
@@ -79,7 +84,7 @@ __global__ __launch_bounds__(256) void prefill_rowstat_generic(const T *__restri
                                                                const T *__restrict__ K,
                                                                float *__restrict__ lse2,
                                                                BatchMeta meta, int n_heads,
-                                                               int cap, float scale_log2)
+                                                               int cap, float scale_log2, int window)
 {
     __shared__ __attribute__((aligned(16))) float Qs[kSlab][kTile];
     __shared__ __attribute__((aligned(16))) float Ks[kSlab][kTile];
@@ -87,6 +92,7 @@ __global__ __launch_bounds__(256) void prefill_rowstat_generic(const T *__restri
     const int len = meta.len[b];
     const int j0 = blockIdx.x * kTile;
     if (j0 >= len) return;
+    if (window >= 0 && j0 + kTile <= len - 1 - window) return;      // no query of this tile is in the window
     const size_t unit = static_cast<size_t>(b) * n_heads + h;
     const T *Qu = Q + unit * cap * D;
     const T *Ku = K + unit * cap * D;
@@ -137,7 +143,8 @@ __global__ __launch_bounds__(256) void prefill_colsum_generic(const T *__restric
                                                               const float *__restrict__ lse2,
                                                               float *__restrict__ S,
                                                               BatchMeta meta, int n_heads,
-                                                              int cap, float scale_log2)
+                                                              int cap, float scale_log2, int window,
+                                                              float *__restrict__ hist)
 {
     __shared__ __attribute__((aligned(16))) float Qs[kSlab][kTile];
     __shared__ __attribute__((aligned(16))) float Ks[kSlab][kTile];
@@ -152,19 +159,27 @@ __global__ __launch_bounds__(256) void prefill_colsum_generic(const T *__restric
     const float *lu = lse2 + unit * cap;
     const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
 
+    // first query row that counts, and the history rows of this unit (w+2 of them, cap entries each)
+    const int q_first = window >= 0 ? max(0, len - 1 - window) : 0;
+    float *hu = hist ? hist + unit * static_cast<size_t>(window + 2) * cap : nullptr;
     float col[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int j0 = i0; j0 < len; j0 += kTile) {
+    for (int j0 = max(i0, q_first / kTile * kTile); j0 < len; j0 += kTile) {
         float acc[4][4];
         logit_tile<T, D>(Qu, Ku, j0, i0, len, Qs, Ks, acc);
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
             const int j = j0 + ty * 4 + a;
-            if (j < len) {
+            if (j < len && j >= q_first) {
                 const float lj = lu[j];
+                float *hrow = hu ? hu + static_cast<size_t>(j % (window + 2)) * cap : nullptr;
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
                     const int i = i0 + tx * 4 + c;
-                    if (i <= j) col[c] += exp2f(acc[a][c] * scale_log2 - lj);
+                    if (i <= j) {
+                        const float pr = exp2f(acc[a][c] * scale_log2 - lj);
+                        col[c] += pr;
+                        if (hrow) hrow[i] = pr;
+                    }
                 }
             }
         }
@@ -204,8 +219,8 @@ hipError_t launch_lse_to_base2(const float *lse, float *lse2, const BatchMeta &m
 }
 
 hipError_t launch_prefill_generic(int dtype, int head_dim, const void *Q, const void *K,
-                                  float *S, float *lse2, bool have_lse, const BatchMeta &meta,
-                                  const Geometry &g, hipStream_t st)
+                                  float *S, float *lse2, bool have_lse, int window, float *hist,
+                                  const BatchMeta &meta, const Geometry &g, hipStream_t st)
 {
     if (g.max_len <= 0) return hipSuccess;
     dim3 grid((g.max_len + kTile - 1) / kTile, g.n_heads, g.batch), block(256);
@@ -214,15 +229,15 @@ hipError_t launch_prefill_generic(int dtype, int head_dim, const void *Q, const 
         if (!have_lse)                                                                         \
             hipLaunchKernelGGL((prefill_rowstat_generic<T, D>), grid, block, 0, st,            \
                                static_cast<const T *>(Q), static_cast<const T *>(K), lse2,     \
-                               meta, g.n_heads, g.cap, g.scale_log2);                          \
+                               meta, g.n_heads, g.cap, g.scale_log2, window);                  \
         hipLaunchKernelGGL((prefill_colsum_generic<T, D>), grid, block, 0, st,                 \
                            static_cast<const T *>(Q), static_cast<const T *>(K), lse2, S,      \
-                           meta, g.n_heads, g.cap, g.scale_log2);                              \
+                           meta, g.n_heads, g.cap, g.scale_log2, window, hist);                \
     } while (0)
     if (dtype == VATP_F32 && head_dim == 64) VATP_PF(float, 64);
     else if (dtype == VATP_F32) VATP_PF(float, 128);
     else if (head_dim == 64) VATP_PF(bf16_t, 64);
-    else return hipErrorInvalidValue;      // bf16 with head_dim 128 belongs to the MFMA kernels
+    else VATP_PF(bf16_t, 128);             // (without a window this shape runs on the MFMA kernels instead)
 #undef VATP_PF
     return hipGetLastError();
 }

@@ -37,6 +37,23 @@ __device__ __forceinline__ float norm_finish(int kind, float a) {
     return kind == VATP_NORM_L2 ? sqrtf(a) : kind == VATP_NORM_NONE ? 1.f : a;     // NONE: attention-only baseline
 }
 
+// History-window scores (paper Eq. 3: only the attention a token received in the last w+1 steps
+// counts) for the fused decode-and-evict step.  hist keeps the last steps' attention weights,
+// rows = w + 2 ring rows of cap_hist columns per head: step t writes ring row t mod rows and
+// subtracts ring row (t+1) mod rows, which holds step t-w-1.  A cached row owns one column for
+// as long as it lives (its `hid`, moved with the row like pos), so evictions never move history:
+// the new row takes the column the last evicted row gave up (free_in), or the next fresh one.
+// hist == nullptr switches all of this off (accumulated scores, Eq. 2).
+struct WindowArgs {
+    float *hist;                     // [units, rows, cap_hist]
+    int32_t *hid;                    // [units, cap]      column of every row of the current set
+    int32_t *hid_out;                // [units, cap_out]  ... of the other set
+    const int32_t *free_in;          // [units]           column for the row appended by this step
+    int32_t *free_out;               // [units]           ... by the next step
+    int32_t rows, cap_hist;
+    int32_t step[VATP_MAX_BATCH];    // index t of the new token in its sequence
+};
+
 constexpr int kDecodeChunk = 128;  // rows of one unit handled by one workgroup of the decode GEMV
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t x) {
@@ -105,9 +122,10 @@ __device__ __forceinline__ float merge_chunk_outputs(const float *__restrict__ w
 hipError_t launch_l1norm(int dtype, int head_dim, const void *V, float *nrm,
                          const BatchMeta &meta, const Geometry &g, hipStream_t st);
 
+// window >= 0: history-window scores (Eq. 3), the window's attention rows go to hist (may be NULL)
 hipError_t launch_prefill_generic(int dtype, int head_dim, const void *Q, const void *K,
-                                  float *S, float *lse2, bool have_lse, const BatchMeta &meta,
-                                  const Geometry &g, hipStream_t st);
+                                  float *S, float *lse2, bool have_lse, int window, float *hist,
+                                  const BatchMeta &meta, const Geometry &g, hipStream_t st);
 
 hipError_t launch_lse_to_base2(const float *lse, float *lse2, const BatchMeta &meta, const Geometry &g,
                                hipStream_t st);
@@ -125,8 +143,8 @@ hipError_t launch_decode_prune(int dtype, int head_dim, const void *K, const voi
                                const float *nrm, const int32_t *pos, void *K_out, void *V_out, float *S_out,
                                float *nrm_out, int32_t *pos_out, int32_t *kept_idx, const int32_t *synced_in,
                                int32_t *synced_out, const float *ws_logit, const float2 *ws_part,
-                               const float *ws_out, float *out, const BatchMeta &meta, const Geometry &g,
-                               hipStream_t st);
+                               const float *ws_out, float *out, const WindowArgs &win, const BatchMeta &meta,
+                               const Geometry &g, hipStream_t st);
 
 // the same step in one launch, one workgroup per head; usable while every head has at most
 // decode_prune_one_max_rows() rows after the append
@@ -145,5 +163,10 @@ hipError_t launch_gather(int dtype, int head_dim, bool evict_one,
                          const int32_t *pos, void *K_out, void *V_out, float *S_out,
                          float *nrm_out, int32_t *pos_out, int32_t *kept_idx,
                          const BatchMeta &meta, const Geometry &g, hipStream_t st);
+
+// prompt prune of the history-window variant: columns of the window's attention rows follow kept_idx
+hipError_t launch_hist_gather(const float *hist_in, const int32_t *kept_idx, float *hist_out, int32_t *hid_out,
+                              int32_t *free_out, int rows, int cap_hist, const BatchMeta &meta, const Geometry &g,
+                              hipStream_t st);
 
 }  // namespace vatp

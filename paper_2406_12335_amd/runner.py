@@ -18,10 +18,13 @@ from . import binding as B
 class PrunedKVCache:
     def __init__(self, batch: int, n_heads: int, head_dim: int, dtype: torch.dtype, n_sink: int, recent: int,
                  budgets: Sequence[int], device, cap_cache: Optional[int] = None, track_pos: bool = True,
-                 ctx=None, norm: int = 0):
+                 ctx=None, norm: int = 0, window: Optional[int] = None):
         self.device = torch.device(device)
         self.batch, self.n_heads, self.head_dim, self.dtype = batch, n_heads, head_dim, dtype
         self.n_sink, self.recent, self.norm = n_sink, recent, norm
+        # window = w: scores over a history window of w steps (Eq. 3) instead of accumulated ones; only the
+        # fused step supports it
+        self.window = window
         self.budgets = [int(x) for x in budgets]
         self.cap = int(cap_cache) if cap_cache else max(self.budgets) + 1
         self._own_ctx = ctx is None
@@ -49,6 +52,12 @@ class PrunedKVCache:
         self._p_dec.set_len(self.lens)
         self.ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.device)
         self.S_prompt = self.nrm_prompt = None
+        if window is not None:
+            self.cap_hist = self.cap
+            self.hist = torch.zeros(batch, n_heads, window + 2, self.cap_hist, dtype=torch.float32, device=self.device)
+            self.hid = [torch.zeros(*shape, dtype=torch.int32, device=self.device) for _ in range(2)]
+            self.free = [torch.zeros(batch * n_heads, dtype=torch.int32, device=self.device) for _ in range(2)]
+            self.hist_prompt = None
         # The decode calls are made once per generated token: their device pointers are converted to
         # ctypes values once, here, instead of on every call.
         vp = lambda t: ctypes.c_void_p(t.data_ptr()) if t is not None else None
@@ -75,7 +84,13 @@ class PrunedKVCache:
         if self.S_prompt is None or self.S_prompt.shape != (b, H, cap_p):
             self.S_prompt = torch.empty(b, H, cap_p, dtype=torch.float32, device=self.device)
             self.nrm_prompt = torch.empty(b, H, cap_p, dtype=torch.float32, device=self.device)
-        B.vatp_prefill_score(self.ctx, p, Q, K, V, self.S_prompt, self.nrm_prompt, self._ws_prompt, stream)
+        if self.window is None:
+            B.vatp_prefill_score(self.ctx, p, Q, K, V, self.S_prompt, self.nrm_prompt, self._ws_prompt, stream)
+        else:
+            if self.hist_prompt is None or self.hist_prompt.shape != (b, H, self.window + 2, cap_p):
+                self.hist_prompt = torch.empty(b, H, self.window + 2, cap_p, dtype=torch.float32, device=self.device)
+            B.vatp_prefill_score_window(self.ctx, p, Q, K, V, self.window, self.S_prompt, self.nrm_prompt,
+                                        self.hist_prompt, self._ws_prompt, stream)
         self._p_prompt = p
         self._prompt_lens = [int(x) for x in lens]
 
@@ -91,8 +106,14 @@ class PrunedKVCache:
         else:
             pos_in = None
         self.cur = 0
-        B.vatp_select_compact(self.ctx, p, K, V, self.S_prompt, self.nrm_prompt, pos_in, self.K[0], self.V[0],
-                              self.S[0], self.nrm[0], self.pos[0], self.kept_idx, None, stream)
+        if self.window is None:
+            B.vatp_select_compact(self.ctx, p, K, V, self.S_prompt, self.nrm_prompt, pos_in, self.K[0], self.V[0],
+                                  self.S[0], self.nrm[0], self.pos[0], self.kept_idx, None, stream)
+        else:
+            B.vatp_select_compact_window(self.ctx, p, K, V, self.S_prompt, self.nrm_prompt, pos_in, self.hist_prompt,
+                                         self.window, self.K[0], self.V[0], self.S[0], self.nrm[0], self.pos[0],
+                                         self.kept_idx, self.hist, self.cap_hist, self.hid[0], self.free[self.synced_cur],
+                                         None, stream)
         self.lens = [min(n, bud) for n, bud in zip(self._prompt_lens, self.budgets)]
         self._synced_valid = False
 
@@ -111,6 +132,8 @@ class PrunedKVCache:
         return ctypes.c_void_p(q.data_ptr()), ctypes.c_void_p(k.data_ptr()), ctypes.c_void_p(v.data_ptr())
 
     def decode_step(self, q, k, v, new_pos: Optional[Sequence[int]], stream=None):
+        if self.window is not None:
+            raise NotImplementedError("history-window scores go through decode_prune_step")
         c, cp = self.cur, self._cp
         self._p_dec.set_len(self.lens)
         st = self._lib.vatp_decode_step(self.ctx, self._p_dec.ref(), *self._qkv(q, k, v), cp["K"][c], cp["V"][c],
@@ -140,6 +163,15 @@ class PrunedKVCache:
             self._synced_valid = True
         self._p_dec.set_len(self.lens)
         cp = self._cp
+        if self.window is not None:
+            B.vatp_decode_prune_step_window(
+                self.ctx, self._p_dec, q, k, v, self.K[c], self.V[c], self.S[c], self.nrm[c], self.pos[c], self.hid[c],
+                new_pos, self.K[o], self.V[o], self.S[o], self.nrm[o], self.pos[o], self.hid[o],
+                self.kept_idx if want_kept_idx else None, self.synced[si], self.synced[so], self.free[si], self.free[so],
+                self.hist, self.window, self.cap_hist, out, self.ws, stream)
+            self.cur, self.synced_cur = o, so
+            self.lens = [min(n + 1, bud) for n, bud in zip(self.lens, self.budgets)]
+            return
         st = self._lib.vatp_decode_prune_step(
             self.ctx, self._p_dec.ref(), *self._qkv(q, k, v), cp["K"][c], cp["V"][c], cp["S"][c], cp["nrm"][c],
             cp["pos"][c], self._new_pos(new_pos), cp["K"][o], cp["V"][o], cp["S"][o], cp["nrm"][o], cp["pos"][o],

@@ -30,16 +30,17 @@ def rtol_for(dtype: torch.dtype) -> float:
     return 1e-5 if dtype == torch.float32 else 1e-3
 
 
-def assert_scores_close(got, want, rtol, what=""):
+def assert_scores_close(got, want, rtol, what="", atol=0.0):
     got = np.asarray(got, dtype=np.float64)
     want = np.asarray(want, dtype=np.float64)
     err = np.abs(got - want)
-    bound = rtol * np.abs(want) + ATOL
+    bound = rtol * np.abs(want) + ATOL + atol
     if not np.all(err <= bound):
         i = int(np.argmax(err / bound))
         raise AssertionError("%s: %d of %d beyond tolerance; worst at %d: got %.9g want %.9g (rel %.3g)" % (
             what, int(np.sum(err > bound)), err.size, i, got[i], want[i], err[i] / max(abs(want[i]), 1e-300)))
-    return float(np.max(err / np.maximum(np.abs(want), 1e-300))) if err.size else 0.0
+    floor = max(1e-300, atol / rtol)          # below this magnitude the absolute part of the bound governs
+    return float(np.max(err / np.maximum(np.abs(want), floor))) if err.size else 0.0
 
 
 def check_kept_set(kept_gpu: np.ndarray, I_oracle: np.ndarray, n: int, B: int, F: int, R: int,
@@ -84,11 +85,15 @@ def _vec(t: torch.Tensor) -> np.ndarray:
 
 def run_trajectory(inp, device, units: Optional[Sequence[Tuple[int, int]]] = None, steps: Optional[int] = None,
                    n_sink: Optional[int] = None, check_every: int = 1, cap_cache: Optional[int] = None,
-                   full_prefill_check: bool = True, norm_kind: int = 0, fused: bool = False) -> TrajectoryReport:
+                   full_prefill_check: bool = True, norm_kind: int = 0, fused: bool = False,
+                   window: Optional[int] = None) -> TrajectoryReport:
     """Prompt pass -> prune -> decode/prune steps on the GPU, mirrored by OracleHead on the chosen units.
 
     fused: every decode step and its prune go through vatp_decode_prune_step instead of
-    vatp_decode_step + vatp_select_compact; the state after each step is compared with the oracle's."""
+    vatp_decode_step + vatp_select_compact; the state after each step is compared with the oracle's.
+    window = w: scores over a history window of w steps (Eq. 3; fused steps only).  The GPU keeps such a
+    score as an fp32 running sum that adds each new weight and later subtracts the same value, so next to
+    the relative tolerance there is an absolute one: a few fp32 ulps of the largest score seen, per step."""
     cfg = inp.cfg
     b, H, d = cfg.batch, cfg.n_heads, cfg.head_dim
     F = cfg.n_sink_keep if n_sink is None else n_sink
@@ -101,7 +106,10 @@ def run_trajectory(inp, device, units: Optional[Sequence[Tuple[int, int]]] = Non
     dev = lambda t: t.to(device)
     Q, K, V = dev(inp.Q), dev(inp.K), dev(inp.V)
     qd, kd, vd = dev(inp.qd), dev(inp.kd), dev(inp.vd)
-    cache = PrunedKVCache(b, H, d, cfg.torch_dtype(), F, R, inp.budgets, device, cap_cache=cap_cache, norm=norm_kind)
+    assert window is None or fused
+    cache = PrunedKVCache(b, H, d, cfg.torch_dtype(), F, R, inp.budgets, device, cap_cache=cap_cache, norm=norm_kind,
+                          window=window)
+    s_max = {u: 0.0 for u in units}          # largest oracle score seen per unit (windowed tolerance)
     try:
         cache.prefill_score(Q, K, V, inp.lens)
         torch.cuda.synchronize()
@@ -110,15 +118,22 @@ def run_trajectory(inp, device, units: Optional[Sequence[Tuple[int, int]]] = Non
         Lmax = max(inp.lens)
         Qh = np.stack([_unit_rows(inp.Q, bb, hh, Lmax) for bb, hh in units])
         Kh = np.stack([_unit_rows(inp.K, bb, hh, Lmax) for bb, hh in units])
-        S_or = orc.prefill_scores_units(Qh, Kh, [inp.lens[bb] for bb, _ in units]) if full_prefill_check else None
+        S_or = orc.prefill_scores_units(Qh, Kh, [inp.lens[bb] for bb, _ in units]) \
+            if full_prefill_check and window is None else None
         for ui, (bb, hh) in enumerate(units):
             L = inp.lens[bb]
-            o = orc.OracleHead(d, norm_kind=norm_kind)
+            o = orc.OracleHead(d, norm_kind=norm_kind, window=window)
             o.K, o.V = Kh[ui, :L].copy(), _unit_rows(inp.V, bb, hh, L)
             o.nrm = orc.vnorm(o.V, norm_kind)
             o.pos = np.arange(L, dtype=np.int64)
             S_gpu = _unit_rows(cache.S_prompt, bb, hh, L)
-            if full_prefill_check:
+            if window is not None:
+                o.S, P = orc.prefill_window(Qh[ui, :L], Kh[ui, :L], window)
+                o.hist = [row.copy() for row in P]
+                s_max[(bb, hh)] = float(o.S.max()) if L else 0.0
+                e = assert_scores_close(S_gpu, o.S, rtol, "windowed prefill S unit (%d,%d)" % (bb, hh))
+                rep.max_rel_err_prefill = max(rep.max_rel_err_prefill, e)
+            elif full_prefill_check:
                 o.S = S_or[ui, :L].copy()
                 e = assert_scores_close(S_gpu, o.S, rtol, "prefill S unit (%d,%d)" % (bb, hh))
                 rep.max_rel_err_prefill = max(rep.max_rel_err_prefill, e)
@@ -164,8 +179,12 @@ def run_trajectory(inp, device, units: Optional[Sequence[Tuple[int, int]]] = Non
                 o.prune(Bq, F, R, forced=kept_gpu)
                 if not do_check:
                     continue
+                atol = 0.0
+                if window is not None:
+                    s_max[(bb, hh)] = max(s_max[(bb, hh)], float(o.S.max()) if nk else 0.0)
+                    atol = 4 * 2.0 ** -24 * (t + 2) * s_max[(bb, hh)]
                 e = assert_scores_close(_unit_rows(cache.S[c], bb, hh, nk), o.S, rtol,
-                                        "fused step %d S unit (%d,%d)" % (t, bb, hh))
+                                        "fused step %d S unit (%d,%d)" % (t, bb, hh), atol=atol)
                 rep.max_rel_err_decode = max(rep.max_rel_err_decode, e)
                 assert_scores_close(_unit_rows(cache.nrm[c], bb, hh, nk), o.nrm, rtol, "fused nrm")
                 assert np.array_equal(_unit_rows(cache.K[c], bb, hh, nk), o.K), "fused: K rows differ from oracle"

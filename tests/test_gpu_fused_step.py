@@ -140,3 +140,23 @@ def test_fused_step_rejects_more_than_one_eviction_and_aliases(gpu_device):
         assert e.value.status == vatp.binding.E_SHAPE
     finally:
         c.close()
+
+
+@pytest.mark.parametrize("name,kw,w", [
+    ("tiny", dict(decode_steps=40), 7),                                      # the whole prompt leaves the window
+    ("tiny", dict(decode_steps=12), 0),
+    ("tiny", dict(decode_steps=10, prompt_len=40), 100),                      # window longer than prompt + decode
+    ("llama7b_layer", dict(n_heads=3, prompt_len=500, decode_steps=30, recent=10), 16),
+    ("llama7b_layer", dict(n_heads=2, head_dim=64, prompt_len=333, decode_steps=20, recent=10), 400),
+    ("ragged16", dict(batch=5, n_heads=2, decode_steps=14, recent=8, ragged=(1, 400)), 9),
+])
+def test_history_window_trajectory_against_oracle(gpu_device, name, kw, w):
+    """Scores over a history window (Eq. 3): windowed prompt pass, prompt prune with its history, fused steps."""
+    cfg = vs.scaled(vs.CONFIGS[name], **kw)
+    _say("history window %d, %s %r" % (w, name, kw))
+    inp = vs.make_inputs(cfg, seed=44)
+    inp.budgets = [max(b, cfg.n_sinks + cfg.recent) for b in inp.budgets]
+    _say("lens=%s budgets=%s" % (inp.lens[:8], inp.budgets[:8]))
+    rep = parity.run_trajectory(inp, gpu_device, fused=True, window=w)
+    _say("report %r" % rep)
+    assert rep.prune_events > 0
