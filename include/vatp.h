@@ -53,7 +53,8 @@ typedef enum {
 enum { VATP_F32 = 0, VATP_BF16 = 1 };
 enum { VATP_NORM_L1 = 0, VATP_NORM_L2 = 1, VATP_NORM_LINF = 2, VATP_NORM_NONE = 3 };
 enum { VATP_CALL_PREFILL_SCORE = 0, VATP_CALL_DECODE_STEP = 1, VATP_CALL_SELECT_COMPACT = 2,
-       VATP_CALL_DECODE_ATTEND_STEP = 3, VATP_CALL_DECODE_PRUNE_STEP = 4 };
+       VATP_CALL_DECODE_ATTEND_STEP = 3, VATP_CALL_DECODE_PRUNE_STEP = 4,
+       VATP_CALL_PREFILL_SCORE_WINDOW = 5 };
 
 typedef struct {
     int32_t batch;          /* 1 .. VATP_MAX_BATCH                                         */
@@ -203,13 +204,14 @@ vatp_status vatp_decode_prune_step(vatp_ctx *ctx, const vatp_params *p,
  *
  * vatp_prefill_score_window: as vatp_prefill_score with S_i = sum_{j >= max(len-1-w, i)} a_i^j
  * (only the prompt's last w+1 query rows are evaluated, a (w+1) x len band instead of the
- * triangle).  hist (device float32 [batch, n_heads, w+2, cap], may be NULL) receives those
- * attention rows, a_i^j at ring row j mod (w+2), column i, for i <= j; other entries are left
- * undefined.  Workspace as for VATP_CALL_PREFILL_SCORE.
+ * triangle).  hist (device float32 [batch, n_heads, w+1, cap], may be NULL) receives those
+ * attention rows, a_i^j at row j - max(len-1-w, 0), column i, for i <= j; other entries are left
+ * undefined.  Workspace size: vatp_workspace_bytes(..., VATP_CALL_PREFILL_SCORE_WINDOW).
  *
- * vatp_select_compact_window: vatp_select_compact of the prompt, after which hist_out (device
+ * vatp_select_compact_window: vatp_select_compact of the prompt (hist: what the call above
+ * left), after which hist_out (device
  * float32 [batch, n_heads, w+2, cap_hist], cap_hist >= min(len, budget)) holds the history of
- * the survivors, column o for survivor o, hid_out ([batch, n_heads, cap_out] int32) is set to
+ * the survivors as a ring (query j in row j mod (w+2)), column o for survivor o, hid_out ([batch, n_heads, cap_out] int32) is set to
  * o and free_out ([batch * n_heads] int32) to the survivor count.
  *
  * vatp_decode_prune_step_window: vatp_decode_prune_step with S_new = S + a^t - a^(t-w-1),

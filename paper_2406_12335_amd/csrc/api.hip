@@ -28,7 +28,7 @@ vatp_status check_params(const vatp_params *p, int which_call)
     const bool decodes = which_call == VATP_CALL_DECODE_STEP || which_call == VATP_CALL_DECODE_ATTEND_STEP ||
                          which_call == VATP_CALL_DECODE_PRUNE_STEP;
     if (prunes && !p->budget) return VATP_E_NULL;
-    if (which_call < VATP_CALL_PREFILL_SCORE || which_call > VATP_CALL_DECODE_PRUNE_STEP) return VATP_E_SHAPE;
+    if (which_call < VATP_CALL_PREFILL_SCORE || which_call > VATP_CALL_PREFILL_SCORE_WINDOW) return VATP_E_SHAPE;
     if (p->dtype != VATP_F32 && p->dtype != VATP_BF16) return VATP_E_DTYPE;
     if (p->batch < 1 || p->batch > VATP_MAX_BATCH || p->n_heads < 1) return VATP_E_SHAPE;
     if (static_cast<int64_t>(p->batch) * p->n_heads > VATP_MAX_UNITS) return VATP_E_SHAPE;
@@ -140,6 +140,9 @@ size_t vatp_workspace_bytes(const vatp_ctx *, const vatp_params *p, int which_ca
     switch (which_call) {
     case VATP_CALL_PREFILL_SCORE:           // lse2[units, cap]
         return align_up(units * p->cap * sizeof(float));
+    case VATP_CALL_PREFILL_SCORE_WINDOW:    // ... + partial row statistics per range of keys
+        return align_up(units * p->cap * sizeof(float)) +
+               align_up(static_cast<size_t>(prefill_window_splits(p->cap)) * units * p->cap * sizeof(float));
     case VATP_CALL_DECODE_STEP: {           // logits[units, cap] + per-chunk softmax statistics
         const size_t chunks = (static_cast<size_t>(p->cap) + kDecodeChunk - 1) / kDecodeChunk;
         return align_up(units * p->cap * sizeof(float)) + align_up(units * chunks * sizeof(float2));
@@ -169,21 +172,27 @@ vatp_status prefill_score_impl(vatp_ctx *ctx, const vatp_params *p, const void *
     if (window < -1 || window > kMaxWindow) return VATP_E_SHAPE;
     const vatp_status st = check_params(p, VATP_CALL_PREFILL_SCORE);
     if (st != VATP_OK) return st;
-    if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16)) return VATP_E_SHAPE;
-    const size_t need = vatp_workspace_bytes(ctx, p, VATP_CALL_PREFILL_SCORE);
+    if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(hist, 4)) return VATP_E_SHAPE;
+    const size_t need = vatp_workspace_bytes(ctx, p, window < 0 ? VATP_CALL_PREFILL_SCORE : VATP_CALL_PREFILL_SCORE_WINDOW);
     if (!ws || ws_bytes < need || misaligned(ws, kAlign)) return VATP_E_WORKSPACE;
     Prepared pr;
     prepare(p, VATP_CALL_PREFILL_SCORE, nullptr, &pr);
+    const size_t units = static_cast<size_t>(p->batch) * p->n_heads;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     float *lse2 = static_cast<float *>(ws);
     if (launch_l1norm(p->dtype, p->head_dim, V, nrm, pr.meta, pr.g, stream) != hipSuccess) return VATP_E_DEVICE;
     if (have_lse && launch_lse_to_base2(lse, lse2, pr.meta, pr.g, stream) != hipSuccess) return VATP_E_DEVICE;
     // bf16 with head_dim 128 runs on the matrix cores; everything else, and the history-window scores
     // (a band of w+1 query rows, a fraction of the full pass), on the fp32 FMA kernels
-    const hipError_t e = (p->dtype == VATP_BF16 && p->head_dim == 128 && window < 0)
-                             ? launch_prefill_mfma(Q, K, S, lse2, have_lse, pr.meta, pr.g, stream)
-                             : launch_prefill_generic(p->dtype, p->head_dim, Q, K, S, lse2, have_lse, window, hist,
-                                                      pr.meta, pr.g, stream);
+    const bool mfma = p->dtype == VATP_BF16 && p->head_dim == 128;
+    hipError_t e;
+    if (mfma && window < 0)
+        e = launch_prefill_mfma(Q, K, S, lse2, have_lse, pr.meta, pr.g, stream);
+    else if (mfma && prefill_mfma_window_fits(window, p->cap))
+        e = launch_prefill_mfma_window(Q, K, S, lse2, lse2 + align_up(units * p->cap * sizeof(float)) / sizeof(float),
+                                       window, hist, pr.meta, pr.g, stream);
+    else
+        e = launch_prefill_generic(p->dtype, p->head_dim, Q, K, S, lse2, have_lse, window, hist, pr.meta, pr.g, stream);
     if (e != hipSuccess) return VATP_E_DEVICE;
     return VATP_OK;
 }

@@ -115,10 +115,10 @@ __global__ __launch_bounds__(256) void gather_kernel(
 }
 
 // History-window scores (Eq. 3): after the prompt has been pruned, the window's attention rows
-// follow the surviving tokens.  hist_in holds a_i^j at [j mod rows][i] for the prompt's last
-// rows-1 queries j and keys i <= j (what the prompt pass stored; everything else is undefined and
-// reads as 0 here); hist_out receives column kept[o] as column o, and surviving row o is given
-// history column o.
+// follow the surviving tokens.  hist_in holds a_i^j at [j - j_first][i] for the prompt's last
+// rows-1 queries j >= j_first and keys i <= j (what the prompt pass stored; everything else is
+// undefined and reads as 0 here); hist_out, a ring of `rows` rows in which query j sits in row
+// j mod rows, receives column kept[o] as column o, and surviving row o is given history column o.
 __global__ __launch_bounds__(256) void hist_gather_kernel(const float *__restrict__ hist_in,
                                                           const int32_t *__restrict__ kept_idx,
                                                           float *__restrict__ hist_out, int32_t *__restrict__ hid_out,
@@ -139,7 +139,7 @@ __global__ __launch_bounds__(256) void hist_gather_kernel(const float *__restric
         const int j = q_first + (s - q_first % rows + rows) % rows;     // the window's query kept in ring row s
         const bool defined = j < n && src <= j;
         hist_out[(unit * rows + s) * static_cast<size_t>(cap_hist) + o] =
-            defined ? hist_in[(unit * rows + s) * static_cast<size_t>(cap) + src] : 0.f;
+            defined ? hist_in[(unit * (rows - 1) + (j - q_first)) * static_cast<size_t>(cap) + src] : 0.f;
     }
 }
 

@@ -14,8 +14,9 @@
 //
 // History-window scores (Eq. 3 after the prompt: only the last w+1 query rows count) use the same
 // two kernels with `window` = w >= 0: query tiles wholly before row len-1-w are skipped, and
-// pass 2 also stores the window's attention rows, p = a_i^j at hist[j mod (w+2)][i], which the
-// decode steps need to drop the row that leaves the window.  window < 0 means no window.
+// pass 2 also stores the window's attention rows, p = a_i^j at row j - j_first of a [w+1, cap]
+// matrix per head, which the decode steps need to drop the row that leaves the window.
+// window < 0 means no window.
 #include "vatp_device.h"
 
 namespace vatp {
@@ -159,9 +160,9 @@ __global__ __launch_bounds__(256) void prefill_colsum_generic(const T *__restric
     const float *lu = lse2 + unit * cap;
     const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
 
-    // first query row that counts, and the history rows of this unit (w+2 of them, cap entries each)
+    // first query row that counts, and the window's attention rows of this unit (w+1 of them, cap entries each)
     const int q_first = window >= 0 ? max(0, len - 1 - window) : 0;
-    float *hu = hist ? hist + unit * static_cast<size_t>(window + 2) * cap : nullptr;
+    float *hu = hist ? hist + unit * static_cast<size_t>(window + 1) * cap : nullptr;
     float col[4] = {0.f, 0.f, 0.f, 0.f};
     for (int j0 = max(i0, q_first / kTile * kTile); j0 < len; j0 += kTile) {
         float acc[4][4];
@@ -171,7 +172,7 @@ __global__ __launch_bounds__(256) void prefill_colsum_generic(const T *__restric
             const int j = j0 + ty * 4 + a;
             if (j < len && j >= q_first) {
                 const float lj = lu[j];
-                float *hrow = hu ? hu + static_cast<size_t>(j % (window + 2)) * cap : nullptr;
+                float *hrow = hu ? hu + static_cast<size_t>(j - q_first) * cap : nullptr;
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
                     const int i = i0 + tx * 4 + c;

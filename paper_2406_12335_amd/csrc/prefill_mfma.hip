@@ -36,6 +36,14 @@
 // index; a workgroup therefore takes the pair of blocks (x, n_blocks-1-x), which gives every
 // workgroup the same amount of work.
 //
+// History-window scores (Eq. 3 after the prompt: only the last w+1 query rows count) reuse both
+// kernels (kWindow).  The row-statistics pass then has only the window's few query blocks to
+// work on, so the keys they stream are cut into ranges, one workgroup per (block, range), each
+// leaving a partial log-sum-exp that a small kernel merges.  The column-sum pass starts
+// streaming at the window's first query, masks the rows before it, and also stores the
+// window's attention rows (row j - j_first of a [w+1, cap] matrix per head) through a buffer
+// descriptor whose bounds check drops the rows outside the window by itself.
+//
 // The contraction index (head dimension) may be permuted freely as long as both operands
 // agree: lane half g takes the 16-byte chunk  s + 8g  of a row for MFMA step s.
 #include <type_traits>
@@ -100,6 +108,16 @@ template <bool kColsum>
 struct Pending {                 // a finished pair of 32x32 tiles awaiting its exponentials
     floatx16 acc[2];
     float lse[kColsum ? 16 : 1];
+    unsigned hist_off[2];        // windowed column sums: byte offset of (first row held, column) per column block
+};
+
+// Arguments of the history-window variant (unused otherwise).
+struct WindowPass {
+    int window;                  // w
+    float *hist;                 // [units, w + 1, cap] attention rows of the window, may be NULL
+    float *lse_part;             // [n_splits, units, cap] partial row statistics
+    int n_splits, split_stages;  // key ranges per query block, 64-row stages per range
+    int n_qb;                    // query blocks per head that can touch the window
 };
 
 template <bool kColsum>
@@ -113,13 +131,22 @@ template <bool kColsum>
 struct Epilogue {
     float ref[2], corr[2], part[2], tmax[2];
 
+    template <bool kStore = false>
     __device__ __forceinline__ void piece(int i, const Pending<kColsum> &p, const Running<kColsum> &run,
-                                          float scale)
+                                          float scale, __amdgpu_buffer_rsrc_t hist_rsrc, int row_bytes)
     {
         if constexpr (kColsum) {
             if (i == 0) { part[0] = 0.f; part[1] = 0.f; }
 #pragma unroll
-            for (int cb = 0; cb < 2; ++cb) part[cb] += fast_exp2(fmaf(p.acc[cb][i], scale, -p.lse[i]));
+            for (int cb = 0; cb < 2; ++cb) {
+                const float pr = fast_exp2(fmaf(p.acc[cb][i], scale, -p.lse[i]));
+                part[cb] += pr;
+                // offsets outside the descriptor (rows before or after the window, columns past the
+                // sequence) are dropped by the store unit
+                if constexpr (kStore)
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_int(pr), hist_rsrc,
+                                                          p.hist_off[cb] + acc_row(i) * row_bytes, 0, 0);
+            }
         } else {
             if (i < 2) {                                   // tile maximum of column block i
                 // a linear chain, so that every two steps fuse into one three-operand maximum
@@ -161,14 +188,16 @@ struct Epilogue {
     }
 };
 
-template <bool kColsum, int kHalves>
+template <bool kColsum, int kHalves, bool kWindow = false>
 __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_t *__restrict__ Q,
                                                            const bf16_t *__restrict__ K,
                                                            float *__restrict__ lse2,
                                                            float *__restrict__ S, BatchMeta meta,
                                                            int n_heads, int n_units, int cap,
-                                                           int n_blocks, float scale_log2)
+                                                           int n_blocks, float scale_log2, WindowPass win)
 {
+    static_assert(!kWindow || kHalves == 1, "the windowed passes use 4-wavefront workgroups");
+    constexpr bool kSplitKeys = kWindow && !kColsum;      // windowed row statistics: one (block, key range) per workgroup
     // A ring slot holds kHalves sub-stages of 64 streamed rows; wavefront w works on sub-stage
     // w / 4 of every slot for the 64 stationary rows of column group w % 4.  With kHalves = 2
     // a workgroup has two wavefronts per SIMD (used when the grid has too few workgroups for
@@ -182,17 +211,24 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
     // Workgroups are handed to the 8 XCDs round-robin by linear id.  All block pairs of one
     // (batch, head) unit are given ids that are equal mod 8, so the unit's streamed matrix is
     // pulled into one XCD's L2 once instead of into all eight.
-    const int n_pairs = (n_blocks + 1) / 2;
+    const int n_pairs = kSplitKeys ? win.n_qb * win.n_splits : (n_blocks + 1) / 2;
     const int xcd = blockIdx.x & 7, in_xcd = blockIdx.x >> 3;
     const int unit_i = xcd + 8 * (in_xcd / n_pairs);
     const int pair = in_xcd % n_pairs;
     if (unit_i >= n_units) return;
     const int b = unit_i / n_heads;
     const int len = meta.len[b];
+    const int q_first = kWindow ? max(0, len - 1 - win.window) : 0;     // first query row that counts
     const size_t unit = static_cast<size_t>(unit_i);
     const uint4 *stat = reinterpret_cast<const uint4 *>((kColsum ? K : Q) + unit * cap * kD);
     const bf16_t *strm = (kColsum ? Q : K) + unit * cap * kD;
     float *lse_u = lse2 + unit * cap;
+    // windowed column sums: descriptor over this head's [w + 1, cap] matrix of attention rows
+    // (no matrix, or another kind of pass: zero records, every store is dropped)
+    const bool with_hist = kWindow && kColsum && win.hist != nullptr;
+    const __amdgpu_buffer_rsrc_t hist_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        with_hist ? win.hist + unit * static_cast<size_t>(win.window + 1) * cap : nullptr, 0,
+        with_hist ? (win.window + 1) * cap * 4 : 0, 0x00020000);
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -226,17 +262,23 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
     };
     // copies per stage issued by this wavefront (column group 0 also brings the lse values)
     const bool extra_copy = kColsum && cw == 0;
-    for (int job = 0; job < 2; ++job) {
-        const int blk = job == 0 ? pair : n_blocks - 1 - pair;
-        if (job == 1 && blk == pair) break;               // odd count: the middle block once
+    for (int job = 0; job < (kSplitKeys ? 1 : 2); ++job) {
+        int blk = job == 0 ? pair : n_blocks - 1 - pair;
+        if constexpr (kSplitKeys) blk = q_first / kBlockCols + pair / win.n_splits;
+        if (!kSplitKeys && job == 1 && blk == pair) break;   // odd count: the middle block once
         const int base0 = blk * kBlockCols;
         if (base0 >= len) continue;
         const int w0 = base0 + cw * kWaveCols;         // first stationary row of this wavefront
 
         // stages of streamed rows this workgroup walks through
-        const int t_begin = kColsum ? base0 / kSlotRows : 0;
+        int t_begin = kColsum ? max(base0, q_first) / kSlotRows : 0;
         const int last_row = kColsum ? len - 1 : min(base0 + kBlockCols - 1, len - 1);
-        const int t_end = last_row / kSlotRows;            // inclusive
+        int t_end = last_row / kSlotRows;                  // inclusive
+        if constexpr (kSplitKeys) {                        // this workgroup's range of keys
+            t_begin = (pair % win.n_splits) * win.split_stages;
+            t_end = min(t_end, t_begin + win.split_stages - 1);
+            if (t_begin > t_end) continue;
+        }
 
 #pragma unroll
         for (int k = 0; k < kAhead; ++k)
@@ -274,6 +316,7 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
             pend.acc[1][v] = -INFINITY;
             if (kColsum) pend.lse[v] = 0.f;
         }
+        pend.hist_off[0] = pend.hist_off[1] = 0x80000000u;      // nothing to store for the neutral pair
 
         // Publish stage t: it is complete once only the copies of younger stages are outstanding.
         // Then the slot freed by stage t-1 (every wavefront is past it now) takes stage t+3.
@@ -323,13 +366,24 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
                         }
 #pragma unroll
                         for (int v = 0; v < 16; ++v) { next.acc[0][v] = 0.f; next.acc[1][v] = 0.f; }
+                        if constexpr (kWindow && kColsum) {
+                            // byte offset of (first streamed row this lane holds - first window row, its
+                            // stationary column); a column past the sequence gets an offset no row can reach
+#pragma unroll
+                            for (int cb = 0; cb < 2; ++cb) {
+                                const int col = w0 + 32 * cb + n;
+                                next.hist_off[cb] = col < len ? static_cast<unsigned>(s0 + 32 * kb + 4 * g - q_first) *
+                                                                        static_cast<unsigned>(cap * 4) + col * 4
+                                                              : 0x80000000u;
+                            }
+                        }
                         Epilogue<kColsum> epi;
 #pragma unroll
                         for (int s = 0; s < 8; ++s) {
                             next.acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], Bf[0][s], next.acc[0], 0, 0, 0);
-                            epi.piece(2 * s, pend, run, scale);
+                            epi.template piece<kWindow && kColsum>(2 * s, pend, run, scale, hist_rsrc, cap * 4);
                             next.acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], Bf[1][s], next.acc[1], 0, 0, 0);
-                            epi.piece(2 * s + 1, pend, run, scale);
+                            epi.template piece<kWindow && kColsum>(2 * s + 1, pend, run, scale, hist_rsrc, cap * 4);
                         }
                         epi.finish(pend, run, scale);
                         // keep the pending pair's results inside this block (no sinking past it)
@@ -350,7 +404,10 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
                             for (int cb = 0; cb < 2; ++cb) {
                                 // lane's stationary index minus the first streamed row it holds
                                 const int row0 = s0 + 32 * kb + 4 * g;
-                                const int d0 = (w0 + 32 * cb + n) - row0;
+                                // (windowed: rows before the window's first query are masked like rows
+                                // before the diagonal)
+                                const int d0 = kWindow && kColsum ? max((w0 + 32 * cb + n) - row0, q_first - row0)
+                                                                  : (w0 + 32 * cb + n) - row0;
                                 const int rows_left = len - row0;
 #pragma unroll
                                 for (int v = 0; v < 16; ++v) {
@@ -368,7 +425,8 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
                 // Sub-stage u = t * kHalves + half holds streamed rows 64u .. 64u+63; the one that
                 // crosses this wavefront's diagonal is u_diag.  t_first is the first stage whose
                 // sub-stage is at or past the diagonal; it is the diagonal itself iff on_diag.
-                const int u_diag = w0 / kStage;
+                // (windowed column sums start at the window's first query if that comes later)
+                const int u_diag = kWindow && kColsum ? max(w0, q_first) / kStage : w0 / kStage;
                 const int du = u_diag - half;
                 const int t_first = du < 0 ? 0 : (du + kHalves - 1) / kHalves;
                 const bool on_diag = du >= 0 && du % kHalves == 0;
@@ -376,14 +434,15 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
                 if (w0 >= len) {
                     for (; t <= t_end; ++t) stage_sync(t);              // no valid stationary row
                 } else if constexpr (!kColsum) {
-                    for (; t < t_first; ++t) { stage_sync(t); do_stage(t, std::false_type{}); }
-                    if (on_diag) { stage_sync(t); do_stage(t, std::true_type{}); ++t; }   // t <= t_end here
+                    // (a range of keys may end before the diagonal or begin after it)
+                    for (; t < t_first && t <= t_end; ++t) { stage_sync(t); do_stage(t, std::false_type{}); }
+                    if (on_diag && t == t_first && t <= t_end) { stage_sync(t); do_stage(t, std::true_type{}); ++t; }
                     for (; t <= t_end; ++t) stage_sync(t);               // keys past the diagonal
                 } else {
                     // last stage whose sub-stage has 64 valid rows: 64u + 63 < len
                     const int t_full_end = (len / kStage - 1 - half + kHalves) / kHalves - 1;
                     for (; t < t_first && t <= t_end; ++t) stage_sync(t);   // queries before the diagonal
-                    if (on_diag && t <= t_end) { stage_sync(t); do_stage(t, std::true_type{}); ++t; }
+                    if (on_diag && t == t_first && t <= t_end) { stage_sync(t); do_stage(t, std::true_type{}); ++t; }
                     for (; t <= min(t_full_end, t_end); ++t) { stage_sync(t); do_stage(t, std::false_type{}); }
                     for (; t <= t_end; ++t) { stage_sync(t); do_stage(t, std::true_type{}); }   // ragged tail
                 }
@@ -393,7 +452,7 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
         {
             Epilogue<kColsum> epi;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) epi.piece(i, pend, run, scale_log2);
+            for (int i = 0; i < 16; ++i) epi.template piece<kWindow && kColsum>(i, pend, run, scale_log2, hist_rsrc, cap * 4);
             epi.finish(pend, run, scale_log2);
         }
 
@@ -440,7 +499,10 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
             for (int cb = 0; cb < 2; ++cb) {
                 const int idx = w0 + 32 * cb + n;
                 if (idx < len) {
-                    if (!kColsum) lse_u[idx] = fin_m[cb] + __log2f(fin_l[cb]);
+                    if constexpr (kSplitKeys)
+                        win.lse_part[(static_cast<size_t>(pair % win.n_splits) * n_units + unit) * cap + idx] =
+                            fin_m[cb] + __log2f(fin_l[cb]);
+                    else if (!kColsum) lse_u[idx] = fin_m[cb] + __log2f(fin_l[cb]);
                     else S[unit * cap + idx] = fin_l[cb];
                 }
             }
@@ -460,9 +522,75 @@ static void launch_both(const bf16_t *Q, const bf16_t *K, float *S, float *lse2,
     const dim3 block(256 * kHalves);
     if (!have_lse)      // row statistics are computed here unless the caller supplied them
         hipLaunchKernelGGL((prefill_mfma_kernel<false, kHalves>), grid, block, 0, st, Q, K, lse2, S, meta, g.n_heads,
-                           n_units, g.cap, n_blocks, g.scale_log2);
+                           n_units, g.cap, n_blocks, g.scale_log2, WindowPass{});
     hipLaunchKernelGGL((prefill_mfma_kernel<true, kHalves>), grid, block, 0, st, Q, K, lse2, S, meta, g.n_heads,
-                       n_units, g.cap, n_blocks, g.scale_log2);
+                       n_units, g.cap, n_blocks, g.scale_log2, WindowPass{});
+}
+
+namespace {
+
+constexpr int kSplitStages = 32;       // keys per workgroup of the windowed row statistics: 32 stages of 64
+
+// lse2_j = log2 sum_s 2^(part_s[j]) over the key ranges s that begin at or before row j, for the
+// window's queries; the few rows before the window that share its first 64-row stage get 0 (they
+// are streamed, masked, by the column-sum pass and must not be NaN).
+__global__ __launch_bounds__(256) void merge_split_lse_kernel(const float *__restrict__ lse_part,
+                                                              float *__restrict__ lse2, BatchMeta meta,
+                                                              int n_heads, int n_units, int cap, int window,
+                                                              int n_splits)
+{
+    const size_t unit = blockIdx.y;
+    const int len = meta.len[unit / n_heads];
+    const int q_first = max(0, len - 1 - window);
+    const int j = q_first / kStage * kStage + blockIdx.x * 256 + threadIdx.x;
+    if (j >= len) return;
+    float out = 0.f;
+    if (j >= q_first) {
+        float m = -INFINITY;
+        for (int s = 0; s < n_splits && s * kSplitStages * kStage <= j; ++s)
+            m = fmaxf(m, lse_part[(static_cast<size_t>(s) * n_units + unit) * cap + j]);
+        float l = 0.f;
+        for (int s = 0; s < n_splits && s * kSplitStages * kStage <= j; ++s)
+            l += exp2f(lse_part[(static_cast<size_t>(s) * n_units + unit) * cap + j] - m);
+        out = m + log2f(l);
+    }
+    lse2[unit * cap + j] = out;
+}
+
+}  // namespace
+
+int prefill_window_splits(int cap) { return ((cap + kStage - 1) / kStage + kSplitStages - 1) / kSplitStages; }
+
+bool prefill_mfma_window_fits(int window, int cap)
+{
+    // byte offsets inside one head's [w + 1, cap] matrix of attention rows are 32-bit
+    return (static_cast<double>(window) + 1 + kBlockCols) * cap * 4.0 < 2147483648.0;
+}
+
+hipError_t launch_prefill_mfma_window(const void *Q, const void *K, float *S, float *lse2, float *lse_part, int window,
+                                      float *hist, const BatchMeta &meta, const Geometry &g, hipStream_t st)
+{
+    if (g.max_len <= 0) return hipSuccess;
+    const int n_blocks = (g.max_len + kBlockCols - 1) / kBlockCols;
+    const int n_units = g.batch * g.n_heads;
+    const unsigned unit_groups = (n_units + 7) / 8;
+    const bf16_t *q = static_cast<const bf16_t *>(Q), *k = static_cast<const bf16_t *>(K);
+    WindowPass win;
+    win.window = window;
+    win.hist = hist;
+    win.lse_part = lse_part;
+    win.split_stages = kSplitStages;
+    win.n_splits = ((g.max_len + kStage - 1) / kStage + kSplitStages - 1) / kSplitStages;
+    const int window_blocks = (window + 1 + kBlockCols - 1) / kBlockCols + 1;     // blocks a window can straddle
+    win.n_qb = window_blocks < n_blocks ? window_blocks : n_blocks;
+    hipLaunchKernelGGL((prefill_mfma_kernel<false, 1, true>), dim3(8u * win.n_qb * win.n_splits * unit_groups), dim3(256),
+                       0, st, q, k, lse2, S, meta, g.n_heads, n_units, g.cap, n_blocks, g.scale_log2, win);
+    const int merge_rows = window + 1 + kStage;
+    hipLaunchKernelGGL(merge_split_lse_kernel, dim3((merge_rows + 255) / 256, n_units), dim3(256), 0, st, lse_part, lse2,
+                       meta, g.n_heads, n_units, g.cap, window, win.n_splits);
+    hipLaunchKernelGGL((prefill_mfma_kernel<true, 1, true>), dim3(8u * ((n_blocks + 1) / 2) * unit_groups), dim3(256), 0,
+                       st, q, k, lse2, S, meta, g.n_heads, n_units, g.cap, n_blocks, g.scale_log2, win);
+    return hipGetLastError();
 }
 
 hipError_t launch_prefill_mfma(const void *Q, const void *K, float *S, float *lse2, bool have_lse,

@@ -133,6 +133,13 @@ hipError_t launch_lse_to_base2(const float *lse, float *lse2, const BatchMeta &m
 hipError_t launch_prefill_mfma(const void *Q, const void *K, float *S, float *lse2, bool have_lse,
                                const BatchMeta &meta, const Geometry &g, hipStream_t st);
 
+// history-window prompt scores on the matrix cores (bf16, head_dim 128); lse_part: workspace of
+// prefill_window_splits(cap) * units * cap floats; usable if prefill_mfma_window_fits(window, cap)
+int prefill_window_splits(int cap);
+bool prefill_mfma_window_fits(int window, int cap);
+hipError_t launch_prefill_mfma_window(const void *Q, const void *K, float *S, float *lse2, float *lse_part, int window,
+                                      float *hist, const BatchMeta &meta, const Geometry &g, hipStream_t st);
+
 hipError_t launch_decode(int dtype, int head_dim, const void *q, const void *k, const void *v,
                          void *K, void *V, float *S, float *nrm, int32_t *pos,
                          float *ws_logit, float2 *ws_part, float *ws_out, float *out, bool finish,

@@ -78,7 +78,8 @@ class PrunedKVCache:
         b, H, cap_p, d = Q.shape
         p = B.Params(b, H, d, self.dtype, self.n_sink, self.recent, cap_p, lens, self.budgets, cap_out=self.cap,
                      norm=self.norm)
-        need = B.vatp_workspace_bytes(self.ctx, p, B.CALL_PREFILL_SCORE)
+        need = B.vatp_workspace_bytes(self.ctx, p, B.CALL_PREFILL_SCORE if self.window is None
+                                      else B.CALL_PREFILL_SCORE_WINDOW)
         if getattr(self, "_ws_prompt", None) is None or self._ws_prompt.numel() < need:
             self._ws_prompt = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
         if self.S_prompt is None or self.S_prompt.shape != (b, H, cap_p):
@@ -87,8 +88,8 @@ class PrunedKVCache:
         if self.window is None:
             B.vatp_prefill_score(self.ctx, p, Q, K, V, self.S_prompt, self.nrm_prompt, self._ws_prompt, stream)
         else:
-            if self.hist_prompt is None or self.hist_prompt.shape != (b, H, self.window + 2, cap_p):
-                self.hist_prompt = torch.empty(b, H, self.window + 2, cap_p, dtype=torch.float32, device=self.device)
+            if self.hist_prompt is None or self.hist_prompt.shape != (b, H, self.window + 1, cap_p):
+                self.hist_prompt = torch.empty(b, H, self.window + 1, cap_p, dtype=torch.float32, device=self.device)
             B.vatp_prefill_score_window(self.ctx, p, Q, K, V, self.window, self.S_prompt, self.nrm_prompt,
                                         self.hist_prompt, self._ws_prompt, stream)
         self._p_prompt = p

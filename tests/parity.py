@@ -20,7 +20,7 @@ from typing import Dict, List, Optional, Sequence, Tuple
 import numpy as np
 import torch
 
-from oracle import vatp_oracle as orc
+from oracle import vatp_oracle as orc  # noqa: F401 (also used as parity.orc)
 from paper_2406_12335_amd.runner import PrunedKVCache
 
 ATOL = 1e-12

@@ -160,3 +160,51 @@ def test_history_window_trajectory_against_oracle(gpu_device, name, kw, w):
     rep = parity.run_trajectory(inp, gpu_device, fused=True, window=w)
     _say("report %r" % rep)
     assert rep.prune_events > 0
+
+
+@pytest.mark.parametrize("dtype,d,lens,w", [
+    ("bf16", 128, [2500, 130], 400),        # two key ranges, window inside the second block
+    ("bf16", 128, [4096, 4095], 400),
+    ("bf16", 128, [2049, 2048], 255),
+    ("bf16", 128, [300, 64], 1000),         # window longer than the prompt
+    ("bf16", 128, [2112, 1], 63),
+    ("bf16", 128, [4100, 257], 0),
+    ("bf16", 128, [700, 699], 256),
+    ("fp32", 64, [700, 65], 100),
+    ("bf16", 64, [1000, 3], 300),
+    ("fp32", 128, [130, 129], 64),
+])
+def test_windowed_prompt_scores_and_attention_rows(gpu_device, dtype, d, lens, w):
+    """vatp_prefill_score_window: S over the last w+1 query rows (Eq. 3) and those rows themselves."""
+    H = 2
+    cfg = vs.scaled(vs.CONFIGS["llama7b_layer"], batch=len(lens), n_heads=H, head_dim=d, dtype=dtype,
+                    prompt_len=max(lens), decode_steps=0)
+    cfg = vs.scaled(cfg, ragged=None)
+    _say("windowed prompt pass %s d=%d lens=%s w=%d" % (dtype, d, lens, w))
+    inp = vs.make_inputs(cfg, seed=61)
+    dev = gpu_device
+    tdt = cfg.torch_dtype()
+    cap = max(lens)
+    ctx = vatp.vatp_create(0)
+    try:
+        p = vatp.Params(len(lens), H, d, tdt, 0, 0, cap, lens, None)
+        ws = torch.empty(vatp.vatp_workspace_bytes(ctx, p, vatp.CALL_PREFILL_SCORE_WINDOW), dtype=torch.uint8, device=dev)
+        S = torch.full((len(lens), H, cap), -1.0, device=dev)
+        nrm = torch.empty(len(lens), H, cap, device=dev)
+        hist = torch.full((len(lens), H, w + 1, cap), -2.0, device=dev)
+        vatp.vatp_prefill_score_window(ctx, p, inp.Q.to(dev), inp.K.to(dev), inp.V.to(dev), w, S, nrm, hist, ws)
+        torch.cuda.synchronize()
+        S, hist = S.cpu().double().numpy(), hist.cpu().double().numpy()
+    finally:
+        vatp.vatp_destroy(ctx)
+    rtol = parity.rtol_for(tdt)
+    for b, L in enumerate(lens):
+        for h in range(H):
+            S_or, P_or = parity.orc.prefill_window(inp.Q[b, h, :L].double().numpy(), inp.K[b, h, :L].double().numpy(), w)
+            parity.assert_scores_close(S[b, h, :L], S_or, rtol, "windowed S (%d,%d)" % (b, h))
+            assert np.all(S[b, h, L:] == -1.0), "scores past the end of the sequence were touched"
+            j0 = max(0, L - 1 - w)
+            for r in range(P_or.shape[0]):
+                j = j0 + r
+                parity.assert_scores_close(hist[b, h, r, :j + 1], P_or[r, :j + 1], rtol,
+                                           "attention row of query %d unit (%d,%d)" % (j, b, h), atol=1e-35)
