@@ -29,9 +29,13 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 FP32_VECTOR_PEAK_TFLOPS = 157.3
 
 
-def algorithmic_flops_prefill(cfg, lens):
-    """Both scoring passes, causal lower triangle only: 2 passes * 2*d flops per (query, key<=query) pair."""
-    return sum(cfg.n_heads * 2 * 2 * cfg.head_dim * (L * (L + 1) // 2) for L in lens) * cfg.layers
+def algorithmic_flops_prefill(cfg, lens, window=None):
+    """Both scoring passes, causal lower triangle only: 2 passes * 2*d flops per (query, key<=query) pair;
+    with a history window only the last window+1 query rows count."""
+    def pairs(L):
+        first = 0 if window is None else max(0, L - 1 - window)
+        return (L * (L + 1) - first * (first + 1)) // 2
+    return sum(cfg.n_heads * 2 * 2 * cfg.head_dim * pairs(L) for L in lens) * cfg.layers
 
 
 def algorithmic_bytes_decode(cfg, n_rows, budget):
@@ -54,6 +58,12 @@ def algorithmic_bytes_fused(cfg, n_rows, budget, rows_moved):
     return n_rows * row + 8 * n_rows + 4 * keep + rows_moved * (4 * row + 16)
 
 
+def algorithmic_bytes_window(cfg, n_rows, window, rows_moved):
+    """Extra bytes of the history-window step per unit: the leaving weight read and the new one written
+    per row (plus the row's column index), the new row's column cleared, and the column index moved."""
+    return 12 * n_rows + 4 * window + 8 * rows_moved
+
+
 def run(args):
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (got --gpus %d)" % args.gpus, file=sys.stderr)
@@ -73,15 +83,19 @@ def run(args):
     if args.decode_steps is not None:
         cfg = vs.scaled(cfg, decode_steps=args.decode_steps)
     T = cfg.decode_steps
+    fused = args.decode_route == "fused"
+    window = args.window
+    if window is not None and not fused:
+        print("bench.py: history-window scores run through the fused decode route only", file=sys.stderr)
+        sys.exit(2)
     layers = [vs.make_inputs(cfg, seed=args.seed, layer=l, device=dev) for l in range(cfg.layers)]
     lens, budgets = layers[0].lens, layers[0].budgets
     for inp in layers:      # per-step views of the new tokens, made once (indexing costs host time per call)
         inp.step_qkv = [(inp.qd[t], inp.kd[t], inp.vd[t]) for t in range(T)]
     ctx = vatp.vatp_create(0)
     caches = [PrunedKVCache(cfg.batch, cfg.n_heads, cfg.head_dim, cfg.torch_dtype(), cfg.n_sink_keep, cfg.recent,
-                            budgets, dev, ctx=ctx) for _ in layers]
+                            budgets, dev, ctx=ctx, window=window) for _ in layers]
     new_pos = [[L + t for L in lens] for t in range(T)]
-    fused = args.decode_route == "fused"
 
     def one_step(ev=None):
         """ev: optional dict of event lists, filled with (start, end) pairs per phase."""
@@ -140,7 +154,7 @@ def run(args):
     for inp, cache in zip(layers, caches):
         cache.prefill_score(inp.Q, inp.K, inp.V, lens)
         cache.prune_prompt(inp.K, inp.V)
-    for t in range(T):
+    for t in range(T if window is None else 0):
         for inp, cache in zip(layers, caches):
             a = torch.cuda.Event(enable_timing=True); a.record()
             cache.decode_step(*inp.step_qkv[t], new_pos[t])
@@ -178,13 +192,15 @@ def run(args):
                     moved = (keep - first[bb]).clamp_(min=0)
                     fused_rows_moved += int(moved.sum())
                     fused_bytes += sum(algorithmic_bytes_fused(cfg, n_after[bb], budgets[bb], int(m)) for m in moved)
+                    if window is not None:
+                        fused_bytes += sum(algorithmic_bytes_window(cfg, n_after[bb], window, int(m)) for m in moved)
         if not readback:
             host_us_per_call = (time.perf_counter() - t_host) * 1e6 / n_calls    # enqueue only, no sync yet
         torch.cuda.synchronize()
     fused_call_ms = total_ms(fused_pairs) / n_calls
 
     # algorithmic work
-    flops = algorithmic_flops_prefill(cfg, lens)
+    flops = algorithmic_flops_prefill(cfg, lens, window)
     n_tokens = sum(lens) * cfg.layers
     dec_bytes = sel_bytes = 0
     cur = [min(L, B) for L, B in zip(lens, budgets)]
@@ -201,7 +217,8 @@ def run(args):
     peak_tf = MFMA_BF16_PEAK_TFLOPS if mfma else FP32_VECTOR_PEAK_TFLOPS
     traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name, cfg.layers), {})
     prefill_tflops = flops / (prefill_ms * 1e-3) / 1e12 if prefill_ms > 0 else 0.0
-    roof_prefill = {"kernel": "vatp_prefill_score = l1norm_kernel + prefill rowstat + prefill colsum",
+    roof_prefill = {"kernel": "vatp_prefill_score = l1norm_kernel + prefill rowstat + prefill colsum" if window is None
+                    else "vatp_prefill_score_window = l1norm_kernel + rowstat over key ranges + merge + colsum with rows",
                     "bound": "mfma" if mfma else "alu",
                     "achieved": round(prefill_tflops, 3), "peak": peak_tf, "unit": "TFLOP/s",
                     "frac": round(prefill_tflops / peak_tf, 5), "traffic": traffic.get("prefill_score"),
@@ -231,8 +248,11 @@ def run(args):
         phases = {"prefill_score": prefill_ms, "decode_step": dec_call_ms * n_calls,
                   "select_compact": sel_call_ms * n_calls}
     dominant = max(phases, key=phases.get)
-    roofline_all = {"prefill_score": roof_prefill, "decode_prune_step": roof_fused, "decode_step": roof_decode,
-                    "select_compact": roof_gather}
+    roofline_all = {"prefill_score": roof_prefill, "decode_prune_step": roof_fused}
+    if window is None:
+        roofline_all.update({"decode_step": roof_decode, "select_compact": roof_gather})
+    else:
+        roof_fused["kernel"] = "vatp_decode_prune_step_window = decode_logits_kernel + decode_prune_kernel (history window)"
     roofline = roofline_all[dominant]
 
     out = {
@@ -246,7 +266,8 @@ def run(args):
         "config": {"workload": cfg.name, "batch": cfg.batch, "layers": cfg.layers, "n_heads": cfg.n_heads,
                    "head_dim": cfg.head_dim, "prompt_len": lens if cfg.ragged else cfg.prompt_len,
                    "budget_pct": cfg.budget_pct, "recent": cfg.recent, "n_sink": cfg.n_sink_keep,
-                   "decode_steps": T, "decode_route": args.decode_route},
+                   "decode_steps": T, "decode_route": args.decode_route, "score": "accumulated (Eq. 2)" if window is None
+                   else "history window w=%d (Eq. 3)" % window},
         "prefill_ms": round(prefill_ms, 4), "prompt_prune_ms": round(prune_ms, 4), "decode_loop_ms": round(decode_ms, 4),
         "prefill_pct_mfma_peak": round(100 * roof_prefill["frac"], 3) if mfma else None,
         "decode_prune_GBps": round(decode_gbps, 2),
@@ -255,7 +276,7 @@ def run(args):
         "roofline_all": roofline_all,
         # the same decode loop through the other route (per-call event times of the replays)
         "decode_loop_ms_by_route": {"fused": round(fused_call_ms * n_calls / 1, 4),
-                                    "separate": round((dec_call_ms + sel_call_ms) * n_calls, 4)},
+                                    "separate": round((dec_call_ms + sel_call_ms) * n_calls, 4) if window is None else None},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, layers[0], args.cpu_seconds)
@@ -336,6 +357,8 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=None)
     ap.add_argument("--decode-route", default="fused", choices=["fused", "separate"],
                     help="fused: vatp_decode_prune_step; separate: vatp_decode_step + vatp_select_compact")
+    ap.add_argument("--window", type=int, default=None,
+                    help="history-window scores (Eq. 3) with this window instead of accumulated scores (Eq. 2)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)

@@ -162,7 +162,7 @@ size_t vatp_workspace_bytes(const vatp_ctx *, const vatp_params *p, int which_ca
 
 namespace {
 
-constexpr int kMaxWindow = 1 << 20;
+constexpr int kMaxWindow = 1 << 18;      // (the history gather indexes ring rows / 8 with a 16-bit grid dimension)
 
 vatp_status prefill_score_impl(vatp_ctx *ctx, const vatp_params *p, const void *Q, const void *K, const void *V,
                                const float *lse, bool have_lse, int window, float *hist, float *S, float *nrm,

@@ -119,6 +119,8 @@ __global__ __launch_bounds__(256) void gather_kernel(
 // rows-1 queries j >= j_first and keys i <= j (what the prompt pass stored; everything else is
 // undefined and reads as 0 here); hist_out, a ring of `rows` rows in which query j sits in row
 // j mod rows, receives column kept[o] as column o, and surviving row o is given history column o.
+constexpr int kHistRowsPerBlock = 8;     // ring rows per workgroup of the history gather
+
 __global__ __launch_bounds__(256) void hist_gather_kernel(const float *__restrict__ hist_in,
                                                           const int32_t *__restrict__ kept_idx,
                                                           float *__restrict__ hist_out, int32_t *__restrict__ hid_out,
@@ -130,17 +132,23 @@ __global__ __launch_bounds__(256) void hist_gather_kernel(const float *__restric
     const int n = meta.len[b], B = meta.aux[b];
     const int n_keep = n < B ? n : B;
     const int o = blockIdx.x * 256 + threadIdx.x;
-    if (blockIdx.x == 0 && threadIdx.x == 0) free_out[unit] = n_keep;
+    const int s0 = blockIdx.z * kHistRowsPerBlock;
+    if (blockIdx.x == 0 && blockIdx.z == 0 && threadIdx.x == 0) free_out[unit] = n_keep;
     if (o >= n_keep) return;
     const int src = kept_idx[unit * cap_out + o];
-    hid_out[unit * cap_out + o] = o;
+    if (blockIdx.z == 0) hid_out[unit * cap_out + o] = o;
     const int q_first = max(0, n - (rows - 1));            // first query of the window (w + 1 = rows - 1 of them)
-    for (int s = 0; s < rows; ++s) {
+    float val[kHistRowsPerBlock];
+#pragma unroll
+    for (int u = 0; u < kHistRowsPerBlock; ++u) {          // all loads first, then the stores
+        const int s = s0 + u;
         const int j = q_first + (s - q_first % rows + rows) % rows;     // the window's query kept in ring row s
-        const bool defined = j < n && src <= j;
-        hist_out[(unit * rows + s) * static_cast<size_t>(cap_hist) + o] =
-            defined ? hist_in[(unit * (rows - 1) + (j - q_first)) * static_cast<size_t>(cap) + src] : 0.f;
+        const bool defined = s < rows && j < n && src <= j;
+        val[u] = defined ? hist_in[(unit * (rows - 1) + (j - q_first)) * static_cast<size_t>(cap) + src] : 0.f;
     }
+#pragma unroll
+    for (int u = 0; u < kHistRowsPerBlock; ++u)
+        if (s0 + u < rows) hist_out[(unit * rows + s0 + u) * static_cast<size_t>(cap_hist) + o] = val[u];
 }
 
 }  // namespace
@@ -178,7 +186,9 @@ hipError_t launch_hist_gather(const float *hist_in, const int32_t *kept_idx, flo
 {
     const unsigned units = static_cast<unsigned>(g.batch) * g.n_heads;
     const int max_keep = g.max_len > 0 ? g.max_len : 1;       // max_len: largest surviving row count
-    hipLaunchKernelGGL(hist_gather_kernel, dim3((max_keep + 255) / 256, units), dim3(256), 0, st, hist_in, kept_idx,
+    hipLaunchKernelGGL(hist_gather_kernel,
+                       dim3((max_keep + 255) / 256, units, (rows + kHistRowsPerBlock - 1) / kHistRowsPerBlock), dim3(256), 0,
+                       st, hist_in, kept_idx,
                        hist_out, hid_out, free_out, meta, g.n_heads, g.cap, g.cap_out, cap_hist, rows);
     return hipGetLastError();
 }
