@@ -149,61 +149,93 @@ def run(args):
     prune_ms = total_ms(ev["prompt_prune"]) / args.steps
     decode_ms = total_ms(ev["decode_loop"]) / args.steps
 
-    # instrumented replay (outside the timed region): split the decode loop per entry point
-    split = {"decode_step": [], "select_compact": []}
-    for inp, cache in zip(layers, caches):
-        cache.prefill_score(inp.Q, inp.K, inp.V, lens)
-        cache.prune_prompt(inp.K, inp.V)
-    for t in range(T if window is None else 0):
-        for inp, cache in zip(layers, caches):
-            a = torch.cuda.Event(enable_timing=True); a.record()
-            cache.decode_step(*inp.step_qkv[t], new_pos[t])
-            b = torch.cuda.Event(enable_timing=True); b.record()
-            cache.prune()
-            c = torch.cuda.Event(enable_timing=True); c.record()
-            split["decode_step"].append((a, b))
-            split["select_compact"].append((b, c))
-    torch.cuda.synchronize()
-    n_calls = max(1, T * cfg.layers)
-    dec_call_ms = total_ms(split["decode_step"]) / n_calls
-    sel_call_ms = total_ms(split["select_compact"]) / n_calls
+    # Replays outside the timed region.  Each is a loop bracketed by ONE pair of events on the stream
+    # the library launches on (event pairs around single calls inside a deep queue proved unreliable).
+    def timed(fn):
+        a = torch.cuda.Event(enable_timing=True); a.record()
+        fn()
+        b = torch.cuda.Event(enable_timing=True); b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b)
 
-    # second replay: the fused route, timed per call; the per-head count of rows it had to move is
-    # read back after every step (min of the two `synced` arrays = first rewritten row)
-    fused_pairs, fused_bytes, fused_rows_moved = [], 0, 0
-    for readback in (False, True):          # first pass: timing only; second pass: rows moved, with syncs
+    def reset():
         for inp, cache in zip(layers, caches):
             cache.prefill_score(inp.Q, inp.K, inp.V, lens)
             cache.prune_prompt(inp.K, inp.V)
+        torch.cuda.synchronize()
+
+    n_calls = max(1, T * cfg.layers)
+    sep_loop_ms = dec_call_ms = sel_call_ms = 0.0
+    if window is None and T:
+        # (1) the decode loop through the separate calls
+        def separate_loop():
+            for t in range(T):
+                for inp, cache in zip(layers, caches):
+                    cache.decode_step(*inp.step_qkv[t], new_pos[t])
+                    cache.prune()
+        reset()
+        sep_loop_ms = timed(separate_loop)
+        # (2) each entry point by itself, T calls on the steady-state shape (the cache holds its budget, the
+        # step appends one row, the prune removes one): the row counts are put back after every call
+        reset()
+        base = [list(c.lens) for c in caches]
+
+        def decode_only():
+            for t in range(T):
+                for inp, cache, n0 in zip(layers, caches, base):
+                    cache.decode_step(*inp.step_qkv[t], new_pos[t])
+                    cache.lens = list(n0)
+        dec_call_ms = timed(decode_only) / n_calls
+        for inp, cache in zip(layers, caches):
+            cache.decode_step(*inp.step_qkv[0], new_pos[0])
+        grown = [(c.cur, list(c.lens)) for c in caches]
+
+        def prune_only():
+            for t in range(T):
+                for cache, (cur0, n1) in zip(caches, grown):
+                    cache.prune()
+                    cache.cur, cache.lens = cur0, list(n1)
+        sel_call_ms = timed(prune_only) / n_calls
+
+    # (3) the fused route: whole loop timed; in a second pass the per-head count of rows it had to move is
+    # read back after every step (min of the two `synced` arrays = first rewritten row)
+    fused_bytes, fused_rows_moved = 0, 0
+    host_us_per_call = 0.0
+
+    def fused_loop():
+        nonlocal host_us_per_call
         t_host = time.perf_counter()
         for t in range(T):
             for inp, cache in zip(layers, caches):
-                n_after = [n + 1 for n in cache.lens]
-                if not readback:
-                    a = torch.cuda.Event(enable_timing=True); a.record()
                 cache.decode_prune_step(*inp.step_qkv[t], new_pos[t], want_kept_idx=False)
-                if not readback:
-                    b = torch.cuda.Event(enable_timing=True); b.record()
-                    fused_pairs.append((a, b))
-                    continue
-                first = torch.minimum(cache.synced[0], cache.synced[1]).view(cfg.batch, cfg.n_heads).cpu()
-                for bb in range(cfg.batch):
-                    keep = min(n_after[bb], budgets[bb])
-                    moved = (keep - first[bb]).clamp_(min=0)
-                    fused_rows_moved += int(moved.sum())
-                    fused_bytes += sum(algorithmic_bytes_fused(cfg, n_after[bb], budgets[bb], int(m)) for m in moved)
-                    if window is not None:
-                        fused_bytes += sum(algorithmic_bytes_window(cfg, n_after[bb], window, int(m)) for m in moved)
-        if not readback:
-            host_us_per_call = (time.perf_counter() - t_host) * 1e6 / n_calls    # enqueue only, no sync yet
-        torch.cuda.synchronize()
-    fused_call_ms = total_ms(fused_pairs) / n_calls
+        host_us_per_call = (time.perf_counter() - t_host) * 1e6 / n_calls    # enqueue only, no sync yet
+    reset()
+    fused_call_ms = timed(fused_loop) / n_calls
+    reset()
+    for t in range(T):
+        for inp, cache in zip(layers, caches):
+            n_after = [n + 1 for n in cache.lens]
+            cache.decode_prune_step(*inp.step_qkv[t], new_pos[t], want_kept_idx=False)
+            first = torch.minimum(cache.synced[0], cache.synced[1]).view(cfg.batch, cfg.n_heads).cpu()
+            for bb in range(cfg.batch):
+                keep = min(n_after[bb], budgets[bb])
+                moved = (keep - first[bb]).clamp_(min=0)
+                fused_rows_moved += int(moved.sum())
+                fused_bytes += sum(algorithmic_bytes_fused(cfg, n_after[bb], budgets[bb], int(m)) for m in moved)
+                if window is not None:
+                    fused_bytes += sum(algorithmic_bytes_window(cfg, n_after[bb], window, int(m)) for m in moved)
+    torch.cuda.synchronize()
 
     # algorithmic work
     flops = algorithmic_flops_prefill(cfg, lens, window)
     n_tokens = sum(lens) * cfg.layers
-    dec_bytes = sel_bytes = 0
+    dec_bytes = sel_bytes = 0          # over the T steps of the trajectory (the separate route's loop)
+    dec_call_bytes = sel_call_bytes = 0   # one call at the steady-state shape (the isolated loops)
     cur = [min(L, B) for L, B in zip(lens, budgets)]
+    for b in range(cfg.batch):
+        s, c = algorithmic_bytes_decode(cfg, cur[b] + 1, budgets[b])
+        dec_call_bytes += s * cfg.n_heads
+        sel_call_bytes += c * cfg.n_heads
     for t in range(T):
         for b in range(cfg.batch):
             s, c = algorithmic_bytes_decode(cfg, cur[b] + 1, budgets[b])
@@ -232,8 +264,8 @@ def run(args):
                   "avg_launch_ms": round(fused_call_ms, 5),
                   "host_enqueue_us_per_call": round(host_us_per_call, 2),
                   "rows_moved_per_head_step": round(fused_rows_moved / max(1, n_calls * cfg.batch * cfg.n_heads), 2)}
-    dec_k_gbps = dec_bytes / n_calls / (dec_call_ms * 1e-3) / 1e9 if T and dec_call_ms > 0 else 0.0
-    sel_k_gbps = sel_bytes / n_calls / (sel_call_ms * 1e-3) / 1e9 if T and sel_call_ms > 0 else 0.0
+    dec_k_gbps = dec_call_bytes / (dec_call_ms * 1e-3) / 1e9 if T and dec_call_ms > 0 else 0.0
+    sel_k_gbps = sel_call_bytes / (sel_call_ms * 1e-3) / 1e9 if T and sel_call_ms > 0 else 0.0
     roof_decode = {"kernel": "vatp_decode_step = decode_logits_kernel + decode_finish_kernel", "bound": "hbm",
                    "achieved": round(dec_k_gbps, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                    "frac": round(dec_k_gbps / HBM_PEAK_GBPS, 5), "traffic": traffic.get("decode_step"),
@@ -276,7 +308,7 @@ def run(args):
         "roofline_all": roofline_all,
         # the same decode loop through the other route (per-call event times of the replays)
         "decode_loop_ms_by_route": {"fused": round(fused_call_ms * n_calls / 1, 4),
-                                    "separate": round((dec_call_ms + sel_call_ms) * n_calls, 4) if window is None else None},
+                                    "separate": round(sep_loop_ms, 4) if window is None else None},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, layers[0], args.cpu_seconds)

@@ -36,8 +36,11 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(
     __shared__ float s_logit[kDecodeChunk];
     __shared__ float s_red[8];
 
-    const size_t unit = blockIdx.y;
-    const int b = static_cast<int>(unit / n_heads), chunk = blockIdx.x;
+    // unit in the fast grid dimension: workgroups go to the 8 XCDs round-robin by linear id, so (with a
+    // unit count that is a multiple of 8) a head's chunks, and the launch that consumes their logits,
+    // share one XCD's L2
+    const size_t unit = blockIdx.x;
+    const int b = static_cast<int>(unit / n_heads), chunk = blockIdx.y;
     const int n0 = meta.len[b];            // rows cached before this step = index of the new row
     const int n = n0 + 1;
     const int row0 = chunk * kDecodeChunk;
@@ -159,11 +162,11 @@ __global__ __launch_bounds__(256) void decode_finish_kernel(float *__restrict__ 
                                                             BatchMeta meta, int n_heads, int cap,
                                                             int chunks_alloc)
 {
-    const size_t unit = blockIdx.y;
+    const size_t unit = blockIdx.x;
     const int b = static_cast<int>(unit / n_heads);
     const int n0 = meta.len[b], n = n0 + 1;
-    const int r = blockIdx.x * 256 + threadIdx.x;                // one row per thread
-    if (blockIdx.x * 256 >= n) return;
+    const int r = blockIdx.y * 256 + threadIdx.x;                // one row per thread
+    if (blockIdx.y * 256 >= n) return;
     float logit = 0.f, s_old = 0.f;
     if (r < n) {
         logit = ws_logit[unit * cap + r];
@@ -177,7 +180,7 @@ __global__ __launch_bounds__(256) void decode_finish_kernel(float *__restrict__ 
     const float lse2 = M + log2f(L);
     if (r < n) S[unit * cap + r] = s_old + exp2f(logit - lse2);
     // attention output of the new token: the chunks' partial sums, rescaled to the common maximum
-    if (out && blockIdx.x == 0 && threadIdx.x < head_dim)
+    if (out && blockIdx.y == 0 && threadIdx.x < head_dim)
         out[unit * head_dim + threadIdx.x] = merge_chunk_outputs(ws_out + unit * chunks_alloc * head_dim, part, n_chunks,
                                                                  head_dim, threadIdx.x, M, L);
 }
@@ -191,7 +194,7 @@ hipError_t launch_decode(int dtype, int head_dim, const void *q, const void *k, 
 {
     const int chunks_alloc = (g.cap + kDecodeChunk - 1) / kDecodeChunk;
     const unsigned units = static_cast<unsigned>(g.batch) * g.n_heads;
-    dim3 grid((g.max_len + kDecodeChunk - 1) / kDecodeChunk, units), block(256);
+    dim3 grid(units, (g.max_len + kDecodeChunk - 1) / kDecodeChunk), block(256);
     const bool attend = ws_out != nullptr;
 #define VATP_DEC(T, D, A)                                                                              \
     hipLaunchKernelGGL((decode_logits_kernel<T, D, A>), grid, block, 0, st, static_cast<const T *>(q),  \
@@ -206,7 +209,7 @@ hipError_t launch_decode(int dtype, int head_dim, const void *q, const void *k, 
 #undef VATP_DEC2
 #undef VATP_DEC
     if (finish)     // (the fused decode-and-evict step has its own second launch)
-        hipLaunchKernelGGL(decode_finish_kernel, dim3((g.max_len + 255) / 256, units), block, 0, st, S, ws_logit,
+        hipLaunchKernelGGL(decode_finish_kernel, dim3(units, (g.max_len + 255) / 256), block, 0, st, S, ws_logit,
                            ws_part, ws_out, out, head_dim, meta, g.n_heads, g.cap, chunks_alloc);
     return hipGetLastError();
 }

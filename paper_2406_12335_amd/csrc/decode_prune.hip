@@ -11,7 +11,7 @@
 // `recent` rows move per step instead of the whole cache; the scores themselves change in
 // every row and are rewritten in full.
 //
-// Grid: (G, units).  Each of a head's G workgroups repeats the cheap part (12 bytes per row
+// Grid: (units, G).  Each of a head's G workgroups repeats the cheap part (12 bytes per row
 // from L2: logit, S, nrm) to learn the evicted row by itself, then takes a 1/G share of the
 // stores, so the launch needs no exchange between workgroups and no second pass.
 //
@@ -41,8 +41,11 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
 
     __shared__ unsigned long long s_min[kThreads / 64];
 
-    const size_t unit = blockIdx.y;
-    const int g = blockIdx.x, G = gridDim.x;
+    // workgroups go to the 8 XCDs round-robin by linear id = unit + units * g: with the unit in the fast
+    // dimension a head's G workgroups meet in one XCD's L2 (unit count a multiple of 8), where the rows
+    // they all scan are fetched once
+    const size_t unit = blockIdx.x;
+    const int g = blockIdx.y, G = gridDim.y;
     const int b = static_cast<int>(unit / n_heads);
     const int n0 = meta.len[b], n = n0 + 1, B = meta.aux[b];
     const int n_keep = n < B ? n : B;
@@ -360,7 +363,7 @@ hipError_t launch_decode_prune(int dtype, int head_dim, const void *K, const voi
     // enough workgroups per head to occupy the chip once (4 of these fit a compute unit)
     unsigned G = 1024u / units;
     G = G < 1u ? 1u : (G > 16u ? 16u : G);
-    dim3 grid(G, units), block(kThreads);
+    dim3 grid(units, G), block(kThreads);
 #define VATP_DP(T, D)                                                                                          \
     hipLaunchKernelGGL((decode_prune_kernel<T, D>), grid, block, 0, st, static_cast<const T *>(K),               \
                        static_cast<const T *>(V), S, nrm, pos, static_cast<T *>(K_out), static_cast<T *>(V_out), \

@@ -72,6 +72,10 @@ def test_workspace_bytes():
     assert dec >= units * cap * 4 and dec % 256 == 0
     assert vatp.vatp_workspace_bytes(None, p, vatp.CALL_SELECT_COMPACT) == 0
     assert vatp.vatp_workspace_bytes(None, _params(dtype=9), vatp.CALL_PREFILL_SCORE) == 0
+    # windowed prompt pass: row statistics plus one set of partial statistics per 2048 keys
+    assert vatp.vatp_workspace_bytes(None, p, vatp.CALL_PREFILL_SCORE_WINDOW) == 2 * units * cap * 4
+    big = _params(cap=5000, len=[5000, 1], budget=[2500, 2500])
+    assert vatp.vatp_workspace_bytes(None, big, vatp.CALL_PREFILL_SCORE_WINDOW) == 4 * units * 5000 * 4
 
 
 def test_entry_points_reject_null_before_any_launch():
@@ -81,6 +85,12 @@ def test_entry_points_reject_null_before_any_launch():
     assert lib.vatp_decode_step(None, p.ref(), *([None] * 9), None, 0, None) == binding.E_NULL
     assert lib.vatp_select_compact(None, p.ref(), *([None] * 11), None, 0, None) == binding.E_NULL
     assert lib.vatp_decode_prune_step(None, p.ref(), *([None] * 18), None, 0, None) == binding.E_NULL
+    assert lib.vatp_prefill_score_window(None, p.ref(), None, None, None, 4, None, None, None, None, 0, None) == binding.E_NULL
+    assert lib.vatp_prefill_score_window(None, p.ref(), None, None, None, -1, None, None, None, None, 0, None) == binding.E_SHAPE
+    assert lib.vatp_select_compact_window(None, p.ref(), *([None] * 6), 4, *([None] * 7), 64, None, None, None, 0,
+                                          None) == binding.E_NULL
+    assert lib.vatp_decode_prune_step_window(None, p.ref(), *([None] * 9), None, *([None] * 12), 4, 64, None, None, 0,
+                                             None) == binding.E_NULL
     assert "NULL" in vatp.strerror(binding.E_NULL)
     assert vatp.strerror(-99) == "unknown status"
 
