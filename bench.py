@@ -323,8 +323,10 @@ def run(args):
 # (FETCH_SIZE x2.000, WRITE_SIZE x1.000); summaries under profiles/.  Keyed by (workload, layers).
 MEASURED_TRAFFIC_BYTES = {
     # calibrated fetch + write bytes per call of the entry point (all of its kernels)
-    ("llama7b_layer", 1): {"prefill_score": 172539487, "decode_step": 18215899, "select_compact": 72840051},
-    ("llama7b_stack", 2): {"prefill_score": 1891085500, "decode_step": 58155237, "select_compact": 233123329},
+    ("llama7b_layer", 1): {"prefill_score": 173490899, "decode_step": 18041612, "select_compact": 72839834,
+                           "decode_prune_step": 21023376},
+    ("llama7b_stack", 2): {"prefill_score": 1891836631, "decode_step": 57720561, "select_compact": 233090131,
+                           "decode_prune_step": 70600000},
 }
 
 
