@@ -180,19 +180,21 @@ vatp_status prefill_score_impl(vatp_ctx *ctx, const vatp_params *p, const void *
     const size_t units = static_cast<size_t>(p->batch) * p->n_heads;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     float *lse2 = static_cast<float *>(ws);
-    if (launch_l1norm(p->dtype, p->head_dim, V, nrm, pr.meta, pr.g, stream) != hipSuccess) return VATP_E_DEVICE;
     if (have_lse && launch_lse_to_base2(lse, lse2, pr.meta, pr.g, stream) != hipSuccess) return VATP_E_DEVICE;
     // bf16 with head_dim 128 runs on the matrix cores; everything else, and the history-window scores
     // (a band of w+1 query rows, a fraction of the full pass), on the fp32 FMA kernels
     const bool mfma = p->dtype == VATP_BF16 && p->head_dim == 128;
     hipError_t e;
-    if (mfma && window < 0)
-        e = launch_prefill_mfma(Q, K, S, lse2, have_lse, pr.meta, pr.g, stream);
-    else if (mfma && prefill_mfma_window_fits(window, p->cap))
-        e = launch_prefill_mfma_window(Q, K, S, lse2, lse2 + align_up(units * p->cap * sizeof(float)) / sizeof(float),
-                                       window, hist, pr.meta, pr.g, stream);
-    else
+    if (mfma && window < 0) {                 // (the matrix-core column-sum pass writes the norms as well)
+        e = launch_prefill_mfma(Q, K, V, S, nrm, lse2, have_lse, pr.meta, pr.g, stream);
+    } else if (mfma && prefill_mfma_window_fits(window, p->cap)) {
+        e = launch_prefill_mfma_window(Q, K, V, S, nrm, lse2,
+                                       lse2 + align_up(units * p->cap * sizeof(float)) / sizeof(float), window, hist,
+                                       pr.meta, pr.g, stream);
+    } else {
+        if (launch_l1norm(p->dtype, p->head_dim, V, nrm, pr.meta, pr.g, stream) != hipSuccess) return VATP_E_DEVICE;
         e = launch_prefill_generic(p->dtype, p->head_dim, Q, K, S, lse2, have_lse, window, hist, pr.meta, pr.g, stream);
+    }
     if (e != hipSuccess) return VATP_E_DEVICE;
     return VATP_OK;
 }

@@ -188,13 +188,42 @@ struct Epilogue {
     }
 };
 
+// Norms of 64 consecutive value rows by one wavefront.  Same arithmetic as l1norm_kernel: 16 lanes per
+// row, 8 elements each in order, then a butterfly over the 16 lanes; all 16 loads of a lane are issued
+// before the first is used.
+template <int kNorm>
+__device__ __forceinline__ void value_norms_64(const uint4 *__restrict__ Vu, float *__restrict__ nu, int row0, int len,
+                                               int lane)
+{
+    const int sub = lane & 15, rr = lane >> 4;
+    uint4 raw[16];
+#pragma unroll
+    for (int p = 0; p < 16; ++p) {
+        const int row = row0 + 4 * p + rr;
+        raw[p] = row < len ? Vu[static_cast<size_t>(row) * kChunksPerRow + sub] : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int p = 0; p < 16; ++p) {
+        const int row = row0 + 4 * p + rr;
+        float x[8], acc = 0.f;
+        Elt<bf16_t>::unpack(raw[p], x);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc = norm_accum(kNorm, acc, x[e]);
+#pragma unroll
+        for (int off = 8; off > 0; off >>= 1) acc = norm_combine(kNorm, acc, __shfl_xor(acc, off));
+        if (sub == 0 && row < len) nu[row] = norm_finish(kNorm, acc);
+    }
+}
+
 template <bool kColsum, int kHalves, bool kWindow = false>
 __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_t *__restrict__ Q,
                                                            const bf16_t *__restrict__ K,
                                                            float *__restrict__ lse2,
                                                            float *__restrict__ S, BatchMeta meta,
                                                            int n_heads, int n_units, int cap,
-                                                           int n_blocks, float scale_log2, WindowPass win)
+                                                           int n_blocks, float scale_log2, WindowPass win,
+                                                           const bf16_t *__restrict__ V, float *__restrict__ nrm,
+                                                           int norm)
 {
     static_assert(!kWindow || kHalves == 1, "the windowed passes use 4-wavefront workgroups");
     constexpr bool kSplitKeys = kWindow && !kColsum;      // windowed row statistics: one (block, key range) per workgroup
@@ -283,6 +312,21 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
 #pragma unroll
         for (int k = 0; k < kAhead; ++k)
             if (t_begin + k <= t_end) copy_stage(t_begin + k, k);
+
+        // The column-sum pass visits every block of keys once: it also leaves the norm of the value rows
+        // of its block (paper Eq. 4), 64 rows per wavefront, while the first stages are on their way.
+        if constexpr (kColsum) {
+            if (V != nullptr && half == 0) {
+                const uint4 *Vu = reinterpret_cast<const uint4 *>(V + unit * cap * kD);
+                float *nu = nrm + unit * cap;
+                switch (norm) {
+                case VATP_NORM_L1: value_norms_64<VATP_NORM_L1>(Vu, nu, w0, len, lane); break;
+                case VATP_NORM_L2: value_norms_64<VATP_NORM_L2>(Vu, nu, w0, len, lane); break;
+                case VATP_NORM_LINF: value_norms_64<VATP_NORM_LINF>(Vu, nu, w0, len, lane); break;
+                default: value_norms_64<VATP_NORM_NONE>(Vu, nu, w0, len, lane); break;
+                }
+            }
+        }
 
         // stationary operand: 2 column blocks x 8 MFMA steps, 8 bf16 per lane each
         bf16x8 Bf[2][8];
@@ -516,15 +560,16 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
 }  // namespace
 
 template <int kHalves>
-static void launch_both(const bf16_t *Q, const bf16_t *K, float *S, float *lse2, bool have_lse, const BatchMeta &meta,
-                        const Geometry &g, int n_units, int n_blocks, dim3 grid, hipStream_t st)
+static void launch_both(const bf16_t *Q, const bf16_t *K, const bf16_t *V, float *S, float *nrm, float *lse2,
+                        bool have_lse, const BatchMeta &meta, const Geometry &g, int n_units, int n_blocks, dim3 grid,
+                        hipStream_t st)
 {
     const dim3 block(256 * kHalves);
     if (!have_lse)      // row statistics are computed here unless the caller supplied them
         hipLaunchKernelGGL((prefill_mfma_kernel<false, kHalves>), grid, block, 0, st, Q, K, lse2, S, meta, g.n_heads,
-                           n_units, g.cap, n_blocks, g.scale_log2, WindowPass{});
+                           n_units, g.cap, n_blocks, g.scale_log2, WindowPass{}, nullptr, nullptr, 0);
     hipLaunchKernelGGL((prefill_mfma_kernel<true, kHalves>), grid, block, 0, st, Q, K, lse2, S, meta, g.n_heads,
-                       n_units, g.cap, n_blocks, g.scale_log2, WindowPass{});
+                       n_units, g.cap, n_blocks, g.scale_log2, WindowPass{}, V, nrm, g.norm);
 }
 
 namespace {
@@ -567,8 +612,9 @@ bool prefill_mfma_window_fits(int window, int cap)
     return (static_cast<double>(window) + 1 + kBlockCols) * cap * 4.0 < 2147483648.0;
 }
 
-hipError_t launch_prefill_mfma_window(const void *Q, const void *K, float *S, float *lse2, float *lse_part, int window,
-                                      float *hist, const BatchMeta &meta, const Geometry &g, hipStream_t st)
+hipError_t launch_prefill_mfma_window(const void *Q, const void *K, const void *V, float *S, float *nrm, float *lse2,
+                                      float *lse_part, int window, float *hist, const BatchMeta &meta,
+                                      const Geometry &g, hipStream_t st)
 {
     if (g.max_len <= 0) return hipSuccess;
     const int n_blocks = (g.max_len + kBlockCols - 1) / kBlockCols;
@@ -584,17 +630,18 @@ hipError_t launch_prefill_mfma_window(const void *Q, const void *K, float *S, fl
     const int window_blocks = (window + 1 + kBlockCols - 1) / kBlockCols + 1;     // blocks a window can straddle
     win.n_qb = window_blocks < n_blocks ? window_blocks : n_blocks;
     hipLaunchKernelGGL((prefill_mfma_kernel<false, 1, true>), dim3(8u * win.n_qb * win.n_splits * unit_groups), dim3(256),
-                       0, st, q, k, lse2, S, meta, g.n_heads, n_units, g.cap, n_blocks, g.scale_log2, win);
+                       0, st, q, k, lse2, S, meta, g.n_heads, n_units, g.cap, n_blocks, g.scale_log2, win, nullptr, nullptr, 0);
     const int merge_rows = window + 1 + kStage;
     hipLaunchKernelGGL(merge_split_lse_kernel, dim3((merge_rows + 255) / 256, n_units), dim3(256), 0, st, lse_part, lse2,
                        meta, g.n_heads, n_units, g.cap, window, win.n_splits);
     hipLaunchKernelGGL((prefill_mfma_kernel<true, 1, true>), dim3(8u * ((n_blocks + 1) / 2) * unit_groups), dim3(256), 0,
-                       st, q, k, lse2, S, meta, g.n_heads, n_units, g.cap, n_blocks, g.scale_log2, win);
+                       st, q, k, lse2, S, meta, g.n_heads, n_units, g.cap, n_blocks, g.scale_log2, win,
+                       static_cast<const bf16_t *>(V), nrm, g.norm);
     return hipGetLastError();
 }
 
-hipError_t launch_prefill_mfma(const void *Q, const void *K, float *S, float *lse2, bool have_lse,
-                               const BatchMeta &meta, const Geometry &g, hipStream_t st)
+hipError_t launch_prefill_mfma(const void *Q, const void *K, const void *V, float *S, float *nrm, float *lse2,
+                               bool have_lse, const BatchMeta &meta, const Geometry &g, hipStream_t st)
 {
     if (g.max_len <= 0) return hipSuccess;
     const int n_blocks = (g.max_len + kBlockCols - 1) / kBlockCols;
@@ -602,11 +649,12 @@ hipError_t launch_prefill_mfma(const void *Q, const void *K, float *S, float *ls
     const int n_pairs = (n_blocks + 1) / 2;
     const unsigned n_wg = 8u * n_pairs * ((n_units + 7) / 8);
     const bf16_t *q = static_cast<const bf16_t *>(Q), *k = static_cast<const bf16_t *>(K);
+    const bf16_t *v = static_cast<const bf16_t *>(V);
     // Two wavefronts per SIMD either way: two 4-wavefront workgroups per compute unit when
     // the grid is large enough to keep pairs of them resident, else 8-wavefront workgroups.
     const int halves = n_wg >= 2u * kComputeUnits ? 1 : 2;
-    if (halves == 2) launch_both<2>(q, k, S, lse2, have_lse, meta, g, n_units, n_blocks, dim3(n_wg), st);
-    else launch_both<1>(q, k, S, lse2, have_lse, meta, g, n_units, n_blocks, dim3(n_wg), st);
+    if (halves == 2) launch_both<2>(q, k, v, S, nrm, lse2, have_lse, meta, g, n_units, n_blocks, dim3(n_wg), st);
+    else launch_both<1>(q, k, v, S, nrm, lse2, have_lse, meta, g, n_units, n_blocks, dim3(n_wg), st);
     return hipGetLastError();
 }
 

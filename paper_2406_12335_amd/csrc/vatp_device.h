@@ -130,15 +130,17 @@ hipError_t launch_prefill_generic(int dtype, int head_dim, const void *Q, const 
 hipError_t launch_lse_to_base2(const float *lse, float *lse2, const BatchMeta &meta, const Geometry &g,
                                hipStream_t st);
 
-hipError_t launch_prefill_mfma(const void *Q, const void *K, float *S, float *lse2, bool have_lse,
-                               const BatchMeta &meta, const Geometry &g, hipStream_t st);
+// (the matrix-core passes also write the value-row norms: no separate launch_l1norm)
+hipError_t launch_prefill_mfma(const void *Q, const void *K, const void *V, float *S, float *nrm, float *lse2,
+                               bool have_lse, const BatchMeta &meta, const Geometry &g, hipStream_t st);
 
 // history-window prompt scores on the matrix cores (bf16, head_dim 128); lse_part: workspace of
 // prefill_window_splits(cap) * units * cap floats; usable if prefill_mfma_window_fits(window, cap)
 int prefill_window_splits(int cap);
 bool prefill_mfma_window_fits(int window, int cap);
-hipError_t launch_prefill_mfma_window(const void *Q, const void *K, float *S, float *lse2, float *lse_part, int window,
-                                      float *hist, const BatchMeta &meta, const Geometry &g, hipStream_t st);
+hipError_t launch_prefill_mfma_window(const void *Q, const void *K, const void *V, float *S, float *nrm, float *lse2,
+                                      float *lse_part, int window, float *hist, const BatchMeta &meta,
+                                      const Geometry &g, hipStream_t st);
 
 hipError_t launch_decode(int dtype, int head_dim, const void *q, const void *k, const void *v,
                          void *K, void *V, float *S, float *nrm, int32_t *pos,
