@@ -208,3 +208,38 @@ def test_windowed_prompt_scores_and_attention_rows(gpu_device, dtype, d, lens, w
                 j = j0 + r
                 parity.assert_scores_close(hist[b, h, r, :j + 1], P_or[r, :j + 1], rtol,
                                            "attention row of query %d unit (%d,%d)" % (j, b, h), atol=1e-35)
+
+
+# ---------------------------------------------------------------- full sizes, in the launch shapes bench.py times
+
+@pytest.mark.parametrize("name,units,steps,window", [
+    ("llama7b_layer", [(0, 0), (0, 13), (0, 31)], 48, None),          # two launches, 16 workgroups per head
+    ("llama7b_stack", [(0, 0), (3, 17), (7, 31)], 48, None),          # 256 heads x 820 rows: one launch
+    ("ragged16", None, 24, None),                                     # 512 heads of unequal length
+    ("llama7b_layer", [(0, 2), (0, 30)], 24, 400),                    # history window, both key ranges of the prompt pass
+    ("llama7b_stack", [(1, 5), (6, 20)], 16, 400),
+])
+def test_fused_route_full_size(gpu_device, name, units, steps, window):
+    cfg = vs.CONFIGS[name]
+    inp = vs.make_inputs(cfg, seed=0, layer=3 if name == "llama7b_stack" else 0, device=gpu_device)
+    if units is None:
+        order = np.argsort(inp.lens)
+        units = [(int(order[0]), 3), (int(order[-1]), 30), (int(order[8]), 12)]
+    _say("fused route full size %s units=%s steps=%d window=%s" % (name, units, steps, window))
+    # with a window the oracle's prompt pass is only the band of w+1 rows, so it is checked in full;
+    # without one the trajectory continues from the GPU's prompt scores (checked by the other full-size tests)
+    rep = parity.run_trajectory(inp, gpu_device, units=units, steps=steps, fused=True, window=window,
+                                full_prefill_check=False, check_every=4)
+    _say("report %r" % rep)
+    assert rep.prune_events == len(units) * (steps + 1)
+
+
+def test_long32k_full_size_history_window(gpu_device):
+    """Prompt of 32768 with w = 400: 16 key ranges in the row-statistics pass; all heads' scores total w+1."""
+    cfg = vs.CONFIGS["long32k"]
+    inp = vs.make_inputs(cfg, seed=0, device=gpu_device)
+    w = 400
+    _say("long32k, history window %d" % w)
+    rep = parity.run_trajectory(inp, gpu_device, units=[(0, 1), (0, 26)], steps=12, fused=True, window=w,
+                                full_prefill_check=False, check_every=3)
+    _say("report %r" % rep)
