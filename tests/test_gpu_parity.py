@@ -148,6 +148,36 @@ def _prompt_scores_gpu(inp, device):
         cache.close()
 
 
+@pytest.mark.parametrize("jump", [40.0, 90.0, 150.0, 230.0])
+def test_prompt_scores_with_a_late_dominant_key(gpu_device, jump):
+    """One key far into the prompt whose logits tower over everything before it, by `jump` in the base-2
+    domain: the running maximum of the row statistics has to follow it (150 and 230 exceed what fp32 could
+    hold relative to the first keys' maximum), and the scores must still match the oracle."""
+    d, L, H = 128, 700, 2
+    g = torch.Generator().manual_seed(int(jump))
+    u = torch.nn.functional.normalize(torch.randn(H, 1, d, generator=g), dim=-1)
+    Q = (torch.randn(1, H, L, d, generator=g) + 10.0 * u).to(torch.bfloat16)
+    K = torch.randn(1, H, L, d, generator=g)
+    # <q, k*> ~ 10 |k*| for every query, so the logit is about jump when |k*| = jump * sqrt(d) / (10 log2 e)
+    K[0, :, 100] = (jump * d ** 0.5 / (10.0 * 1.4427)) * u[:, 0]
+    K = K.to(torch.bfloat16)
+    V = torch.randn(1, H, L, d, generator=g).to(torch.bfloat16)
+    _say("late dominant key, jump %.0f" % jump)
+    cache = PrunedKVCache(1, H, d, torch.bfloat16, 2, 8, [L // 2], gpu_device)
+    try:
+        cache.prefill_score(Q.to(gpu_device), K.to(gpu_device), V.to(gpu_device), [L])
+        torch.cuda.synchronize()
+        S = cache.S_prompt.cpu().double().numpy()
+    finally:
+        cache.close()
+    for h in range(H):
+        want = orc.prefill_scores(Q[0, h].double().numpy(), K[0, h].double().numpy())
+        assert np.all(np.isfinite(S[0, h]))
+        # scores below 1e-30 belong to keys that every later query ignores next to the dominant one
+        parity.assert_scores_close(S[0, h], want, 1e-3, "late dominant key, head %d" % h, atol=1e-30)
+        assert abs(S[0, h].sum() - L) < 1e-3 * L
+
+
 # ------------------------------------------------------------------ selection in isolation
 
 @pytest.mark.parametrize("n,B,F,R,seed", [
