@@ -186,7 +186,7 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
 // exactly as decode_logits_kernel forms them (128-row chunks, the same butterflies), so the
 // result has the same bits as the two-launch route.
 constexpr int kOneThreads = 1024;
-constexpr int kOneMaxRows = 8192;                          // logits kept in LDS (32 KiB)
+constexpr int kOneMaxRows = 2048;                          // logits, old scores and norms kept in LDS (24 KiB)
 
 template <typename T, int D>
 __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
@@ -200,10 +200,13 @@ __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
     constexpr int kE = Elt<T>::kPer16B;
     constexpr int kLanesPerRow = D / kE;
     constexpr int kRowsPerPass = kOneThreads / kLanesPerRow;
-    constexpr int kGroup = 8;                              // row loads in flight per thread
+    constexpr int kGroup = 16;                             // row loads in flight per thread: 1024 rows per round trip
     constexpr int kWaves = kOneThreads / 64;
+    constexpr int kPre = kOneMaxRows / kOneThreads;        // rows of S and nrm a thread brings in
 
     __shared__ float s_logit[kOneMaxRows];
+    __shared__ float s_score[kOneMaxRows];                 // old scores (0 for the appended row)
+    __shared__ float s_norm[kOneMaxRows];
     __shared__ float2 s_part[kOneMaxRows / kDecodeChunk];
     __shared__ float s_wave[kWaves];
     __shared__ float s_new_norm;
@@ -222,28 +225,23 @@ __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
     const uint4 *knew = reinterpret_cast<const uint4 *>(k_new + unit * D);
     const int synced = synced_in[unit];
 
-    float qf[kE];
-    Elt<T>::unpack(reinterpret_cast<const uint4 *>(q + unit * D)[sub], qf);
-
-    // append the new row: k, v, |v|, pos
+    // Every load this phase needs is requested before the first result is used: the query, the new row,
+    // the old scores and norms (parked in LDS after the sweep, so that the later phases do not start with a
+    // round trip to memory of their own), then the first 16 K rows of every thread.
+    const uint4 q_raw = reinterpret_cast<const uint4 *>(q + unit * D)[sub];
+    uint4 k_raw = make_uint4(0, 0, 0, 0), v_raw = make_uint4(0, 0, 0, 0);
     if (tid < kLanesPerRow) {
-        const uint4 kraw = knew[sub];
-        const uint4 vraw = reinterpret_cast<const uint4 *>(v_new + unit * D)[sub];
-        reinterpret_cast<uint4 *>(K + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = kraw;
-        reinterpret_cast<uint4 *>(V + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = vraw;
-        float vf[kE], a = 0.f;
-        Elt<T>::unpack(vraw, vf);
-#pragma unroll
-        for (int e = 0; e < kE; ++e) a = norm_accum(norm, a, vf[e]);
-#pragma unroll
-        for (int off = kLanesPerRow / 2; off > 0; off >>= 1) a = norm_combine(norm, a, __shfl_xor(a, off));
-        if (sub == 0) {
-            const float new_norm = norm_finish(norm, a);
-            s_new_norm = new_norm;
-            Nu[n0] = new_norm;
-            if (pos) pos[unit * cap + n0] = len_pos.aux[b];
-        }
+        k_raw = knew[sub];
+        v_raw = reinterpret_cast<const uint4 *>(v_new + unit * D)[sub];
     }
+    float pre_s[kPre], pre_w[kPre];
+#pragma unroll
+    for (int u = 0; u < kPre; ++u) {
+        const int r = tid + u * kOneThreads;
+        pre_s[u] = r < n0 ? Su[r] : 0.f;
+        pre_w[u] = r < n0 ? Nu[r] : 0.f;
+    }
+    float qf[kE];
 
     // logits of all rows into LDS; the new row is read from the step's input, not from the cache
     for (int r0 = 0; r0 < n; r0 += kGroup * kRowsPerPass) {
@@ -253,6 +251,26 @@ __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
             const int r = r0 + u * kRowsPerPass + rloc;
             const uint4 *src = (r == n0) ? knew + sub : Ku + static_cast<size_t>(r) * kLanesPerRow + sub;
             raw[u] = (r < n) ? *src : make_uint4(0, 0, 0, 0);
+        }
+        if (r0 == 0) {
+            Elt<T>::unpack(q_raw, qf);
+            // append the new row: k, v, |v|, pos
+            if (tid < kLanesPerRow) {
+                reinterpret_cast<uint4 *>(K + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = k_raw;
+                reinterpret_cast<uint4 *>(V + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = v_raw;
+                float vf[kE], a = 0.f;
+                Elt<T>::unpack(v_raw, vf);
+#pragma unroll
+                for (int e = 0; e < kE; ++e) a = norm_accum(norm, a, vf[e]);
+#pragma unroll
+                for (int off = kLanesPerRow / 2; off > 0; off >>= 1) a = norm_combine(norm, a, __shfl_xor(a, off));
+                if (sub == 0) {
+                    const float new_norm = norm_finish(norm, a);
+                    s_new_norm = new_norm;
+                    Nu[n0] = new_norm;
+                    if (pos) pos[unit * cap + n0] = len_pos.aux[b];
+                }
+            }
         }
 #pragma unroll
         for (int u = 0; u < kGroup; ++u) {
@@ -266,7 +284,13 @@ __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
             if (sub == 0 && r < n) s_logit[r] = dot * scale_log2;
         }
     }
+#pragma unroll
+    for (int u = 0; u < kPre; ++u) {
+        const int r = tid + u * kOneThreads;
+        if (r < n0) { s_score[r] = pre_s[u]; s_norm[r] = pre_w[u]; }
+    }
     __syncthreads();
+    if (tid == 0) { s_score[n0] = 0.f; s_norm[n0] = s_new_norm; }      // the appended row (published by the syncs below)
 
     // statistics of every 128-row chunk: two wavefronts per chunk, lane = row within the wavefront's 64
     const int n_chunks = (n + kDecodeChunk - 1) / kDecodeChunk;
@@ -293,9 +317,8 @@ __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
     merge_chunk_stats(s_part, n_chunks, M, L);
     const float lse2 = M + log2f(L);
 
-    auto new_score = [&](int r) { return (r != n0 ? Su[r] : 0.f) + exp2f(s_logit[r] - lse2); };
-    // (the norm of the row appended above is taken from LDS, not from this launch's own store)
-    auto row_norm = [&](int r) { return r == n0 ? s_new_norm : Nu[r]; };
+    auto new_score = [&](int r) { return s_score[r] + exp2f(s_logit[r] - lse2); };
+    auto row_norm = [&](int r) { return s_norm[r]; };
 
     // the row that leaves: minimise (importance bits, ~row) over the unprotected rows
     int evicted = n;
@@ -342,7 +365,7 @@ __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
             Ko[static_cast<size_t>(o) * kLanesPerRow + sub] = kr;
             Vo[static_cast<size_t>(o) * kLanesPerRow + sub] = vr;
             if (sub == 0) {
-                nrm_out[unit * cap_out + o] = Nu[src];
+                nrm_out[unit * cap_out + o] = s_norm[src];
                 if (pos_out) pos_out[unit * cap_out + o] = pos[unit * cap + src];
             }
         }

@@ -243,3 +243,58 @@ def test_long32k_full_size_history_window(gpu_device):
     rep = parity.run_trajectory(inp, gpu_device, units=[(0, 1), (0, 26)], steps=12, fused=True, window=w,
                                 full_prefill_check=False, check_every=3)
     _say("report %r" % rep)
+
+
+def test_window_calls_reject_bad_arguments_and_accept_no_history_buffer(gpu_device):
+    dev = gpu_device
+    b, H, d, L, w = 1, 2, 128, 300, 50
+    cfg = vs.scaled(vs.CONFIGS["llama7b_layer"], n_heads=H, prompt_len=L, decode_steps=2, recent=8)
+    inp = vs.make_inputs(cfg, seed=9)
+    Q, K, V = inp.Q.to(dev), inp.K.to(dev), inp.V.to(dev)
+    ctx = vatp.vatp_create(0)
+    try:
+        p = vatp.Params(b, H, d, torch.bfloat16, 2, 8, L, [L], [150])
+        ws = torch.empty(vatp.vatp_workspace_bytes(ctx, p, vatp.CALL_PREFILL_SCORE_WINDOW), dtype=torch.uint8, device=dev)
+        S0, S1 = torch.empty(b, H, L, device=dev), torch.empty(b, H, L, device=dev)
+        nrm = torch.empty(b, H, L, device=dev)
+        hist = torch.empty(b, H, w + 1, L, device=dev)
+        vatp.vatp_prefill_score_window(ctx, p, Q, K, V, w, S0, nrm, hist, ws)
+        vatp.vatp_prefill_score_window(ctx, p, Q, K, V, w, S1, nrm, None, ws)      # scores only
+        torch.cuda.synchronize()
+        assert torch.equal(S0, S1)
+        with pytest.raises(vatp.VatpError) as e:                                   # workspace of the plain call is too small
+            small = torch.empty(vatp.vatp_workspace_bytes(ctx, p, vatp.CALL_PREFILL_SCORE), dtype=torch.uint8, device=dev)
+            vatp.vatp_prefill_score_window(ctx, p, Q, K, V, w, S0, nrm, hist, small)
+        assert e.value.status == vatp.binding.E_WORKSPACE
+        with pytest.raises(vatp.VatpError) as e:
+            vatp.vatp_prefill_score_window(ctx, p, Q, K, V, -3, S0, nrm, hist, ws)
+        assert e.value.status == vatp.binding.E_SHAPE
+    finally:
+        vatp.vatp_destroy(ctx)
+    c = PrunedKVCache(b, H, d, torch.bfloat16, 2, 8, [150], dev, window=w)
+    try:
+        c.prefill_score(Q, K, V, [L])
+        c.prune_prompt(K, V)
+        x = torch.zeros(b, H, d, dtype=torch.bfloat16, device=dev)
+        good_hist, good_free = c.hist, c.free
+        c.cap_hist = 100                                                            # fewer columns than budget + 1
+        with pytest.raises(vatp.VatpError) as e:
+            c.decode_prune_step(x, x, x, [L])
+        assert e.value.status == vatp.binding.E_BUDGET
+        c.cap_hist = c.cap
+        c.free = [good_free[0], good_free[0]]                                       # the two count arrays must differ
+        with pytest.raises(vatp.VatpError) as e:
+            c.decode_prune_step(x, x, x, [L])
+        assert e.value.status == vatp.binding.E_SHAPE
+        c.free = good_free
+        with pytest.raises(vatp.VatpError) as e:                                    # the step index is required
+            vatp.vatp_decode_prune_step_window(c.ctx, c._p_dec, x, x, x, c.K[0], c.V[0], c.S[0], c.nrm[0], c.pos[0], c.hid[0],
+                                               None, c.K[1], c.V[1], c.S[1], c.nrm[1], c.pos[1], c.hid[1], None,
+                                               c.synced[0], c.synced[1], c.free[0], c.free[1], good_hist, w, c.cap_hist,
+                                               None, c.ws)
+        assert e.value.status == vatp.binding.E_NULL
+        c.decode_prune_step(x, x, x, [L])                                           # and the good call still works
+        torch.cuda.synchronize()
+        assert c.lens == [150]
+    finally:
+        c.close()
