@@ -165,8 +165,9 @@ __global__ __launch_bounds__(256) void decode_finish_kernel(float *__restrict__ 
     const size_t unit = blockIdx.x;
     const int b = static_cast<int>(unit / n_heads);
     const int n0 = meta.len[b], n = n0 + 1;
-    const int r = blockIdx.y * 256 + threadIdx.x;                // one row per thread
-    if (blockIdx.y * 256 >= n) return;
+    const int row0 = static_cast<int>(blockIdx.y) * 256;
+    const int r = row0 + static_cast<int>(threadIdx.x);          // one row per thread
+    if (row0 >= n) return;
     float logit = 0.f, s_old = 0.f;
     if (r < n) {
         logit = ws_logit[unit * cap + r];
@@ -180,7 +181,7 @@ __global__ __launch_bounds__(256) void decode_finish_kernel(float *__restrict__ 
     const float lse2 = M + log2f(L);
     if (r < n) S[unit * cap + r] = s_old + exp2f(logit - lse2);
     // attention output of the new token: the chunks' partial sums, rescaled to the common maximum
-    if (out && blockIdx.y == 0 && threadIdx.x < head_dim)
+    if (out && blockIdx.y == 0 && static_cast<int>(threadIdx.x) < head_dim)
         out[unit * head_dim + threadIdx.x] = merge_chunk_outputs(ws_out + unit * chunks_alloc * head_dim, part, n_chunks,
                                                                  head_dim, threadIdx.x, M, L);
 }
