@@ -323,9 +323,9 @@ def run(args):
 # (FETCH_SIZE x2.000, WRITE_SIZE x1.000); summaries under profiles/.  Keyed by (workload, layers).
 MEASURED_TRAFFIC_BYTES = {
     # calibrated fetch + write bytes per call of the entry point (all of its kernels)
-    ("llama7b_layer", 1): {"prefill_score": 173490899, "decode_step": 18041612, "select_compact": 72839834,
-                           "decode_prune_step": 21023376},
-    ("llama7b_stack", 2): {"prefill_score": 1891836631, "decode_step": 57720561, "select_compact": 233090131,
+    ("llama7b_layer", 1): {"prefill_score": 185507511, "decode_step": 18051834, "select_compact": 72839821,
+                           "decode_prune_step": 21023422},
+    ("llama7b_stack", 2): {"prefill_score": 2075447204, "decode_step": 57730736, "select_compact": 233079038,
                            "decode_prune_step": 70600000},
 }
 
