@@ -51,27 +51,16 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(
     const int sub = tid % kLanesPerRow;
     const int rloc = tid / kLanesPerRow;
 
-    // this lane's slice of the query, widened once
-    float qf[kE];
-    Elt<T>::unpack(reinterpret_cast<const uint4 *>(q + unit * D)[sub], qf);
-
-    // the workgroup that owns the new row stores k, v, |v|_1 and pos into the caches
-    if (n0 >= row0 && n0 < row0 + kDecodeChunk && tid < kLanesPerRow) {
-        const uint4 kraw = knew[sub];
-        const uint4 vraw = reinterpret_cast<const uint4 *>(v_new + unit * D)[sub];
-        reinterpret_cast<uint4 *>(K + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = kraw;
-        reinterpret_cast<uint4 *>(V + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = vraw;
-        float vf[kE], a = 0.f;
-        Elt<T>::unpack(vraw, vf);
-#pragma unroll
-        for (int e = 0; e < kE; ++e) a = norm_accum(norm, a, vf[e]);
-#pragma unroll
-        for (int off = kLanesPerRow / 2; off > 0; off >>= 1) a = norm_combine(norm, a, __shfl_xor(a, off));
-        if (sub == 0) {
-            nrm[unit * cap + n0] = norm_finish(norm, a);
-            if (pos) pos[unit * cap + n0] = meta.aux[b];
-        }
+    // Every load of this phase is requested before the first result is used: the query, the new row (in the
+    // workgroup that owns it), then all of the workgroup's K rows.
+    const uint4 q_raw = reinterpret_cast<const uint4 *>(q + unit * D)[sub];
+    const bool owns_new_row = n0 >= row0 && n0 < row0 + kDecodeChunk && tid < kLanesPerRow;
+    uint4 kraw = make_uint4(0, 0, 0, 0), vraw = make_uint4(0, 0, 0, 0);
+    if (owns_new_row) {
+        kraw = knew[sub];
+        vraw = reinterpret_cast<const uint4 *>(v_new + unit * D)[sub];
     }
+    float qf[kE];
 
     // logits of the chunk's rows; the new row is read from the step's input, not from the cache
 #pragma unroll
@@ -82,6 +71,24 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(
             const int r = row0 + (p0 + u) * kRowsPerPass + rloc;
             const uint4 *src = (r == n0) ? knew + sub : Ku + static_cast<size_t>(r) * kLanesPerRow + sub;
             raw[u] = (r < n) ? *src : make_uint4(0, 0, 0, 0);
+        }
+        if (p0 == 0) {
+            Elt<T>::unpack(q_raw, qf);         // this lane's slice of the query, widened once
+            // the workgroup that owns the new row stores k, v, |v| and pos into the caches
+            if (owns_new_row) {
+                reinterpret_cast<uint4 *>(K + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = kraw;
+                reinterpret_cast<uint4 *>(V + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = vraw;
+                float vf[kE], a = 0.f;
+                Elt<T>::unpack(vraw, vf);
+#pragma unroll
+                for (int e = 0; e < kE; ++e) a = norm_accum(norm, a, vf[e]);
+#pragma unroll
+                for (int off = kLanesPerRow / 2; off > 0; off >>= 1) a = norm_combine(norm, a, __shfl_xor(a, off));
+                if (sub == 0) {
+                    nrm[unit * cap + n0] = norm_finish(norm, a);
+                    if (pos) pos[unit * cap + n0] = meta.aux[b];
+                }
+            }
         }
 #pragma unroll
         for (int u = 0; u < kGroup; ++u) {
