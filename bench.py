@@ -263,6 +263,10 @@ def run(args):
                   "frac": round(fused_gbps / HBM_PEAK_GBPS, 5), "traffic": traffic.get("decode_prune_step"),
                   "avg_launch_ms": round(fused_call_ms, 5),
                   "host_enqueue_us_per_call": round(host_us_per_call, 2),
+                  # for orientation only, not used in `achieved`: the bytes the out-of-place route moves for the
+                  # same step (K read, S read + written, whole cache copied), over this route's time
+                  "out_of_place_equivalent_GBps": round((dec_bytes + sel_bytes) / n_calls / (fused_call_ms * 1e-3) / 1e9, 2)
+                  if T and fused_call_ms > 0 and window is None else None,
                   "rows_moved_per_head_step": round(fused_rows_moved / max(1, n_calls * cfg.batch * cfg.n_heads), 2)}
     dec_k_gbps = dec_call_bytes / (dec_call_ms * 1e-3) / 1e9 if T and dec_call_ms > 0 else 0.0
     sel_k_gbps = sel_call_bytes / (sel_call_ms * 1e-3) / 1e9 if T and sel_call_ms > 0 else 0.0
