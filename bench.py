@@ -82,6 +82,9 @@ def run(args):
         cfg = vs.scaled(cfg, layers=args.layers)
     if args.decode_steps is not None:
         cfg = vs.scaled(cfg, decode_steps=args.decode_steps)
+    for field, value in (("batch", args.batch), ("budget_pct", args.budget_pct), ("recent", args.recent)):
+        if value is not None:
+            cfg = vs.scaled(cfg, **{field: value})
     T = cfg.decode_steps
     fused = args.decode_route == "fused"
     window = args.window
@@ -393,6 +396,9 @@ def main():
     ap.add_argument("--workload", default="llama7b_layer", choices=sorted(vs.CONFIGS))
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers of the workload")
     ap.add_argument("--decode-steps", type=int, default=None)
+    ap.add_argument("--batch", type=int, default=None, help="override the batch size of the workload")
+    ap.add_argument("--budget-pct", type=int, default=None, help="override the KV budget (percent of the prompt)")
+    ap.add_argument("--recent", type=int, default=None, help="override the recent window R")
     ap.add_argument("--decode-route", default="fused", choices=["fused", "separate"],
                     help="fused: vatp_decode_prune_step; separate: vatp_decode_step + vatp_select_compact")
     ap.add_argument("--window", type=int, default=None,
