@@ -112,7 +112,24 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
             const int r = lo + tid + u * kThreads;
             if (r < hi) consider(r, combine(s_r[u], exp2f(t_r[u] - lse2), x_r[u]), w_r[u]);
         }
-        for (int r = lo + tid + kScan * kThreads; r < hi; r += kThreads) consider(r, new_score(r), Nu[r]);
+        // further rows, four per thread at a time: loads first, then the arithmetic
+        for (int r0 = lo + tid + kScan * kThreads; r0 < hi; r0 += kScan * kThreads) {
+            float t4[kScan], s4[kScan], w4[kScan], x4[kScan];
+#pragma unroll
+            for (int u = 0; u < kScan; ++u) {
+                const int r = r0 + u * kThreads;
+                const bool ok = r < hi;
+                t4[u] = ok ? Lu[r] : 0.f;
+                s4[u] = ok && r != n0 ? Su[r] : 0.f;
+                w4[u] = ok ? Nu[r] : 0.f;
+                x4[u] = ok ? leaving(r) : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < kScan; ++u) {
+                const int r = r0 + u * kThreads;
+                if (r < hi) consider(r, combine(s4[u], exp2f(t4[u] - lse2), x4[u]), w4[u]);
+            }
+        }
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) {
             const unsigned long long o = __shfl_xor(best, off);
@@ -130,11 +147,28 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
     {
         const int share = (n_keep + G - 1) / G;
         const int o_end = min(n_keep, (g + 1) * share);
-        for (int o = g * share + tid; o < o_end; o += kThreads) {
-            const int src = o + (o >= evicted ? 1 : 0);
-            S_out[unit * cap_out + o] = new_score(src);
-            if (kept_idx) kept_idx[unit * cap_out + o] = src;
-            if (windowed) h_write[column(src)] = exp2f(Lu[src] - lse2);
+        for (int o0 = g * share + tid; o0 < o_end; o0 += kScan * kThreads) {
+            float t4[kScan], s4[kScan], x4[kScan];
+            int c4[kScan];
+#pragma unroll
+            for (int u = 0; u < kScan; ++u) {           // loads first, then the arithmetic and the stores
+                const int o = o0 + u * kThreads;
+                const int src = o + (o >= evicted ? 1 : 0);
+                const bool ok = o < o_end;
+                t4[u] = ok ? Lu[src] : 0.f;
+                s4[u] = ok && src != n0 ? Su[src] : 0.f;
+                x4[u] = ok ? leaving(src) : 0.f;
+                c4[u] = ok && windowed ? column(src) : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < kScan; ++u) {
+                const int o = o0 + u * kThreads;
+                if (o >= o_end) continue;
+                const float p = exp2f(t4[u] - lse2);
+                S_out[unit * cap_out + o] = combine(s4[u], p, x4[u]);
+                if (kept_idx) kept_idx[unit * cap_out + o] = o + (o >= evicted ? 1 : 0);
+                if (windowed) h_write[c4[u]] = p;
+            }
         }
     }
     if (windowed && g == 0) {
