@@ -187,7 +187,7 @@ vatp_status prefill_score_impl(vatp_ctx *ctx, const vatp_params *p, const void *
     hipError_t e;
     if (mfma && window < 0) {                 // (the matrix-core column-sum pass writes the norms as well)
         e = launch_prefill_mfma(Q, K, V, S, nrm, lse2, have_lse, pr.meta, pr.g, stream);
-    } else if (mfma && prefill_mfma_window_fits(window, p->cap)) {
+    } else if (mfma && prefill_mfma_window_fits(window, p->cap, static_cast<int>(units))) {
         e = launch_prefill_mfma_window(Q, K, V, S, nrm, lse2,
                                        lse2 + align_up(units * p->cap * sizeof(float)) / sizeof(float), window, hist,
                                        pr.meta, pr.g, stream);

@@ -606,10 +606,15 @@ __global__ __launch_bounds__(256) void merge_split_lse_kernel(const float *__res
 
 int prefill_window_splits(int cap) { return ((cap + kStage - 1) / kStage + kSplitStages - 1) / kSplitStages; }
 
-bool prefill_mfma_window_fits(int window, int cap)
+bool prefill_mfma_window_fits(int window, int cap, int n_units)
 {
-    // byte offsets inside one head's [w + 1, cap] matrix of attention rows are 32-bit
-    return (static_cast<double>(window) + 1 + kBlockCols) * cap * 4.0 < 2147483648.0;
+    // byte offsets inside one head's [w + 1, cap] matrix of attention rows are 32-bit ...
+    if ((static_cast<double>(window) + 1 + kBlockCols) * cap * 4.0 >= 2147483648.0) return false;
+    // ... and so is the number of workgroups of the row-statistics launch
+    const double n_blocks = (cap + kBlockCols - 1) / kBlockCols;
+    const double window_blocks = (window + 1 + kBlockCols - 1) / kBlockCols + 1;
+    const double n_qb = window_blocks < n_blocks ? window_blocks : n_blocks;
+    return 8.0 * n_qb * prefill_window_splits(cap) * ((n_units + 7) / 8) < 2147483648.0;
 }
 
 hipError_t launch_prefill_mfma_window(const void *Q, const void *K, const void *V, float *S, float *nrm, float *lse2,

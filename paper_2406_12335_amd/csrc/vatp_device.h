@@ -135,9 +135,9 @@ hipError_t launch_prefill_mfma(const void *Q, const void *K, const void *V, floa
                                bool have_lse, const BatchMeta &meta, const Geometry &g, hipStream_t st);
 
 // history-window prompt scores on the matrix cores (bf16, head_dim 128); lse_part: workspace of
-// prefill_window_splits(cap) * units * cap floats; usable if prefill_mfma_window_fits(window, cap)
+// prefill_window_splits(cap) * units * cap floats; usable if prefill_mfma_window_fits(window, cap, units)
 int prefill_window_splits(int cap);
-bool prefill_mfma_window_fits(int window, int cap);
+bool prefill_mfma_window_fits(int window, int cap, int n_units);
 hipError_t launch_prefill_mfma_window(const void *Q, const void *K, const void *V, float *S, float *nrm, float *lse2,
                                       float *lse_part, int window, float *hist, const BatchMeta &meta,
                                       const Geometry &g, hipStream_t st);
