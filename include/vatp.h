@@ -45,7 +45,8 @@ typedef enum {
     VATP_E_NULL = -1,        /* a required pointer is NULL                                 */
     VATP_E_SHAPE = -2,       /* batch / heads / head_dim / cap / len / norm out of range   */
     VATP_E_DTYPE = -3,       /* dtype is neither VATP_F32 nor VATP_BF16                    */
-    VATP_E_BUDGET = -4,      /* budget[b] < n_sink + recent, or budget[b] > cap_out        */
+    VATP_E_BUDGET = -4,      /* budget[b] < n_sink + recent, survivors exceed cap_out (or  */
+                             /* cap_hist), or a fused step would have to remove two rows  */
     VATP_E_WORKSPACE = -5,   /* workspace missing, too small or not 256-byte aligned       */
     VATP_E_DEVICE = -6       /* HIP reported an error (no device, launch failure)          */
 } vatp_status;
@@ -69,7 +70,8 @@ typedef struct {
     float   scale;          /* logit scale c; 0 selects 1/sqrt(head_dim)                   */
     const int32_t *len;     /* HOST [batch]: valid rows per sequence, same for all heads   */
     const int32_t *budget;  /* HOST [batch]: B, rows kept per head (F and R included).     */
-                            /*   only vatp_select_compact reads it; may be NULL elsewhere  */
+                            /*   read by the calls that prune (vatp_select_compact*,       */
+                            /*   vatp_decode_prune_step*); may be NULL elsewhere           */
     int32_t norm;           /* value-row norm of Eq. 4: VATP_NORM_L1 (0, the paper's choice), */
                             /*   VATP_NORM_L2 or VATP_NORM_LINF (the ablation of Table 2), or  */
                             /*   VATP_NORM_NONE: nrm = 1, the attention-only baseline (H2O)    */
@@ -83,8 +85,8 @@ const char *vatp_strerror(vatp_status st);
 
 /*
  * Checks `p` for call `which_call` (a VATP_CALL_* value) exactly as that call does before
- * it launches anything; touches no device.  For the two decode calls, len[b] + 1 <= cap
- * is required (room for the appended row).
+ * it launches anything; touches no device.  For the decode calls, len[b] + 1 <= cap is
+ * required (room for the appended row).
  */
 vatp_status vatp_validate(const vatp_params *p, int which_call);
 
