@@ -134,6 +134,21 @@ def run(args):
         torch.cuda.synchronize()
         del src, dst
 
+    # yardstick beside the data-sheet HBM figure: what a plain device-to-device copy reaches here
+    src = torch.empty(128 * 1024 * 1024, dtype=torch.float32, device=dev).normal_()      # 512 MiB
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(10):
+        dst.copy_(src)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 10 * 2 * src.numel() * 4 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del src, dst
+
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()
@@ -311,6 +326,9 @@ def run(args):
         "prefill_pct_mfma_peak": round(100 * roof_prefill["frac"], 3) if mfma else None,
         "decode_prune_GBps": round(decode_gbps, 2),
         "decode_prune_pct_hbm_peak": round(100 * decode_gbps / HBM_PEAK_GBPS, 3),
+        # read + write rate of a plain 512 MiB device copy (torch copy_) on this machine, for comparison with
+        # the 8000 GB/s data-sheet figure the fractions are taken against
+        "measured_copy_GBps": round(copy_gbps, 1),
         "roofline": roofline,
         "roofline_all": roofline_all,
         # the same decode loop through the other route (per-call event times of the replays)
