@@ -148,6 +148,19 @@ def run(args):
     torch.cuda.synchronize()
     copy_gbps = 10 * 2 * src.numel() * 4 / (c0.elapsed_time(c1) * 1e-3) / 1e9
     del src, dst
+    # the vendor library's bf16 GEMM (8192^3, random operands): what the matrix cores sustain here on a plain product
+    ga = torch.randn(8192, 8192, device=dev).to(torch.bfloat16)
+    gb = torch.randn(8192, 8192, device=dev).to(torch.bfloat16)
+    for _ in range(3):
+        gc = torch.matmul(ga, gb)
+    torch.cuda.synchronize()
+    c0.record()
+    for _ in range(5):
+        gc = torch.matmul(ga, gb)
+    c1.record()
+    torch.cuda.synchronize()
+    gemm_tflops = 5 * 2 * 8192 ** 3 / (c0.elapsed_time(c1) * 1e-3) / 1e12
+    del ga, gb, gc
 
     for _ in range(args.warmup):
         one_step()
@@ -329,6 +342,8 @@ def run(args):
         # read + write rate of a plain 512 MiB device copy (torch copy_) on this machine, for comparison with
         # the 8000 GB/s data-sheet figure the fractions are taken against
         "measured_copy_GBps": round(copy_gbps, 1),
+        # rate of the vendor library's 8192^3 bf16 GEMM on this machine, beside the 2500 TFLOP/s data-sheet figure
+        "measured_gemm_TFLOPs": round(gemm_tflops, 1),
         "roofline": roofline,
         "roofline_all": roofline_all,
         # the same decode loop through the other route (per-call event times of the replays)
