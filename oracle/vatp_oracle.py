@@ -188,6 +188,31 @@ def attention_output(q, K, V, c: Optional[float] = None):
     return out, abs_out
 
 
+def prefill_scores_group(Qg, K, c: Optional[float] = None) -> np.ndarray:
+    """Grouped-query attention (Limitations section, paragraph on GQA): the g query heads that share one
+    key/value head each attend on their own (Eq. 1, 2); the token score of the shared head is the mean of
+    their accumulated scores.  Qg: [g, L, d], K: [L, d]."""
+    Qg = _f64(Qg)
+    g = Qg.shape[0]
+    S = np.zeros(Qg.shape[1], dtype=np.float64)
+    for r in range(g):
+        S += prefill_scores(Qg[r], K, c)
+    return S / g
+
+
+def decode_scores_group(qg, K, S, c: Optional[float] = None):
+    """One decode step with g query heads on one key/value head: (S + a, a) with a the mean over the
+    group of the heads' attention weights (each head has its own softmax).  qg: [g, d]."""
+    qg, K = _f64(qg), _f64(K)
+    g, n = qg.shape[0], K.shape[0]
+    a = np.zeros(n, dtype=np.float64)
+    for r in range(g):
+        _, ar = decode_scores(qg[r], K, np.zeros(n), c)
+        a += ar
+    a /= g
+    return _f64(S) + a, a
+
+
 def l1norm(V) -> np.ndarray:
     V = _f64(V)
     n, d = V.shape
@@ -256,9 +281,14 @@ class OracleHead:
     another implementation after an admissible near-tie difference.
     """
 
-    def __init__(self, d: int, c: Optional[float] = None, norm_kind: int = 0, window: Optional[int] = None):
+    def __init__(self, d: int, c: Optional[float] = None, norm_kind: int = 0, window: Optional[int] = None,
+                 group: int = 1):
         self.d = d
         self.norm_kind = norm_kind
+        # group = g > 1: grouped-query attention, g query heads on this key/value head; queries then come as
+        # [g, L, d] (prompt) and [g, d] (decode step) and scores are means over the group
+        self.group = group
+        assert group == 1 or window is None
         # window = w: scores are sums over the last w+1 steps only (Eq. 3); `hist` then holds those
         # steps' attention rows (oldest first, one entry per cached row) and S is their plain sum
         self.window = window
@@ -276,7 +306,9 @@ class OracleHead:
 
     def prefill(self, Q, K, V):
         self.K, self.V = _f64(K).copy(), _f64(V).copy()
-        if self.window is None:
+        if self.group > 1:
+            self.S = prefill_scores_group(Q, self.K, self.c)
+        elif self.window is None:
             self.S = prefill_scores(Q, self.K, self.c)
         else:
             self.S, P = prefill_window(Q, self.K, self.window, self.c)
@@ -305,7 +337,10 @@ class OracleHead:
         new_row = _f64(v)[None, :]
         self.nrm = np.concatenate([self.nrm, l1norm(new_row) if self.norm_kind == 0 else vnorm(new_row, self.norm_kind)])
         self.pos = np.concatenate([self.pos, np.array([new_pos], dtype=np.int64)])
-        self.S, a = decode_scores(q, self.K, self.S, self.c)
+        if self.group > 1:
+            self.S, a = decode_scores_group(q, self.K, self.S, self.c)
+        else:
+            self.S, a = decode_scores(q, self.K, self.S, self.c)
         if self.window is not None:
             # the new row was not there at earlier steps; the oldest step leaves the window
             self.hist = [np.concatenate([row, np.zeros(1)]) for row in self.hist] + [a.copy()]

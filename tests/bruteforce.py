@@ -81,3 +81,43 @@ def replay(Q, K, V, qd, kd, vd, c, B, F, R):
             r["S"] += ei / z
         prune()
     return out
+
+
+def group_mean(rows: Sequence[Sequence[float]]) -> List[float]:
+    """Element-wise mean of g equally long lists."""
+    g = len(rows)
+    return [math.fsum(row[i] for row in rows) / g for i in range(len(rows[0]))]
+
+
+def replay_group(Qg, K, V, qdg, kd, vd, c, B, F, R):
+    """`replay` for grouped-query attention: g query heads (Qg[r] prompt queries, qdg[t][r] the decode
+    query of head r at step t) share the K/V rows; each head has its own softmax, the token score is
+    the mean over the group of what the heads give it (Limitations section, paragraph on GQA)."""
+    g, L = len(Qg), len(K)
+    S = group_mean([accumulated_scores(attention_matrix(Qg[r], K, c)) for r in range(g)])
+    rows = [dict(k=list(K[i]), v=list(V[i]), S=S[i], pos=i) for i in range(L)]
+    out = []
+
+    def prune():
+        nonlocal rows
+        nrm = l1([r["v"] for r in rows])
+        I = [rows[i]["S"] * nrm[i] for i in range(len(rows))]
+        keep = keep_set(I, len(rows), B, F, R)
+        rows = [rows[i] for i in keep]
+        out.append(([r["pos"] for r in rows], [r["S"] for r in rows], keep))
+
+    prune()
+    for t in range(len(qdg)):
+        rows.append(dict(k=list(kd[t]), v=list(vd[t]), S=0.0, pos=L + t))
+        weights = []
+        for r in range(g):
+            q = qdg[t][r]
+            logits = [c * math.fsum(q[x] * row["k"][x] for x in range(len(q))) for row in rows]
+            m = max(logits)
+            e = [math.exp(s - m) for s in logits]
+            z = math.fsum(e)
+            weights.append([ei / z for ei in e])
+        for row, a in zip(rows, group_mean(weights)):
+            row["S"] += a
+        prune()
+    return out

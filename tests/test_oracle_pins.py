@@ -438,3 +438,79 @@ def test_window_head_with_pruning_keeps_history_aligned():
         if t - L + 1 >= w + 1:                      # the prompt's rows have left the window
             for p, s in zip(h.pos, h.S):
                 np.testing.assert_allclose(s, sum(received[int(p)][-(w + 1):]), rtol=1e-12, atol=1e-300)
+
+
+# ---------------------------------------------------------------- grouped-query attention
+
+@pytest.mark.parametrize("g,seed,B,F,R", [(2, 0, 12, 2, 4), (3, 1, 10, 0, 0), (8, 2, 9, 1, 6)])
+def test_group_trajectory_matches_bruteforce_replay(g, seed, B, F, R):
+    rng = np.random.default_rng(300 + seed)
+    L, d, T = 22, 6, 9
+    Qg, K, V = _rand(rng, g, L, d) * 2, _rand(rng, L, d) * 2, _rand(rng, L, d) * np.exp(0.7 * _rand(rng, L, 1))
+    qdg, kd, vd = _rand(rng, T, g, d) * 2, _rand(rng, T, d) * 2, _rand(rng, T, d)
+    c = 1.0 / math.sqrt(d)
+    want = bf.replay_group(Qg.tolist(), K.tolist(), V.tolist(), qdg.tolist(), kd.tolist(), vd.tolist(), c, B, F, R)
+    h = orc.OracleHead(d, group=g)
+    h.prefill(Qg, K, V)
+    kept = h.prune(B, F, R)
+    got = [(h.pos.tolist(), h.S.copy(), kept.tolist())]
+    for t in range(T):
+        a = h.append_and_score(qdg[t], kd[t], vd[t], L + t)
+        assert abs(a.sum() - 1.0) < 1e-14           # a mean of g softmax rows still sums to one
+        kept = h.prune(B, F, R)
+        got.append((h.pos.tolist(), h.S.copy(), kept.tolist()))
+    assert len(got) == len(want)
+    for (gp, gS, gk), (wp, wS, wk) in zip(got, want):
+        assert gp == wp and gk == wk
+        np.testing.assert_allclose(gS, wS, rtol=1e-12)
+
+
+def test_group_scores_match_torch_softmax_mean():
+    gen = torch.Generator().manual_seed(77)
+    g, L, d = 4, 193, 64
+    Q = torch.randn(g, L, d, generator=gen, dtype=torch.float64) * 1.3
+    K = torch.randn(L, d, generator=gen, dtype=torch.float64)
+    logits = torch.einsum("gjd,id->gji", Q, K) / math.sqrt(d)
+    logits = logits.masked_fill(torch.triu(torch.ones(L, L, dtype=torch.bool), 1), float("-inf"))
+    want = torch.softmax(logits, dim=-1).sum(dim=1).mean(dim=0).numpy()
+    got = orc.prefill_scores_group(Q.numpy(), K.numpy())
+    np.testing.assert_allclose(got, want, rtol=1e-11)
+    assert abs(got.sum() - L) < 1e-9
+    # decode step: mean of the heads' softmax rows
+    q = torch.randn(g, d, generator=gen, dtype=torch.float64) * 2
+    S0 = torch.rand(L, generator=gen, dtype=torch.float64)
+    a = torch.softmax(q @ K.T / math.sqrt(d), dim=-1).mean(dim=0)
+    S1, a_got = orc.decode_scores_group(q.numpy(), K.numpy(), S0.numpy())
+    np.testing.assert_allclose(a_got, a.numpy(), rtol=1e-12)
+    np.testing.assert_allclose(S1, (S0 + a).numpy(), rtol=1e-13)
+
+
+def test_group_of_one_and_group_of_equal_heads_reduce_to_a_single_head():
+    rng = np.random.default_rng(31)
+    L, d = 40, 8
+    Q, K = _rand(rng, L, d) * 1.5, _rand(rng, L, d)
+    S1 = orc.prefill_scores(Q, K)
+    np.testing.assert_array_equal(orc.prefill_scores_group(Q[None], K), S1)
+    np.testing.assert_array_equal(orc.prefill_scores_group(np.stack([Q] * 4), K), S1)     # (4x)/4 is exact
+    np.testing.assert_allclose(orc.prefill_scores_group(np.stack([Q] * 3), K), S1, rtol=1e-15)
+
+
+def test_group_mean_is_taken_after_each_heads_softmax():
+    """Two heads whose scores are known in closed form: head A has zero queries (uniform attention,
+    harmonic sums), head B puts all its attention on key 0.  The group score is the mean of the two;
+    a sum, a softmax over mean logits or a softmax over both heads' logits together would all differ."""
+    L, d, beta = 12, 4, 60.0
+    K = np.zeros((L, d))
+    K[0, 0] = beta                       # only key 0 has a component along e_0
+    K[1:, 1] = 1.0
+    QA = np.zeros((L, d))
+    QB = np.zeros((L, d))
+    QB[:, 0] = beta                      # logit of key 0: c * beta^2 = 1800, every other logit 0
+    S = orc.prefill_scores_group(np.stack([QA, QB]), K)
+    harm = np.array([float(x) for x in bf.harmonic_scores(L)])
+    sB = np.zeros(L)
+    sB[0] = L                            # exp(-1800) underflows to 0: the rest receives nothing
+    np.testing.assert_allclose(S, (harm + sB) / 2, rtol=1e-14)
+    # the attention-only ranking of the group therefore starts with token 0, then the oldest tokens
+    kept = orc.select(S, 5, 0, 0)
+    assert kept.tolist() == [0, 1, 2, 3, 4]
