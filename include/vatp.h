@@ -35,7 +35,8 @@ extern "C" {
 #endif
 
 #define VATP_MAX_BATCH 64          /* sequences per call                                  */
-#define VATP_MAX_UNITS 16384       /* batch * n_heads per call                            */
+#define VATP_MAX_UNITS 16384       /* batch * n_heads * max(q_per_kv, 1) per call         */
+#define VATP_MAX_GROUP 8           /* query heads per K/V head (grouped-query attention)  */
 #define VATP_MAX_CAP   4194304     /* rows per (batch, head) unit: cap and cap_out        */
 
 typedef struct vatp_ctx vatp_ctx;  /* opaque */
@@ -75,7 +76,25 @@ typedef struct {
     int32_t norm;           /* value-row norm of Eq. 4: VATP_NORM_L1 (0, the paper's choice), */
                             /*   VATP_NORM_L2 or VATP_NORM_LINF (the ablation of Table 2), or  */
                             /*   VATP_NORM_NONE: nrm = 1, the attention-only baseline (H2O)    */
+    int32_t q_per_kv;       /* g: query heads per K/V head, 0 or 1 .. VATP_MAX_GROUP (0 = 1).  */
+                            /*   g > 1 is grouped-query attention: see the note below          */
 } vatp_params;
+
+/*
+ * Grouped-query attention (Limitations section, paragraph on GQA: the group-wise averaged
+ * attention score as the token score).  With g = q_per_kv > 1, n_heads counts the K/V heads --
+ * the caches, S, nrm, pos, budgets and kept sets are per K/V head as before -- and every tensor
+ * of queries, and what is computed per query head, has n_heads * g heads: Q
+ * [batch, n_heads * g, cap, head_dim], q [batch, n_heads * g, head_dim], lse
+ * [batch, n_heads * g, cap], out [batch, n_heads * g, head_dim]; query head h * g + r belongs
+ * to K/V head h.  Each query head has its own softmax over the rows of its K/V head (Eq. 1);
+ * the score of a row is the mean over the group of what the g heads give it,
+ *     S[i] = (1/g) sum_r sum_j a_i^{j,r}   (prompt),     S[i] += (1/g) sum_r a_i^r   (decode),
+ * and Eq. 4 multiplies it by the norm of the shared value row.  Supported by
+ * vatp_prefill_score, vatp_prefill_score_lse, vatp_decode_step, vatp_decode_attend_step,
+ * vatp_decode_prune_step and (no queries involved) vatp_select_compact; the history-window
+ * calls return VATP_E_SHAPE for g > 1.
+ */
 
 /* Creates a context for HIP device `device` (host memory only).  The device must be the
  * current HIP device whenever a call that takes the context is made. */

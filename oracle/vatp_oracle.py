@@ -200,6 +200,19 @@ def prefill_scores_group(Qg, K, c: Optional[float] = None) -> np.ndarray:
     return S / g
 
 
+def prefill_scores_group_units(Qg, K, lens, c: Optional[float] = None) -> np.ndarray:
+    """prefill_scores_group for many K/V heads at once (OpenMP over query heads).
+    Qg: [units, g, cap, d], K: [units, cap, d]. Returns [units, cap]."""
+    Qg, K = _f64(Qg), _f64(K)
+    units, g, cap, d = Qg.shape
+    lens = np.asarray(lens, dtype=np.int64)
+    S_q = prefill_scores_units(Qg.reshape(units * g, cap, d), np.repeat(K, g, axis=0), np.repeat(lens, g), c)
+    S = np.zeros((units, cap), dtype=np.float64)
+    for r in range(g):                     # same order of additions as prefill_scores_group
+        S += S_q.reshape(units, g, cap)[:, r]
+    return S / g
+
+
 def decode_scores_group(qg, K, S, c: Optional[float] = None):
     """One decode step with g query heads on one key/value head: (S + a, a) with a the mean over the
     group of the heads' attention weights (each head has its own softmax).  qg: [g, d]."""

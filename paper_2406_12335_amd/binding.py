@@ -20,7 +20,7 @@ VATP_F32, VATP_BF16 = 0, 1
 NORM_L1, NORM_L2, NORM_LINF, NORM_NONE = 0, 1, 2, 3
 CALL_PREFILL_SCORE, CALL_DECODE_STEP, CALL_SELECT_COMPACT, CALL_DECODE_ATTEND_STEP, CALL_DECODE_PRUNE_STEP = 0, 1, 2, 3, 4
 CALL_PREFILL_SCORE_WINDOW = 5
-VATP_MAX_BATCH, VATP_MAX_UNITS = 64, 16384
+VATP_MAX_BATCH, VATP_MAX_UNITS, VATP_MAX_GROUP = 64, 16384, 8
 OK, E_NULL, E_SHAPE, E_DTYPE, E_BUDGET, E_WORKSPACE, E_DEVICE = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = ("vatp_create", "vatp_destroy", "vatp_strerror", "vatp_validate", "vatp_workspace_bytes",
@@ -40,7 +40,7 @@ class _Params(ctypes.Structure):
                 ("dtype", ctypes.c_int32), ("n_sink", ctypes.c_int32), ("recent", ctypes.c_int32),
                 ("cap", ctypes.c_int32), ("cap_out", ctypes.c_int32), ("scale", ctypes.c_float),
                 ("len", ctypes.POINTER(ctypes.c_int32)), ("budget", ctypes.POINTER(ctypes.c_int32)),
-                ("norm", ctypes.c_int32)]
+                ("norm", ctypes.c_int32), ("q_per_kv", ctypes.c_int32)]
 
 
 _lib = None
@@ -103,7 +103,7 @@ class Params:
 
     def __init__(self, batch: int, n_heads: int, head_dim: int, dtype, n_sink: int, recent: int,
                  cap: int, len: Sequence[int], budget: Optional[Sequence[int]] = None,
-                 cap_out: int = 0, scale: float = 0.0, norm: int = 0):
+                 cap_out: int = 0, scale: float = 0.0, norm: int = 0, q_per_kv: int = 0):
         if isinstance(dtype, torch.dtype):
             dtype = {torch.float32: VATP_F32, torch.bfloat16: VATP_BF16}.get(dtype, -1)
         self._len = (ctypes.c_int32 * max(1, batch))(*list(len)) if len is not None else None
@@ -111,7 +111,7 @@ class Params:
         self.c = _Params(batch, n_heads, head_dim, int(dtype), n_sink, recent, cap, cap_out, scale,
                          ctypes.cast(self._len, ctypes.POINTER(ctypes.c_int32)) if self._len is not None else None,
                          ctypes.cast(self._budget, ctypes.POINTER(ctypes.c_int32)) if self._budget is not None else None,
-                         int(norm))
+                         int(norm), int(q_per_kv))
 
     def set_len(self, len: Sequence[int]) -> None:
         for i, v in enumerate(len):

@@ -31,7 +31,10 @@ vatp_status check_params(const vatp_params *p, int which_call)
     if (which_call < VATP_CALL_PREFILL_SCORE || which_call > VATP_CALL_PREFILL_SCORE_WINDOW) return VATP_E_SHAPE;
     if (p->dtype != VATP_F32 && p->dtype != VATP_BF16) return VATP_E_DTYPE;
     if (p->batch < 1 || p->batch > VATP_MAX_BATCH || p->n_heads < 1) return VATP_E_SHAPE;
-    if (static_cast<int64_t>(p->batch) * p->n_heads > VATP_MAX_UNITS) return VATP_E_SHAPE;
+    if (p->q_per_kv < 0 || p->q_per_kv > VATP_MAX_GROUP) return VATP_E_SHAPE;
+    const int group = p->q_per_kv > 1 ? p->q_per_kv : 1;
+    if (group > 1 && which_call == VATP_CALL_PREFILL_SCORE_WINDOW) return VATP_E_SHAPE;   // no grouped history window
+    if (static_cast<int64_t>(p->batch) * p->n_heads * group > VATP_MAX_UNITS) return VATP_E_SHAPE;
     if (p->head_dim != 64 && p->head_dim != 128) return VATP_E_SHAPE;
     if (p->cap < 1 || p->cap_out < 0 || p->n_sink < 0 || p->recent < 0) return VATP_E_SHAPE;
     if (p->cap > VATP_MAX_CAP || p->cap_out > VATP_MAX_CAP) return VATP_E_SHAPE;   // 32-bit byte offsets inside a unit
@@ -68,6 +71,7 @@ void prepare(const vatp_params *p, int which_call, const int32_t *new_pos, Prepa
     g.n_sink = p->n_sink;
     g.recent = p->recent;
     g.norm = p->norm;
+    g.group = p->q_per_kv > 1 ? p->q_per_kv : 1;
     const double c = p->scale > 0.f ? static_cast<double>(p->scale) : 1.0 / sqrt(static_cast<double>(p->head_dim));
     g.scale_log2 = static_cast<float>(c * 1.4426950408889634074);
     g.max_len = 0;
@@ -136,7 +140,8 @@ vatp_status vatp_validate(const vatp_params *p, int which_call) { return check_p
 size_t vatp_workspace_bytes(const vatp_ctx *, const vatp_params *p, int which_call)
 {
     if (check_params(p, which_call) != VATP_OK) return 0;
-    const size_t units = static_cast<size_t>(p->batch) * p->n_heads;
+    // everything kept in the workspace is per query head
+    const size_t units = static_cast<size_t>(p->batch) * p->n_heads * (p->q_per_kv > 1 ? p->q_per_kv : 1);
     switch (which_call) {
     case VATP_CALL_PREFILL_SCORE:           // lse2[units, cap]
         return align_up(units * p->cap * sizeof(float));
@@ -170,7 +175,7 @@ vatp_status prefill_score_impl(vatp_ctx *ctx, const vatp_params *p, const void *
 {
     if (!ctx || !Q || !K || !V || !S || !nrm || (have_lse && !lse)) return VATP_E_NULL;
     if (window < -1 || window > kMaxWindow) return VATP_E_SHAPE;
-    const vatp_status st = check_params(p, VATP_CALL_PREFILL_SCORE);
+    const vatp_status st = check_params(p, window < 0 ? VATP_CALL_PREFILL_SCORE : VATP_CALL_PREFILL_SCORE_WINDOW);
     if (st != VATP_OK) return st;
     if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(hist, 4)) return VATP_E_SHAPE;
     const size_t need = vatp_workspace_bytes(ctx, p, window < 0 ? VATP_CALL_PREFILL_SCORE : VATP_CALL_PREFILL_SCORE_WINDOW);
@@ -244,7 +249,7 @@ vatp_status decode_step_impl(vatp_ctx *ctx, const vatp_params *p, int which_call
     if (!ws || ws_bytes < need || misaligned(ws, kAlign)) return VATP_E_WORKSPACE;
     Prepared pr;
     prepare(p, which_call, pos ? new_pos : nullptr, &pr);
-    const size_t units = static_cast<size_t>(p->batch) * p->n_heads;
+    const size_t units = static_cast<size_t>(p->batch) * p->n_heads * pr.g.group;      // query heads
     const size_t chunks = (static_cast<size_t>(p->cap) + kDecodeChunk - 1) / kDecodeChunk;
     char *base = static_cast<char *>(ws);
     float *ws_logit = reinterpret_cast<float *>(base);
@@ -303,7 +308,9 @@ vatp_status decode_prune_impl(vatp_ctx *ctx, const vatp_params *p, const void *q
     if (!ws || ws_bytes < need || misaligned(ws, kAlign)) return VATP_E_WORKSPACE;
     Prepared pr;
     prepare(p, VATP_CALL_DECODE_PRUNE_STEP, pos ? new_pos : nullptr, &pr);
-    const size_t units = static_cast<size_t>(p->batch) * p->n_heads;
+    if (win.hist && pr.g.group > 1) return VATP_E_SHAPE;                      // no grouped history window
+    const size_t kv_units = static_cast<size_t>(p->batch) * p->n_heads;
+    const size_t units = kv_units * pr.g.group;                               // query heads
     const size_t chunks = (static_cast<size_t>(p->cap) + kDecodeChunk - 1) / kDecodeChunk;
     char *base = static_cast<char *>(ws);
     float *ws_logit = reinterpret_cast<float *>(base);
@@ -316,7 +323,8 @@ vatp_status decode_prune_impl(vatp_ctx *ctx, const vatp_params *p, const void *q
     // One launch with a workgroup per head when there are enough heads to fill the chip that way and
     // each is short enough for a single workgroup to stream quickly (measured: 19.9 against 22.3 us per
     // step at 256 heads x 820 rows; slower than two launches at 32 heads x 2049 rows, 23 against 14 us).
-    const bool one = !out && !win.hist && units >= 128 && pr.g.max_len <= 1024 && pr.g.max_len <= decode_prune_one_max_rows();
+    const bool one = !out && !win.hist && pr.g.group == 1 && kv_units >= 128 && pr.g.max_len <= 1024 &&
+                     pr.g.max_len <= decode_prune_one_max_rows();
     if (one) {
         if (launch_decode_prune_one(p->dtype, p->head_dim, q, k, v, K, V, S, nrm, pos, K_out, V_out, S_out, nrm_out,
                                     pos_out, kept_idx, synced_in, synced_out, pr.meta, budgets, pr.g, stream) !=
@@ -392,6 +400,7 @@ vatp_status vatp_select_compact_window(vatp_ctx *ctx, const vatp_params *p, cons
     if (window < 0 || window > kMaxWindow || hist == hist_out) return VATP_E_SHAPE;
     vatp_status st = check_params(p, VATP_CALL_SELECT_COMPACT);
     if (st != VATP_OK) return st;
+    if (p->q_per_kv > 1) return VATP_E_SHAPE;                                  // no grouped history window
     for (int b = 0; b < p->batch; ++b)
         if (cap_hist < (p->len[b] < p->budget[b] ? p->len[b] : p->budget[b])) return VATP_E_BUDGET;
     st = vatp_select_compact(ctx, p, K, V, S, nrm, pos, K_out, V_out, S_out, nrm_out, pos_out, kept_idx, ws, ws_bytes,

@@ -161,13 +161,181 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(
     }
 }
 
+// The same launch for grouped-query attention: the workgroup reads its chunk of K rows once and
+// forms the logits of all g query heads of the group against it (the point of sharing a K/V head:
+// the cache is read once per group, not once per query head).  Logits and chunk statistics are kept
+// per query head ([g, cap] and [g, chunks] per unit); with an output pointer each head's share of
+// its attention output as well.
+template <typename T, int D, bool kAttend>
+__global__ __launch_bounds__(256) void decode_logits_group_kernel(
+    const T *__restrict__ q, const T *__restrict__ k_new, const T *__restrict__ v_new,
+    T *__restrict__ K, T *__restrict__ V, float *__restrict__ nrm, int32_t *__restrict__ pos,
+    float *__restrict__ ws_logit, float2 *__restrict__ ws_part, float *__restrict__ ws_out,
+    BatchMeta meta, int n_heads, int cap, int chunks_alloc, float scale_log2, int norm, int group)
+{
+    constexpr int kG = VATP_MAX_GROUP;
+    constexpr int kE = Elt<T>::kPer16B;
+    constexpr int kLanesPerRow = D / kE;
+    constexpr int kRowsPerPass = 256 / kLanesPerRow;
+    constexpr int kPasses = kDecodeChunk / kRowsPerPass;
+    constexpr int kGroup = kPasses < 16 ? kPasses : 16;        // loads issued back to back
+
+    __shared__ float s_logit[kG][kDecodeChunk];
+    __shared__ float s_max[kG];
+
+    const size_t unit = blockIdx.x;                            // K/V head
+    const int b = static_cast<int>(unit / n_heads), chunk = blockIdx.y;
+    const int n0 = meta.len[b];
+    const int n = n0 + 1;
+    const int row0 = chunk * kDecodeChunk;
+    if (row0 >= n) return;
+    const uint4 *Ku = reinterpret_cast<const uint4 *>(K + unit * cap * D);
+    const uint4 *knew = reinterpret_cast<const uint4 *>(k_new + unit * D);
+    const int tid = threadIdx.x;
+    const int sub = tid % kLanesPerRow;
+    const int rloc = tid / kLanesPerRow;
+    const int lane = tid & 63, wave = tid >> 6;
+
+    uint4 q_raw[kG];
+#pragma unroll
+    for (int i = 0; i < kG; ++i)
+        q_raw[i] = i < group ? reinterpret_cast<const uint4 *>(q + (unit * group + i) * D)[sub] : make_uint4(0, 0, 0, 0);
+    const bool owns_new_row = n0 >= row0 && n0 < row0 + kDecodeChunk && tid < kLanesPerRow;
+    uint4 kraw = make_uint4(0, 0, 0, 0), vraw = make_uint4(0, 0, 0, 0);
+    if (owns_new_row) {
+        kraw = knew[sub];
+        vraw = reinterpret_cast<const uint4 *>(v_new + unit * D)[sub];
+    }
+    float qf[kG][kE];
+
+#pragma unroll
+    for (int p0 = 0; p0 < kPasses; p0 += kGroup) {
+        uint4 raw[kGroup];
+#pragma unroll
+        for (int u = 0; u < kGroup; ++u) {
+            const int r = row0 + (p0 + u) * kRowsPerPass + rloc;
+            const uint4 *src = (r == n0) ? knew + sub : Ku + static_cast<size_t>(r) * kLanesPerRow + sub;
+            raw[u] = (r < n) ? *src : make_uint4(0, 0, 0, 0);
+        }
+        if (p0 == 0) {
+#pragma unroll
+            for (int i = 0; i < kG; ++i) Elt<T>::unpack(q_raw[i], qf[i]);
+            if (owns_new_row) {                     // append k, v, |v| and pos
+                reinterpret_cast<uint4 *>(K + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = kraw;
+                reinterpret_cast<uint4 *>(V + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = vraw;
+                float vf[kE], a = 0.f;
+                Elt<T>::unpack(vraw, vf);
+#pragma unroll
+                for (int e = 0; e < kE; ++e) a = norm_accum(norm, a, vf[e]);
+#pragma unroll
+                for (int off = kLanesPerRow / 2; off > 0; off >>= 1) a = norm_combine(norm, a, __shfl_xor(a, off));
+                if (sub == 0) {
+                    nrm[unit * cap + n0] = norm_finish(norm, a);
+                    if (pos) pos[unit * cap + n0] = meta.aux[b];
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kGroup; ++u) {
+            const int rl = (p0 + u) * kRowsPerPass + rloc;
+            float kf[kE];
+            Elt<T>::unpack(raw[u], kf);
+#pragma unroll
+            for (int i = 0; i < kG; ++i) {
+                if (i >= group) continue;
+                float dot = 0.f;
+#pragma unroll
+                for (int e = 0; e < kE; ++e) dot = fmaf(qf[i][e], kf[e], dot);
+#pragma unroll
+                for (int off = kLanesPerRow / 2; off > 0; off >>= 1) dot += __shfl_xor(dot, off);
+                if (sub == 0) s_logit[i][rl] = (row0 + rl < n) ? dot * scale_log2 : -INFINITY;
+            }
+        }
+    }
+    __syncthreads();
+
+    // chunk statistics, one wavefront per query head (two rows per lane): no exchange between wavefronts
+    for (int i = wave; i < group; i += 4) {
+        const float t0 = s_logit[i][lane], t1 = s_logit[i][lane + 64];
+        float mx = fmaxf(t0, t1);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+        float e = exp2f(t0 - mx) + exp2f(t1 - mx);           // 2^(-inf) = 0 for rows past the end
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) e += __shfl_xor(e, off);
+        if (lane == 0) {
+            ws_part[(unit * group + i) * chunks_alloc + chunk] = make_float2(mx, e);
+            s_max[i] = mx;
+        }
+    }
+    for (int idx = tid; idx < group * kDecodeChunk; idx += 256) {
+        const int i = idx / kDecodeChunk, r = idx % kDecodeChunk;
+        if (row0 + r < n) ws_logit[(unit * group + i) * cap + row0 + r] = s_logit[i][r];
+    }
+
+    if constexpr (kAttend) {
+        // every head's share of its attention output (Eq. 1) over this chunk, relative to the head's
+        // chunk maximum; rows are summed inside the wavefront first, then across the four through LDS
+        __shared__ float s_o[4][kG][D];
+        __syncthreads();                                      // s_max
+        const uint4 *Vu = reinterpret_cast<const uint4 *>(V + unit * cap * D);
+        const uint4 *vnew = reinterpret_cast<const uint4 *>(v_new + unit * D);
+        float oacc[kG][kE];
+#pragma unroll
+        for (int i = 0; i < kG; ++i)
+#pragma unroll
+            for (int e = 0; e < kE; ++e) oacc[i][e] = 0.f;
+#pragma unroll
+        for (int p0 = 0; p0 < kPasses; p0 += kGroup) {
+            uint4 raw[kGroup];
+#pragma unroll
+            for (int u = 0; u < kGroup; ++u) {
+                const int r = row0 + (p0 + u) * kRowsPerPass + rloc;
+                const uint4 *src = (r == n0) ? vnew + sub : Vu + static_cast<size_t>(r) * kLanesPerRow + sub;
+                raw[u] = (r < n) ? *src : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int u = 0; u < kGroup; ++u) {
+                const int rl = (p0 + u) * kRowsPerPass + rloc;
+                float vf[kE];
+                Elt<T>::unpack(raw[u], vf);
+#pragma unroll
+                for (int i = 0; i < kG; ++i) {
+                    if (i >= group) continue;
+                    const float p = exp2f(s_logit[i][rl] - s_max[i]);       // 0 past the end
+#pragma unroll
+                    for (int e = 0; e < kE; ++e) oacc[i][e] = fmaf(p, vf[e], oacc[i][e]);
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < kG; ++i) {
+            if (i >= group) continue;
+#pragma unroll
+            for (int e = 0; e < kE; ++e) {
+                float o = oacc[i][e];
+#pragma unroll
+                for (int off = kLanesPerRow; off < 64; off <<= 1) o += __shfl_xor(o, off);
+                if (lane < kLanesPerRow) s_o[wave][i][sub * kE + e] = o;
+            }
+        }
+        __syncthreads();
+        for (int idx = tid; idx < group * D; idx += 256) {
+            const int i = idx / D, x = idx % D;
+            ws_out[((unit * group + i) * chunks_alloc + chunk) * D + x] =
+                (s_o[0][i][x] + s_o[1][i][x]) + (s_o[2][i][x] + s_o[3][i][x]);
+        }
+    }
+}
+
+template <int kMaxG>
 __global__ __launch_bounds__(256) void decode_finish_kernel(float *__restrict__ S,
                                                             const float *__restrict__ ws_logit,
                                                             const float2 *__restrict__ ws_part,
                                                             const float *__restrict__ ws_out,
                                                             float *__restrict__ out, int head_dim,
                                                             BatchMeta meta, int n_heads, int cap,
-                                                            int chunks_alloc)
+                                                            int chunks_alloc, int group)
 {
     const size_t unit = blockIdx.x;
     const int b = static_cast<int>(unit / n_heads);
@@ -175,22 +343,28 @@ __global__ __launch_bounds__(256) void decode_finish_kernel(float *__restrict__ 
     const int row0 = static_cast<int>(blockIdx.y) * 256;
     const int r = row0 + static_cast<int>(threadIdx.x);          // one row per thread
     if (row0 >= n) return;
-    float logit = 0.f, s_old = 0.f;
-    if (r < n) {
-        logit = ws_logit[unit * cap + r];
-        if (r != n0) s_old = S[unit * cap + r];
-    }
-    // the softmax denominator from the unit's chunk statistics (per wavefront, one round trip)
+    float logit[kMaxG], s_old = 0.f;
+    load_group_logits<kMaxG>(logit, ws_logit + unit * group * cap, cap, group, r, r < n);
+    if (r < n && r != n0) s_old = S[unit * cap + r];
+    // the softmax denominators from the unit's chunk statistics (per wavefront, one round trip)
     const int n_chunks = (n + kDecodeChunk - 1) / kDecodeChunk;
-    const float2 *part = ws_part + unit * chunks_alloc;
-    float M, L;
-    merge_chunk_stats(part, n_chunks, M, L);
-    const float lse2 = M + log2f(L);
-    if (r < n) S[unit * cap + r] = s_old + exp2f(logit - lse2);
-    // attention output of the new token: the chunks' partial sums, rescaled to the common maximum
-    if (out && blockIdx.y == 0 && static_cast<int>(threadIdx.x) < head_dim)
-        out[unit * head_dim + threadIdx.x] = merge_chunk_outputs(ws_out + unit * chunks_alloc * head_dim, part, n_chunks,
-                                                                 head_dim, threadIdx.x, M, L);
+    const float2 *part = ws_part + unit * group * chunks_alloc;
+    float M[kMaxG], L[kMaxG], lse2[kMaxG];
+    merge_group_stats<kMaxG>(part, chunks_alloc, group, n_chunks, M, L, lse2);
+    if (r < n) S[unit * cap + r] = s_old + group_weight<kMaxG>(logit, lse2, group);
+    // attention output of the new token, per query head: the chunks' partial sums, rescaled to the common maximum
+    if (out && blockIdx.y == 0) {
+        for (int idx = threadIdx.x; idx < group * head_dim; idx += 256) {
+            const int i = idx / head_dim, x = idx % head_dim;
+            float Mi = M[0], Li = L[0];
+#pragma unroll
+            for (int k = 1; k < kMaxG; ++k)
+                if (k == i) { Mi = M[k]; Li = L[k]; }
+            const size_t qh = unit * group + i;
+            out[qh * head_dim + x] = merge_chunk_outputs(ws_out + qh * chunks_alloc * head_dim,
+                                                         part + static_cast<size_t>(i) * chunks_alloc, n_chunks, head_dim, x, Mi, Li);
+        }
+    }
 }
 
 }  // namespace
@@ -204,21 +378,36 @@ hipError_t launch_decode(int dtype, int head_dim, const void *q, const void *k, 
     const unsigned units = static_cast<unsigned>(g.batch) * g.n_heads;
     dim3 grid(units, (g.max_len + kDecodeChunk - 1) / kDecodeChunk), block(256);
     const bool attend = ws_out != nullptr;
-#define VATP_DEC(T, D, A)                                                                              \
-    hipLaunchKernelGGL((decode_logits_kernel<T, D, A>), grid, block, 0, st, static_cast<const T *>(q),  \
+#define VATP_DEC(KERNEL, T, D, A, ...)                                                                 \
+    hipLaunchKernelGGL((KERNEL<T, D, A>), grid, block, 0, st, static_cast<const T *>(q),               \
                        static_cast<const T *>(k), static_cast<const T *>(v), static_cast<T *>(K),      \
                        static_cast<T *>(V), nrm, pos, ws_logit, ws_part, ws_out, meta, g.n_heads,      \
-                       g.cap, chunks_alloc, g.scale_log2, g.norm)
-#define VATP_DEC2(T, D) do { if (attend) VATP_DEC(T, D, true); else VATP_DEC(T, D, false); } while (0)
+                       g.cap, chunks_alloc, g.scale_log2, g.norm, ##__VA_ARGS__)
+#define VATP_DEC2(T, D)                                                                                \
+    do {                                                                                               \
+        if (g.group > 1) {                                                                             \
+            if (attend) VATP_DEC(decode_logits_group_kernel, T, D, true, g.group);                     \
+            else VATP_DEC(decode_logits_group_kernel, T, D, false, g.group);                           \
+        } else {                                                                                       \
+            if (attend) VATP_DEC(decode_logits_kernel, T, D, true);                                    \
+            else VATP_DEC(decode_logits_kernel, T, D, false);                                          \
+        }                                                                                              \
+    } while (0)
     if (dtype == VATP_F32 && head_dim == 64) VATP_DEC2(float, 64);
     else if (dtype == VATP_F32) VATP_DEC2(float, 128);
     else if (head_dim == 64) VATP_DEC2(bf16_t, 64);
     else VATP_DEC2(bf16_t, 128);
 #undef VATP_DEC2
 #undef VATP_DEC
-    if (finish)     // (the fused decode-and-evict step has its own second launch)
-        hipLaunchKernelGGL(decode_finish_kernel, dim3(units, (g.max_len + 255) / 256), block, 0, st, S, ws_logit,
-                           ws_part, ws_out, out, head_dim, meta, g.n_heads, g.cap, chunks_alloc);
+    if (finish) {   // (the fused decode-and-evict step has its own second launch)
+        const dim3 fgrid(units, (g.max_len + 255) / 256);
+        if (g.group > 1)
+            hipLaunchKernelGGL(decode_finish_kernel<VATP_MAX_GROUP>, fgrid, block, 0, st, S, ws_logit, ws_part, ws_out,
+                               out, head_dim, meta, g.n_heads, g.cap, chunks_alloc, g.group);
+        else
+            hipLaunchKernelGGL(decode_finish_kernel<1>, fgrid, block, 0, st, S, ws_logit, ws_part, ws_out, out,
+                               head_dim, meta, g.n_heads, g.cap, chunks_alloc, 1);
+    }
     return hipGetLastError();
 }
 

@@ -25,7 +25,7 @@ namespace {
 
 constexpr int kThreads = 512;
 
-template <typename T, int D>
+template <typename T, int D, int kMaxG>
 __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
     const T *__restrict__ K, const T *__restrict__ V, const float *__restrict__ S,
     const float *__restrict__ nrm, const int32_t *__restrict__ pos, T *__restrict__ K_out,
@@ -33,7 +33,7 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
     int32_t *__restrict__ pos_out, int32_t *__restrict__ kept_idx, const int32_t *__restrict__ synced_in,
     int32_t *__restrict__ synced_out, const float *__restrict__ ws_logit, const float2 *__restrict__ ws_part,
     const float *__restrict__ ws_out, float *__restrict__ out, WindowArgs win, BatchMeta meta, int n_heads,
-    int cap, int cap_out, int chunks_alloc, int n_sink, int recent)
+    int cap, int cap_out, int chunks_alloc, int n_sink, int recent, int group)
 {
     constexpr int kE = Elt<T>::kPer16B;
     constexpr int kLanesPerRow = D / kE;
@@ -52,7 +52,7 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
     const int tid = threadIdx.x;
     const float *Su = S + unit * cap;
     const float *Nu = nrm + unit * cap;
-    const float *Lu = ws_logit + unit * cap;
+    const float *Lu = ws_logit + unit * group * cap;       // the group's logits: query head i at Lu + i * cap
 
     const int synced = synced_in[unit];
     const int lo = n_sink, hi = n - recent;                // rows [lo, hi) may leave
@@ -71,23 +71,22 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
     // the unprotected rows this thread looks at (logit, old score, norm), requested before the
     // denominator is known so that both round trips to memory overlap
     constexpr int kScan = 4;
-    float t_r[kScan], s_r[kScan], w_r[kScan], x_r[kScan];
+    float t_r[kScan][kMaxG], s_r[kScan], w_r[kScan], x_r[kScan];
 #pragma unroll
     for (int u = 0; u < kScan; ++u) {
         const int r = lo + tid + u * kThreads;
         const bool ok = n > B && r < hi;
-        t_r[u] = ok ? Lu[r] : 0.f;
+        load_group_logits<kMaxG>(t_r[u], Lu, cap, group, r, ok);
         s_r[u] = ok && r != n0 ? Su[r] : 0.f;
         w_r[u] = ok ? Nu[r] : 0.f;
         x_r[u] = ok ? leaving(r) : 0.f;
     }
 
-    // log2 of the softmax denominator from the chunk statistics
+    // log2 of the softmax denominator of every query head of the group from the chunk statistics
     const int n_chunks = (n + kDecodeChunk - 1) / kDecodeChunk;
-    const float2 *part = ws_part + unit * chunks_alloc;
-    float M, L;
-    merge_chunk_stats(part, n_chunks, M, L);
-    const float lse2 = M + log2f(L);
+    const float2 *part = ws_part + unit * group * chunks_alloc;
+    float M[kMaxG], L[kMaxG], lse2[kMaxG];
+    merge_group_stats<kMaxG>(part, chunks_alloc, group, n_chunks, M, L, lse2);
 
     // new score from the old one, this step's attention weight and (windowed) the weight that leaves;
     // rounding may leave a windowed sum a hair below zero: it is a sum of non-negative terms
@@ -95,7 +94,6 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
         const float s = s_old + p;
         return windowed ? fmaxf(s - gone, 0.f) : s;
     };
-    auto new_score = [&](int r) { return combine(r != n0 ? Su[r] : 0.f, exp2f(Lu[r] - lse2), leaving(r)); };
 
     // the row that leaves: minimise (importance bits, ~row) over the unprotected rows
     int evicted = n;                                       // n <= B: nothing leaves
@@ -110,16 +108,16 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
 #pragma unroll
         for (int u = 0; u < kScan; ++u) {
             const int r = lo + tid + u * kThreads;
-            if (r < hi) consider(r, combine(s_r[u], exp2f(t_r[u] - lse2), x_r[u]), w_r[u]);
+            if (r < hi) consider(r, combine(s_r[u], group_weight<kMaxG>(t_r[u], lse2, group), x_r[u]), w_r[u]);
         }
         // further rows, four per thread at a time: loads first, then the arithmetic
         for (int r0 = lo + tid + kScan * kThreads; r0 < hi; r0 += kScan * kThreads) {
-            float t4[kScan], s4[kScan], w4[kScan], x4[kScan];
+            float t4[kScan][kMaxG], s4[kScan], w4[kScan], x4[kScan];
 #pragma unroll
             for (int u = 0; u < kScan; ++u) {
                 const int r = r0 + u * kThreads;
                 const bool ok = r < hi;
-                t4[u] = ok ? Lu[r] : 0.f;
+                load_group_logits<kMaxG>(t4[u], Lu, cap, group, r, ok);
                 s4[u] = ok && r != n0 ? Su[r] : 0.f;
                 w4[u] = ok ? Nu[r] : 0.f;
                 x4[u] = ok ? leaving(r) : 0.f;
@@ -127,7 +125,7 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
 #pragma unroll
             for (int u = 0; u < kScan; ++u) {
                 const int r = r0 + u * kThreads;
-                if (r < hi) consider(r, combine(s4[u], exp2f(t4[u] - lse2), x4[u]), w4[u]);
+                if (r < hi) consider(r, combine(s4[u], group_weight<kMaxG>(t4[u], lse2, group), x4[u]), w4[u]);
             }
         }
 #pragma unroll
@@ -148,14 +146,14 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
         const int share = (n_keep + G - 1) / G;
         const int o_end = min(n_keep, (g + 1) * share);
         for (int o0 = g * share + tid; o0 < o_end; o0 += kScan * kThreads) {
-            float t4[kScan], s4[kScan], x4[kScan];
+            float t4[kScan][kMaxG], s4[kScan], x4[kScan];
             int c4[kScan];
 #pragma unroll
             for (int u = 0; u < kScan; ++u) {           // loads first, then the arithmetic and the stores
                 const int o = o0 + u * kThreads;
                 const int src = o + (o >= evicted ? 1 : 0);
                 const bool ok = o < o_end;
-                t4[u] = ok ? Lu[src] : 0.f;
+                load_group_logits<kMaxG>(t4[u], Lu, cap, group, src, ok);
                 s4[u] = ok && src != n0 ? Su[src] : 0.f;
                 x4[u] = ok ? leaving(src) : 0.f;
                 c4[u] = ok && windowed ? column(src) : 0;
@@ -164,7 +162,7 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
             for (int u = 0; u < kScan; ++u) {
                 const int o = o0 + u * kThreads;
                 if (o >= o_end) continue;
-                const float p = exp2f(t4[u] - lse2);
+                const float p = group_weight<kMaxG>(t4[u], lse2, group);
                 S_out[unit * cap_out + o] = combine(s4[u], p, x4[u]);
                 if (kept_idx) kept_idx[unit * cap_out + o] = o + (o >= evicted ? 1 : 0);
                 if (windowed) h_write[c4[u]] = p;
@@ -208,9 +206,19 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
         }
     }
 
-    // attention output of the new token (optional): the chunks' partial sums on a common maximum
-    if (out && g == 0 && tid < D)
-        out[unit * D + tid] = merge_chunk_outputs(ws_out + unit * chunks_alloc * D, part, n_chunks, D, tid, M, L);
+    // attention output of the new token (optional), per query head: the chunks' partial sums on a common maximum
+    if (out && g == 0) {
+        for (int idx = tid; idx < group * D; idx += kThreads) {
+            const int i = idx / D, x = idx % D;
+            float Mi = M[0], Li = L[0];
+#pragma unroll
+            for (int k = 1; k < kMaxG; ++k)
+                if (k == i) { Mi = M[k]; Li = L[k]; }
+            const size_t qh = unit * group + i;
+            out[qh * D + x] = merge_chunk_outputs(ws_out + qh * chunks_alloc * D, part + static_cast<size_t>(i) * chunks_alloc,
+                                                  n_chunks, D, x, Mi, Li);
+        }
+    }
 }
 
 // The whole step in one launch, one workgroup of 16 wavefronts per head: logits of the new query
@@ -421,16 +429,18 @@ hipError_t launch_decode_prune(int dtype, int head_dim, const void *K, const voi
     unsigned G = 1024u / units;
     G = G < 1u ? 1u : (G > 16u ? 16u : G);
     dim3 grid(units, G), block(kThreads);
-#define VATP_DP(T, D)                                                                                          \
-    hipLaunchKernelGGL((decode_prune_kernel<T, D>), grid, block, 0, st, static_cast<const T *>(K),               \
+#define VATP_DPG(T, D, G)                                                                                      \
+    hipLaunchKernelGGL((decode_prune_kernel<T, D, G>), grid, block, 0, st, static_cast<const T *>(K),            \
                        static_cast<const T *>(V), S, nrm, pos, static_cast<T *>(K_out), static_cast<T *>(V_out), \
                        S_out, nrm_out, pos_out, kept_idx, synced_in, synced_out, ws_logit, ws_part, ws_out, out, \
-                       win, meta, g.n_heads, g.cap, g.cap_out, chunks_alloc, g.n_sink, g.recent)
+                       win, meta, g.n_heads, g.cap, g.cap_out, chunks_alloc, g.n_sink, g.recent, g.group)
+#define VATP_DP(T, D) do { if (g.group > 1) VATP_DPG(T, D, VATP_MAX_GROUP); else VATP_DPG(T, D, 1); } while (0)
     if (dtype == VATP_F32 && head_dim == 64) VATP_DP(float, 64);
     else if (dtype == VATP_F32) VATP_DP(float, 128);
     else if (head_dim == 64) VATP_DP(bf16_t, 64);
     else VATP_DP(bf16_t, 128);
 #undef VATP_DP
+#undef VATP_DPG
     return hipGetLastError();
 }
 

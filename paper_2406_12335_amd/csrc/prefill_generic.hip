@@ -85,7 +85,7 @@ __global__ __launch_bounds__(256) void prefill_rowstat_generic(const T *__restri
                                                                const T *__restrict__ K,
                                                                float *__restrict__ lse2,
                                                                BatchMeta meta, int n_heads,
-                                                               int cap, float scale_log2, int window)
+                                                               int cap, float scale_log2, int window, int group)
 {
     __shared__ __attribute__((aligned(16))) float Qs[kSlab][kTile];
     __shared__ __attribute__((aligned(16))) float Ks[kSlab][kTile];
@@ -94,9 +94,10 @@ __global__ __launch_bounds__(256) void prefill_rowstat_generic(const T *__restri
     const int j0 = blockIdx.x * kTile;
     if (j0 >= len) return;
     if (window >= 0 && j0 + kTile <= len - 1 - window) return;      // no query of this tile is in the window
-    const size_t unit = static_cast<size_t>(b) * n_heads + h;
+    // h runs over the query heads; query head h reads the keys of K/V head h / group
+    const size_t unit = static_cast<size_t>(b) * n_heads * group + h;
     const T *Qu = Q + unit * cap * D;
-    const T *Ku = K + unit * cap * D;
+    const T *Ku = K + unit / group * cap * D;
     const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
 
     float m[4], l[4];
@@ -145,7 +146,7 @@ __global__ __launch_bounds__(256) void prefill_colsum_generic(const T *__restric
                                                               float *__restrict__ S,
                                                               BatchMeta meta, int n_heads,
                                                               int cap, float scale_log2, int window,
-                                                              float *__restrict__ hist)
+                                                              float *__restrict__ hist, int group)
 {
     __shared__ __attribute__((aligned(16))) float Qs[kSlab][kTile];
     __shared__ __attribute__((aligned(16))) float Ks[kSlab][kTile];
@@ -155,31 +156,35 @@ __global__ __launch_bounds__(256) void prefill_colsum_generic(const T *__restric
     const int i0 = blockIdx.x * kTile;
     if (i0 >= len) return;
     const size_t unit = static_cast<size_t>(b) * n_heads + h;
-    const T *Qu = Q + unit * cap * D;
     const T *Ku = K + unit * cap * D;
-    const float *lu = lse2 + unit * cap;
     const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
 
     // first query row that counts, and the window's attention rows of this unit (w+1 of them, cap entries each)
     const int q_first = window >= 0 ? max(0, len - 1 - window) : 0;
     float *hu = hist ? hist + unit * static_cast<size_t>(window + 1) * cap : nullptr;
     float col[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int j0 = max(i0, q_first / kTile * kTile); j0 < len; j0 += kTile) {
-        float acc[4][4];
-        logit_tile<T, D>(Qu, Ku, j0, i0, len, Qs, Ks, acc);
+    // the query heads that share this K/V head, one after the other (grouped-query attention; one otherwise):
+    // their column sums add up in the same registers and the mean is taken at the end
+    for (int qh = 0; qh < group; ++qh) {
+        const T *Qu = Q + (unit * group + qh) * cap * D;
+        const float *lu = lse2 + (unit * group + qh) * cap;
+        for (int j0 = max(i0, q_first / kTile * kTile); j0 < len; j0 += kTile) {
+            float acc[4][4];
+            logit_tile<T, D>(Qu, Ku, j0, i0, len, Qs, Ks, acc);
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            const int j = j0 + ty * 4 + a;
-            if (j < len && j >= q_first) {
-                const float lj = lu[j];
-                float *hrow = hu ? hu + static_cast<size_t>(j - q_first) * cap : nullptr;
+            for (int a = 0; a < 4; ++a) {
+                const int j = j0 + ty * 4 + a;
+                if (j < len && j >= q_first) {
+                    const float lj = lu[j];
+                    float *hrow = hu ? hu + static_cast<size_t>(j - q_first) * cap : nullptr;
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const int i = i0 + tx * 4 + c;
-                    if (i <= j) {
-                        const float pr = exp2f(acc[a][c] * scale_log2 - lj);
-                        col[c] += pr;
-                        if (hrow) hrow[i] = pr;
+                    for (int c = 0; c < 4; ++c) {
+                        const int i = i0 + tx * 4 + c;
+                        if (i <= j) {
+                            const float pr = exp2f(acc[a][c] * scale_log2 - lj);
+                            col[c] += pr;
+                            if (hrow) hrow[i] = pr;
+                        }
                     }
                 }
             }
@@ -193,7 +198,7 @@ __global__ __launch_bounds__(256) void prefill_colsum_generic(const T *__restric
 #pragma unroll
         for (int y = 0; y < 16; ++y) s += red[y][threadIdx.x];
         const int i = i0 + threadIdx.x;
-        if (i < len) S[unit * cap + i] = s;
+        if (i < len) S[unit * cap + i] = s * (1.f / static_cast<float>(group));      // (exact for one head)
     }
 }
 
@@ -214,8 +219,9 @@ hipError_t launch_lse_to_base2(const float *lse, float *lse2, const BatchMeta &m
                                hipStream_t st)
 {
     if (g.max_len <= 0) return hipSuccess;
-    hipLaunchKernelGGL(lse_to_base2_kernel, dim3((g.max_len + 255) / 256, g.n_heads, g.batch), dim3(256), 0, st, lse,
-                       lse2, meta, g.n_heads, g.cap);
+    const int q_heads = g.n_heads * g.group;           // one row log-sum-exp per query head
+    hipLaunchKernelGGL(lse_to_base2_kernel, dim3((g.max_len + 255) / 256, q_heads, g.batch), dim3(256), 0, st, lse,
+                       lse2, meta, q_heads, g.cap);
     return hipGetLastError();
 }
 
@@ -225,15 +231,16 @@ hipError_t launch_prefill_generic(int dtype, int head_dim, const void *Q, const 
 {
     if (g.max_len <= 0) return hipSuccess;
     dim3 grid((g.max_len + kTile - 1) / kTile, g.n_heads, g.batch), block(256);
+    dim3 grid_q(grid.x, g.n_heads * g.group, g.batch);        // row statistics: one pass per query head
 #define VATP_PF(T, D)                                                                          \
     do {                                                                                       \
         if (!have_lse)                                                                         \
-            hipLaunchKernelGGL((prefill_rowstat_generic<T, D>), grid, block, 0, st,            \
+            hipLaunchKernelGGL((prefill_rowstat_generic<T, D>), grid_q, block, 0, st,          \
                                static_cast<const T *>(Q), static_cast<const T *>(K), lse2,     \
-                               meta, g.n_heads, g.cap, g.scale_log2, window);                  \
+                               meta, g.n_heads, g.cap, g.scale_log2, window, g.group);         \
         hipLaunchKernelGGL((prefill_colsum_generic<T, D>), grid, block, 0, st,                 \
                            static_cast<const T *>(Q), static_cast<const T *>(K), lse2, S,      \
-                           meta, g.n_heads, g.cap, g.scale_log2, window, hist);                \
+                           meta, g.n_heads, g.cap, g.scale_log2, window, hist, g.group);       \
     } while (0)
     if (dtype == VATP_F32 && head_dim == 64) VATP_PF(float, 64);
     else if (dtype == VATP_F32) VATP_PF(float, 128);

@@ -215,7 +215,7 @@ __device__ __forceinline__ void value_norms_64(const uint4 *__restrict__ Vu, flo
     }
 }
 
-template <bool kColsum, int kHalves, bool kWindow = false>
+template <bool kColsum, int kHalves, bool kWindow = false, bool kGrouped = false>
 __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_t *__restrict__ Q,
                                                            const bf16_t *__restrict__ K,
                                                            float *__restrict__ lse2,
@@ -223,9 +223,10 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
                                                            int n_heads, int n_units, int cap,
                                                            int n_blocks, float scale_log2, WindowPass win,
                                                            const bf16_t *__restrict__ V, float *__restrict__ nrm,
-                                                           int norm)
+                                                           int norm, int group)
 {
     static_assert(!kWindow || kHalves == 1, "the windowed passes use 4-wavefront workgroups");
+    static_assert(!kGrouped || (kColsum && !kWindow), "only the plain column-sum pass loops over a group's query heads");
     constexpr bool kSplitKeys = kWindow && !kColsum;      // windowed row statistics: one (block, key range) per workgroup
     // A ring slot holds kHalves sub-stages of 64 streamed rows; wavefront w works on sub-stage
     // w / 4 of every slot for the 64 stationary rows of column group w % 4.  With kHalves = 2
@@ -249,9 +250,15 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
     const int len = meta.len[b];
     const int q_first = kWindow ? max(0, len - 1 - win.window) : 0;     // first query row that counts
     const size_t unit = static_cast<size_t>(unit_i);
+    // Grouped-query attention (group > 1; paper, Limitations section): query head u belongs to K/V head
+    // u / group.  The row-statistics pass has one unit per query head (n_heads then counts query heads) and
+    // streams the keys of that head's K/V head; the column-sum pass (kGrouped) has one unit per K/V head
+    // and streams the queries of its `group` query heads one after the other into the same column sums.
     const uint4 *stat = reinterpret_cast<const uint4 *>((kColsum ? K : Q) + unit * cap * kD);
-    const bf16_t *strm = (kColsum ? Q : K) + unit * cap * kD;
-    float *lse_u = lse2 + unit * cap;
+    const bf16_t *const strm0 = kColsum ? Q + unit * group * cap * kD : K + unit / group * cap * kD;
+    float *const lse_u0 = lse2 + (kColsum ? unit * group : unit) * cap;
+    const bf16_t *strm = strm0;
+    float *lse_u = lse_u0;
     // windowed column sums: descriptor over this head's [w + 1, cap] matrix of attention rows
     // (no matrix, or another kind of pass: zero records, every store is dropped)
     const bool with_hist = kWindow && kColsum && win.hist != nullptr;
@@ -259,6 +266,7 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
         with_hist ? win.hist + unit * static_cast<size_t>(win.window + 1) * cap : nullptr, 0,
         with_hist ? (win.window + 1) * cap * 4 : 0, 0x00020000);
 
+    const float inv_group = 1.f / static_cast<float>(group);     // the group mean (exactly 1 for one head)
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int cw = wave & 3, half = wave >> 2;      // column group, sub-stage
@@ -291,7 +299,13 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
     };
     // copies per stage issued by this wavefront (column group 0 also brings the lse values)
     const bool extra_copy = kColsum && cw == 0;
-    for (int job = 0; job < (kSplitKeys ? 1 : 2); ++job) {
+    // A job is one block of stationary rows; with grouped queries it is walked once per query head
+    // (`run` and the stationary operand live on from one head to the next).
+    const int n_qh = kGrouped ? group : 1;
+    bf16x8 Bf[2][8] = {};
+    Running<kColsum> run;
+    for (int it = 0, n_it = (kSplitKeys ? 1 : 2) * n_qh; it < n_it; ++it) {
+        const int job = kGrouped ? it / n_qh : it, qh = kGrouped ? it % n_qh : 0;
         int blk = job == 0 ? pair : n_blocks - 1 - pair;
         if constexpr (kSplitKeys) blk = q_first / kBlockCols + pair / win.n_splits;
         if (!kSplitKeys && job == 1 && blk == pair) break;   // odd count: the middle block once
@@ -309,6 +323,10 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
             if (t_begin > t_end) continue;
         }
 
+        if constexpr (kGrouped) {
+            strm = strm0 + static_cast<size_t>(qh) * cap * kD;
+            lse_u = lse_u0 + static_cast<size_t>(qh) * cap;
+        }
 #pragma unroll
         for (int k = 0; k < kAhead; ++k)
             if (t_begin + k <= t_end) copy_stage(t_begin + k, k);
@@ -316,7 +334,7 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
         // The column-sum pass visits every block of keys once: it also leaves the norm of the value rows
         // of its block (paper Eq. 4), 64 rows per wavefront, while the first stages are on their way.
         if constexpr (kColsum) {
-            if (V != nullptr && half == 0) {
+            if (V != nullptr && half == 0 && qh == 0) {
                 const uint4 *Vu = reinterpret_cast<const uint4 *>(V + unit * cap * kD);
                 float *nu = nrm + unit * cap;
                 switch (norm) {
@@ -329,16 +347,20 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
         }
 
         // stationary operand: 2 column blocks x 8 MFMA steps, 8 bf16 per lane each
-        bf16x8 Bf[2][8];
+        if (qh == 0) {
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-            const int row = w0 + 32 * cb + n;
+            for (int cb = 0; cb < 2; ++cb) {
+                const int row = w0 + 32 * cb + n;
 #pragma unroll
-            for (int s = 0; s < 8; ++s) {
-                uint4 raw = make_uint4(0, 0, 0, 0);
-                if (row < len) raw = stat[static_cast<size_t>(row) * kChunksPerRow + s + 8 * g];
-                Bf[cb][s] = as_bf16x8(raw);
+                for (int s = 0; s < 8; ++s) {
+                    uint4 raw = make_uint4(0, 0, 0, 0);
+                    if (row < len) raw = stat[static_cast<size_t>(row) * kChunksPerRow + s + 8 * g];
+                    Bf[cb][s] = as_bf16x8(raw);
+                }
             }
+            run.m[0] = run.m[1] = -1e30f;
+            run.l[0] = run.l[1] = 0.f;
+            run.col[0] = run.col[1] = 0.f;
         }
 
         // Make the stationary loads complete here, where the compiler can see it: otherwise it
@@ -348,10 +370,6 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
         for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
             for (int s = 0; s < 8; ++s) asm volatile("" ::"v"(Bf[cb][s]));
-        Running<kColsum> run;
-        run.m[0] = run.m[1] = -1e30f;
-        run.l[0] = run.l[1] = 0.f;
-        run.col[0] = run.col[1] = 0.f;
         // a neutral pending pair: -inf logits turn into zeros in both epilogues
         Pending<kColsum> pend;
 #pragma unroll
@@ -500,6 +518,7 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
             epi.finish(pend, run, scale_log2);
         }
 
+        if (qh == n_qh - 1) {
         // merge the two lane halves (same stationary column, complementary streamed rows), then,
         // with two sub-stages, the two wavefronts of a column group through LDS
         float fin_m[2], fin_l[2];
@@ -547,9 +566,10 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
                         win.lse_part[(static_cast<size_t>(pair % win.n_splits) * n_units + unit) * cap + idx] =
                             fin_m[cb] + __log2f(fin_l[cb]);
                     else if (!kColsum) lse_u[idx] = fin_m[cb] + __log2f(fin_l[cb]);
-                    else S[unit * cap + idx] = fin_l[cb];
+                    else S[unit * cap + idx] = kGrouped ? fin_l[cb] * inv_group : fin_l[cb];
                 }
             }
+        }
         }
         // every wavefront must be done reading the ring before the next job refills it (all
         // copies have landed by now; the result stores need not have)
@@ -558,19 +578,6 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
 }
 
 }  // namespace
-
-template <int kHalves>
-static void launch_both(const bf16_t *Q, const bf16_t *K, const bf16_t *V, float *S, float *nrm, float *lse2,
-                        bool have_lse, const BatchMeta &meta, const Geometry &g, int n_units, int n_blocks, dim3 grid,
-                        hipStream_t st)
-{
-    const dim3 block(256 * kHalves);
-    if (!have_lse)      // row statistics are computed here unless the caller supplied them
-        hipLaunchKernelGGL((prefill_mfma_kernel<false, kHalves>), grid, block, 0, st, Q, K, lse2, S, meta, g.n_heads,
-                           n_units, g.cap, n_blocks, g.scale_log2, WindowPass{}, nullptr, nullptr, 0);
-    hipLaunchKernelGGL((prefill_mfma_kernel<true, kHalves>), grid, block, 0, st, Q, K, lse2, S, meta, g.n_heads,
-                       n_units, g.cap, n_blocks, g.scale_log2, WindowPass{}, V, nrm, g.norm);
-}
 
 namespace {
 
@@ -635,13 +642,13 @@ hipError_t launch_prefill_mfma_window(const void *Q, const void *K, const void *
     const int window_blocks = (window + 1 + kBlockCols - 1) / kBlockCols + 1;     // blocks a window can straddle
     win.n_qb = window_blocks < n_blocks ? window_blocks : n_blocks;
     hipLaunchKernelGGL((prefill_mfma_kernel<false, 1, true>), dim3(8u * win.n_qb * win.n_splits * unit_groups), dim3(256),
-                       0, st, q, k, lse2, S, meta, g.n_heads, n_units, g.cap, n_blocks, g.scale_log2, win, nullptr, nullptr, 0);
+                       0, st, q, k, lse2, S, meta, g.n_heads, n_units, g.cap, n_blocks, g.scale_log2, win, nullptr, nullptr, 0, 1);
     const int merge_rows = window + 1 + kStage;
     hipLaunchKernelGGL(merge_split_lse_kernel, dim3((merge_rows + 255) / 256, n_units), dim3(256), 0, st, lse_part, lse2,
                        meta, g.n_heads, n_units, g.cap, window, win.n_splits);
     hipLaunchKernelGGL((prefill_mfma_kernel<true, 1, true>), dim3(8u * ((n_blocks + 1) / 2) * unit_groups), dim3(256), 0,
                        st, q, k, lse2, S, meta, g.n_heads, n_units, g.cap, n_blocks, g.scale_log2, win,
-                       static_cast<const bf16_t *>(V), nrm, g.norm);
+                       static_cast<const bf16_t *>(V), nrm, g.norm, 1);
     return hipGetLastError();
 }
 
@@ -650,16 +657,35 @@ hipError_t launch_prefill_mfma(const void *Q, const void *K, const void *V, floa
 {
     if (g.max_len <= 0) return hipSuccess;
     const int n_blocks = (g.max_len + kBlockCols - 1) / kBlockCols;
-    const int n_units = g.batch * g.n_heads;
     const int n_pairs = (n_blocks + 1) / 2;
-    const unsigned n_wg = 8u * n_pairs * ((n_units + 7) / 8);
     const bf16_t *q = static_cast<const bf16_t *>(Q), *k = static_cast<const bf16_t *>(K);
     const bf16_t *v = static_cast<const bf16_t *>(V);
-    // Two wavefronts per SIMD either way: two 4-wavefront workgroups per compute unit when
-    // the grid is large enough to keep pairs of them resident, else 8-wavefront workgroups.
-    const int halves = n_wg >= 2u * kComputeUnits ? 1 : 2;
-    if (halves == 2) launch_both<2>(q, k, v, S, nrm, lse2, have_lse, meta, g, n_units, n_blocks, dim3(n_wg), st);
-    else launch_both<1>(q, k, v, S, nrm, lse2, have_lse, meta, g, n_units, n_blocks, dim3(n_wg), st);
+    // One unit per query head in the row-statistics pass, one per K/V head in the column-sum pass (the
+    // same count unless query heads share K/V heads).  Two wavefronts per SIMD either way: two
+    // 4-wavefront workgroups per compute unit when the grid is large enough to keep pairs of them
+    // resident, else 8-wavefront workgroups.
+    const int kv_units = g.batch * g.n_heads, q_units = kv_units * g.group;
+    const unsigned wg_q = 8u * n_pairs * ((q_units + 7) / 8), wg_kv = 8u * n_pairs * ((kv_units + 7) / 8);
+    if (!have_lse) {    // row statistics are computed here unless the caller supplied them
+        if (wg_q >= 2u * kComputeUnits)
+            hipLaunchKernelGGL((prefill_mfma_kernel<false, 1>), dim3(wg_q), dim3(256), 0, st, q, k, lse2, S, meta,
+                               g.n_heads * g.group, q_units, g.cap, n_blocks, g.scale_log2, WindowPass{}, nullptr,
+                               nullptr, 0, g.group);
+        else
+            hipLaunchKernelGGL((prefill_mfma_kernel<false, 2>), dim3(wg_q), dim3(512), 0, st, q, k, lse2, S, meta,
+                               g.n_heads * g.group, q_units, g.cap, n_blocks, g.scale_log2, WindowPass{}, nullptr,
+                               nullptr, 0, g.group);
+    }
+#define VATP_COLSUM(HALVES, GROUPED)                                                                              \
+    hipLaunchKernelGGL((prefill_mfma_kernel<true, HALVES, false, GROUPED>), dim3(wg_kv), dim3(256 * HALVES), 0, st, q, k, \
+                       lse2, S, meta, g.n_heads, kv_units, g.cap, n_blocks, g.scale_log2, WindowPass{}, v, nrm, g.norm, \
+                       g.group)
+    if (wg_kv >= 2u * kComputeUnits) {
+        if (g.group > 1) VATP_COLSUM(1, true); else VATP_COLSUM(1, false);
+    } else {
+        if (g.group > 1) VATP_COLSUM(2, true); else VATP_COLSUM(2, false);
+    }
+#undef VATP_COLSUM
     return hipGetLastError();
 }
 

@@ -23,6 +23,7 @@ struct Geometry {
     float   scale_log2;            // c * log2(e): logits are kept in the base-2 domain
     int32_t max_len;               // max over the batch of len (decode: len + 1)
     int32_t norm;                  // VATP_NORM_*: value-row norm of the importance (paper Eq. 4, Table 2)
+    int32_t group;                 // g >= 1: query heads per K/V head (n_heads counts K/V heads)
 };
 
 // Value-row norm in three steps: lane-local accumulation, combination across the row's lanes,
@@ -116,6 +117,69 @@ __device__ __forceinline__ float merge_chunk_outputs(const float *__restrict__ w
         }
     }
     return ((acc[0] + acc[1]) + (acc[2] + acc[3])) / L;
+}
+
+// Grouped-query attention: g query heads share a K/V head, each with its own softmax, and a row's
+// score grows by the mean of the g attention weights (paper, Limitations section, paragraph on GQA).
+// The heads' logits of a unit lie one after the other ([g, cap]), their chunk statistics likewise
+// ([g, chunks_alloc]).  lse2[i] = log2 of head i's softmax denominator + log2 g, so that
+//     group_weight = sum_i 2^(t_i - lse2[i])
+// is that mean.  kMaxG = 1 is plain multi-head attention: the same operations, in the same order,
+// as merge_chunk_stats followed by 2^(t - lse2).
+template <int kMaxG>
+__device__ __forceinline__ void merge_group_stats(const float2 *__restrict__ part, int chunks_alloc, int g,
+                                                  int n_chunks, float (&M)[kMaxG], float (&L)[kMaxG],
+                                                  float (&lse2)[kMaxG])
+{
+    if constexpr (kMaxG == 1) {
+        merge_chunk_stats(part, n_chunks, M[0], L[0]);
+        lse2[0] = M[0] + log2f(L[0]);
+    } else {
+        const int lane = threadIdx.x & 63;
+        float2 mine[kMaxG];
+#pragma unroll
+        for (int i = 0; i < kMaxG; ++i) {           // every head's first round of loads is in flight at once
+            mine[i] = make_float2(-INFINITY, 0.f);
+            if (i < g && lane < n_chunks) mine[i] = part[static_cast<size_t>(i) * chunks_alloc + lane];
+        }
+        const float log2g = log2f(static_cast<float>(g));
+#pragma unroll
+        for (int i = 0; i < kMaxG; ++i) {
+            M[i] = 0.f; L[i] = 1.f; lse2[i] = 0.f;
+            if (i >= g) continue;
+            const float2 *pi = part + static_cast<size_t>(i) * chunks_alloc;
+            float m = mine[i].x;
+            for (int c = lane + 64; c < n_chunks; c += 64) m = fmaxf(m, pi[c].x);
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+            float l = mine[i].y * exp2f(mine[i].x - m);
+            for (int c = lane + 64; c < n_chunks; c += 64) l += pi[c].y * exp2f(pi[c].x - m);
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) l += __shfl_xor(l, off);
+            M[i] = m;
+            L[i] = l;
+            lse2[i] = m + log2f(l) + log2g;
+        }
+    }
+}
+
+// the g logits of row r (head i at Lu + i * cap); zeros when !ok
+template <int kMaxG>
+__device__ __forceinline__ void load_group_logits(float (&t)[kMaxG], const float *__restrict__ Lu, int cap, int g,
+                                                  int r, bool ok)
+{
+#pragma unroll
+    for (int i = 0; i < kMaxG; ++i) t[i] = (ok && i < g) ? Lu[static_cast<size_t>(i) * cap + r] : 0.f;
+}
+
+template <int kMaxG>
+__device__ __forceinline__ float group_weight(const float (&t)[kMaxG], const float (&lse2)[kMaxG], int g)
+{
+    float p = exp2f(t[0] - lse2[0]);
+#pragma unroll
+    for (int i = 1; i < kMaxG; ++i)
+        if (i < g) p += exp2f(t[i] - lse2[i]);
+    return p;
 }
 
 // ---- host-side launchers, one per source file --------------------------------------

@@ -18,13 +18,17 @@ from . import binding as B
 class PrunedKVCache:
     def __init__(self, batch: int, n_heads: int, head_dim: int, dtype: torch.dtype, n_sink: int, recent: int,
                  budgets: Sequence[int], device, cap_cache: Optional[int] = None, track_pos: bool = True,
-                 ctx=None, norm: int = 0, window: Optional[int] = None):
+                 ctx=None, norm: int = 0, window: Optional[int] = None, q_per_kv: int = 1):
         self.device = torch.device(device)
         self.batch, self.n_heads, self.head_dim, self.dtype = batch, n_heads, head_dim, dtype
         self.n_sink, self.recent, self.norm = n_sink, recent, norm
         # window = w: scores over a history window of w steps (Eq. 3) instead of accumulated ones; only the
         # fused step supports it
         self.window = window
+        # q_per_kv = g > 1: grouped-query attention; n_heads counts the K/V heads, query tensors have n_heads * g heads
+        self.q_per_kv = int(q_per_kv)
+        if window is not None and self.q_per_kv > 1:
+            raise ValueError("vatp: the history-window calls do not take grouped queries")
         self.budgets = [int(x) for x in budgets]
         self.cap = int(cap_cache) if cap_cache else max(self.budgets) + 1
         self._own_ctx = ctx is None
@@ -45,7 +49,7 @@ class PrunedKVCache:
         self.cur = 0
         self.lens: List[int] = [0] * batch
         self._p_dec = B.Params(batch, n_heads, head_dim, dtype, n_sink, recent, self.cap, self.lens, self.budgets,
-                               norm=norm)
+                               norm=norm, q_per_kv=self.q_per_kv)
         # sized for the fullest cache a decode step may meet (cap - 1 rows plus the new one)
         self._p_dec.set_len([self.cap - 1] * batch)
         nbytes = B.vatp_workspace_bytes(self.ctx, self._p_dec, B.CALL_DECODE_ATTEND_STEP)   # the largest of the decode calls
@@ -74,10 +78,13 @@ class PrunedKVCache:
 
     # -- prompt pass -----------------------------------------------------------------
     def prefill_score(self, Q, K, V, lens: Sequence[int], stream=None):
-        """vatp_prefill_score on [b, H, cap_p, d] prompt tensors; results kept in S_prompt / nrm_prompt."""
-        b, H, cap_p, d = Q.shape
+        """vatp_prefill_score on [b, H, cap_p, d] prompt tensors (Q: [b, H * q_per_kv, cap_p, d]); results kept in
+        S_prompt / nrm_prompt."""
+        b, H, cap_p, d = K.shape
+        if tuple(Q.shape) != (b, H * self.q_per_kv, cap_p, d):
+            raise ValueError("vatp: Q must have n_heads * q_per_kv heads")
         p = B.Params(b, H, d, self.dtype, self.n_sink, self.recent, cap_p, lens, self.budgets, cap_out=self.cap,
-                     norm=self.norm)
+                     norm=self.norm, q_per_kv=self.q_per_kv)
         need = B.vatp_workspace_bytes(self.ctx, p, B.CALL_PREFILL_SCORE if self.window is None
                                       else B.CALL_PREFILL_SCORE_WINDOW)
         if getattr(self, "_ws_prompt", None) is None or self._ws_prompt.numel() < need:

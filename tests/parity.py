@@ -96,6 +96,8 @@ def run_trajectory(inp, device, units: Optional[Sequence[Tuple[int, int]]] = Non
     the relative tolerance there is an absolute one: a few fp32 ulps of the largest score seen, per step."""
     cfg = inp.cfg
     b, H, d = cfg.batch, cfg.n_heads, cfg.head_dim
+    grp = cfg.q_per_kv                       # > 1: grouped queries, query heads h*grp .. h*grp+grp-1 on K/V head h
+    assert grp == 1 or window is None
     F = cfg.n_sink_keep if n_sink is None else n_sink
     R = cfg.recent
     T = cfg.decode_steps if steps is None else steps
@@ -108,7 +110,12 @@ def run_trajectory(inp, device, units: Optional[Sequence[Tuple[int, int]]] = Non
     qd, kd, vd = dev(inp.qd), dev(inp.kd), dev(inp.vd)
     assert window is None or fused
     cache = PrunedKVCache(b, H, d, cfg.torch_dtype(), F, R, inp.budgets, device, cap_cache=cap_cache, norm=norm_kind,
-                          window=window)
+                          window=window, q_per_kv=grp)
+
+    def q_of(t: torch.Tensor, bb: int, hh: int) -> np.ndarray:
+        """Decode query of unit (bb, hh): [d], or [grp, d] for grouped queries."""
+        return _vec(t[bb, hh]) if grp == 1 else _vec(t[bb, hh * grp:(hh + 1) * grp])
+
     s_max = {u: 0.0 for u in units}          # largest oracle score seen per unit (windowed tolerance)
     try:
         cache.prefill_score(Q, K, V, inp.lens)
@@ -116,13 +123,18 @@ def run_trajectory(inp, device, units: Optional[Sequence[Tuple[int, int]]] = Non
         heads: Dict[Tuple[int, int], orc.OracleHead] = {}
         # oracle prompt pass for the chosen units (OpenMP over units)
         Lmax = max(inp.lens)
-        Qh = np.stack([_unit_rows(inp.Q, bb, hh, Lmax) for bb, hh in units])
         Kh = np.stack([_unit_rows(inp.K, bb, hh, Lmax) for bb, hh in units])
-        S_or = orc.prefill_scores_units(Qh, Kh, [inp.lens[bb] for bb, _ in units]) \
-            if full_prefill_check and window is None else None
+        S_or = None
+        if grp == 1:
+            Qh = np.stack([_unit_rows(inp.Q, bb, hh, Lmax) for bb, hh in units])
+            if full_prefill_check and window is None:
+                S_or = orc.prefill_scores_units(Qh, Kh, [inp.lens[bb] for bb, _ in units])
+        elif full_prefill_check:
+            Qg = np.stack([np.stack([_unit_rows(inp.Q, bb, hh * grp + r, Lmax) for r in range(grp)]) for bb, hh in units])
+            S_or = orc.prefill_scores_group_units(Qg, Kh, [inp.lens[bb] for bb, _ in units])
         for ui, (bb, hh) in enumerate(units):
             L = inp.lens[bb]
-            o = orc.OracleHead(d, norm_kind=norm_kind, window=window)
+            o = orc.OracleHead(d, norm_kind=norm_kind, window=window, group=grp)
             o.K, o.V = Kh[ui, :L].copy(), _unit_rows(inp.V, bb, hh, L)
             o.nrm = orc.vnorm(o.V, norm_kind)
             o.pos = np.arange(L, dtype=np.int64)
@@ -196,7 +208,7 @@ def run_trajectory(inp, device, units: Optional[Sequence[Tuple[int, int]]] = Non
             n_before = [n + 1 for n in cache.lens]
             cache.decode_prune_step(qd[t], kd[t], vd[t], new_pos)
             for (bb, hh), o in heads.items():
-                o.append_and_score(_vec(inp.qd[t, bb, hh]), _vec(inp.kd[t, bb, hh]), _vec(inp.vd[t, bb, hh]),
+                o.append_and_score(q_of(inp.qd[t], bb, hh), _vec(inp.kd[t, bb, hh]), _vec(inp.vd[t, bb, hh]),
                                    new_pos[bb])
             check_fused_step(t, n_before, (t % check_every == 0) or t == T - 1)
 
@@ -209,7 +221,7 @@ def run_trajectory(inp, device, units: Optional[Sequence[Tuple[int, int]]] = Non
             if do_check:
                 torch.cuda.synchronize()
             for (bb, hh), o in heads.items():
-                o.append_and_score(_vec(inp.qd[t, bb, hh]), _vec(inp.kd[t, bb, hh]), _vec(inp.vd[t, bb, hh]),
+                o.append_and_score(q_of(inp.qd[t], bb, hh), _vec(inp.kd[t, bb, hh]), _vec(inp.vd[t, bb, hh]),
                                    new_pos[bb])
                 if do_check:
                     n = n_before[bb]

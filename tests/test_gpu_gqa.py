@@ -1,0 +1,224 @@
+"""GPU parity for grouped-query attention: g query heads per K/V head, token score = mean over the
+group of the heads' attention (paper, Limitations section, paragraph on GQA)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import parity
+import vatp_synth as vs
+from oracle import vatp_oracle as orc
+import paper_2406_12335_amd as vatp
+from paper_2406_12335_amd import binding as B
+from paper_2406_12335_amd.runner import PrunedKVCache
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+CASES = [
+    # dtype, d, K/V heads, g, prompt length, batch
+    ("fp32", 64, 2, 2, 200, 1),
+    ("bf16", 128, 2, 4, 333, 1),        # matrix-core passes, 8-wavefront workgroups, ragged last block
+    ("bf16", 128, 3, 3, 700, 2),        # a group size that is not a power of two
+    ("bf16", 128, 40, 8, 520, 1),       # 4-wavefront workgroups in both passes
+    ("bf16", 64, 2, 8, 150, 1),
+    ("fp32", 128, 1, 5, 97, 2),
+]
+
+
+@pytest.mark.parametrize("fused", [False, True])
+@pytest.mark.parametrize("dtype,d,H,g,L,b", CASES)
+def test_grouped_query_trajectories(gpu_device, dtype, d, H, g, L, b, fused):
+    cfg = vs.scaled(vs.CONFIGS["llama7b_layer"], batch=b, n_heads=H, head_dim=d, prompt_len=L, dtype=dtype,
+                    budget_pct=40, recent=16, decode_steps=10, q_per_kv=g)
+    inp = vs.make_inputs(cfg, seed=200 + g)
+    units = [(bb, hh) for bb in range(b) for hh in sorted({0, H // 2, H - 1})]
+    _say("gqa %s d=%d H=%d g=%d L=%d b=%d fused=%s" % (dtype, d, H, g, L, b, fused))
+    rep = parity.run_trajectory(inp, gpu_device, units=units, fused=fused)
+    _say("report %r" % rep)
+    assert rep.prune_events == len(units) * 11
+
+
+def test_grouped_query_ragged_batch(gpu_device):
+    cfg = vs.scaled(vs.CONFIGS["ragged16"], batch=4, n_heads=2, ragged=(40, 600), recent=8, decode_steps=6, q_per_kv=4)
+    inp = vs.make_inputs(cfg, seed=3)
+    _say("gqa ragged lens=%s" % inp.lens)
+    for fused in (False, True):
+        rep = parity.run_trajectory(inp, gpu_device, fused=fused)
+        _say("report %r" % rep)
+
+
+@pytest.mark.parametrize("dtype,d,g", [("bf16", 128, 4), ("fp32", 64, 3)])
+def test_fused_step_is_bit_identical_to_separate_calls_with_groups(gpu_device, dtype, d, g):
+    H, L, T = 3, 300, 12
+    cfg = vs.scaled(vs.CONFIGS["llama7b_layer"], n_heads=H, head_dim=d, prompt_len=L, dtype=dtype, budget_pct=30,
+                    recent=8, decode_steps=T, q_per_kv=g)
+    inp = vs.make_inputs(cfg, seed=77)
+    dev = gpu_device
+    _say("gqa fused vs separate %s d=%d g=%d" % (dtype, d, g))
+    Q, K, V = inp.Q.to(dev), inp.K.to(dev), inp.V.to(dev)
+    qd, kd, vd = inp.qd.to(dev), inp.kd.to(dev), inp.vd.to(dev)
+    caches = [PrunedKVCache(1, H, d, cfg.torch_dtype(), 2, cfg.recent, inp.budgets, dev, q_per_kv=g) for _ in range(2)]
+    try:
+        for c in caches:
+            c.prefill_score(Q, K, V, inp.lens)
+            c.prune_prompt(K, V)
+        for t in range(T):
+            caches[0].decode_step(qd[t], kd[t], vd[t], [L + t])
+            caches[0].prune()
+            caches[1].decode_prune_step(qd[t], kd[t], vd[t], [L + t])
+            torch.cuda.synchronize()
+            n = caches[0].lens[0]
+            assert caches[1].lens[0] == n
+            a, b = caches[0], caches[1]
+            for name in ("K", "V", "S", "nrm", "pos"):
+                assert torch.equal(getattr(a, name)[a.cur][:, :, :n], getattr(b, name)[b.cur][:, :, :n]), (name, t)
+            assert torch.equal(a.kept_idx[:, :, :n], b.kept_idx[:, :, :n])
+    finally:
+        for c in caches:
+            c.close()
+
+
+def test_group_of_one_is_plain_multi_head_attention(gpu_device):
+    """q_per_kv = 1 and q_per_kv = 0 (unset) give the same bits."""
+    cfg = vs.scaled(vs.CONFIGS["llama7b_layer"], n_heads=2, prompt_len=260, decode_steps=3)
+    inp = vs.make_inputs(cfg, seed=5)
+    dev = gpu_device
+    _say("gqa g=1 identity")
+    ctx = vatp.vatp_create(0)
+    try:
+        outs = []
+        for g in (0, 1):
+            p = vatp.Params(1, 2, 128, torch.bfloat16, 2, 8, 260, inp.lens, None, q_per_kv=g)
+            ws = torch.empty(vatp.vatp_workspace_bytes(ctx, p, vatp.CALL_PREFILL_SCORE), dtype=torch.uint8, device=dev)
+            S = torch.zeros(1, 2, 260, device=dev)
+            nrm = torch.zeros(1, 2, 260, device=dev)
+            vatp.vatp_prefill_score(ctx, p, inp.Q.to(dev), inp.K.to(dev), inp.V.to(dev), S, nrm, ws)
+            torch.cuda.synchronize()
+            outs.append((S.cpu(), nrm.cpu()))
+        assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+    finally:
+        vatp.vatp_destroy(ctx)
+
+
+@pytest.mark.parametrize("dtype,d,g,n0s", [("bf16", 128, 4, [1500, 0, 130]), ("fp32", 64, 3, [300, 127]), ("bf16", 64, 8, [257, 5]),
+                                           ("fp32", 128, 2, [129, 64])])
+def test_grouped_decode_step_with_attention_output(gpu_device, dtype, d, g, n0s):
+    """vatp_decode_attend_step with groups: every query head gets its own attention output (Eq. 1) over the
+    rows of its K/V head; the scores grow by the group mean of the heads' weights."""
+    H, b = 2, len(n0s)
+    tdt = torch.float32 if dtype == "fp32" else torch.bfloat16
+    cap = max(n0s) + 1
+    gen = torch.Generator().manual_seed(91)
+    K = (torch.randn(b, H, cap, d, generator=gen) * 1.2).to(tdt)
+    V = (torch.randn(b, H, cap, d, generator=gen) * torch.exp(0.5 * torch.randn(b, H, cap, 1, generator=gen))).to(tdt)
+    S0 = torch.rand(b, H, cap, generator=gen) + 0.1
+    q = (torch.randn(b, H * g, d, generator=gen) * 1.5).to(tdt)
+    k, v = ((torch.randn(b, H, d, generator=gen) * 1.5).to(tdt) for _ in range(2))
+    _say("gqa attend %s d=%d g=%d n0=%s" % (dtype, d, g, n0s))
+    dev = gpu_device
+    ctx = vatp.vatp_create(0)
+    try:
+        p = vatp.Params(b, H, d, tdt, 0, 0, cap, n0s, None, q_per_kv=g)
+        res = []
+        for attend in (False, True):
+            Kd, Vd, Sd = K.to(dev).clone(), V.to(dev).clone(), S0.to(dev).clone()
+            Nd = torch.zeros(b, H, cap, device=dev)
+            out = torch.full((b, H * g, d), 9.0, device=dev)
+            call = vatp.CALL_DECODE_ATTEND_STEP if attend else vatp.CALL_DECODE_STEP
+            ws = torch.empty(vatp.vatp_workspace_bytes(ctx, p, call), dtype=torch.uint8, device=dev)
+            if attend:
+                vatp.vatp_decode_attend_step(ctx, p, q.to(dev), k.to(dev), v.to(dev), Kd, Vd, Sd, Nd, None, None, out, ws)
+            else:
+                vatp.vatp_decode_step(ctx, p, q.to(dev), k.to(dev), v.to(dev), Kd, Vd, Sd, Nd, None, None, ws)
+            torch.cuda.synchronize()
+            res.append((Kd.cpu(), Vd.cpu(), Sd.cpu(), Nd.cpu(), out.cpu()))
+    finally:
+        vatp.vatp_destroy(ctx)
+    rtol = parity.rtol_for(tdt)
+    (Ka, Va, Sa, Na, _), (Kb, Vb, Sb, Nb, out) = res
+    for bb, n0 in enumerate(n0s):
+        n = n0 + 1
+        assert torch.equal(Ka[bb, :, :n], Kb[bb, :, :n]) and torch.equal(Va[bb, :, :n], Vb[bb, :, :n])
+        assert torch.equal(Sa[bb, :, :n], Sb[bb, :, :n]) and torch.equal(Na[bb, :, n0], Nb[bb, :, n0])
+        for h in range(H):
+            Kfull = torch.cat([K[bb, h, :n0], k[bb, h][None]], 0).double().numpy()
+            Vfull = torch.cat([V[bb, h, :n0], v[bb, h][None]], 0).double().numpy()
+            assert torch.equal(Kb[bb, h, n0], k[bb, h]) and torch.equal(Vb[bb, h, n0], v[bb, h])
+            S_start = np.concatenate([S0[bb, h, :n0].double().numpy(), np.zeros(1)])
+            S_want, _ = orc.decode_scores_group(q[bb, h * g:(h + 1) * g].double().numpy(), Kfull, S_start)
+            parity.assert_scores_close(Sb[bb, h, :n].numpy(), S_want, rtol, "grouped decode S (%d,%d)" % (bb, h))
+            for r in range(g):
+                want, scale = orc.attention_output(q[bb, h * g + r].double().numpy(), Kfull, Vfull)
+                err = np.abs(out[bb, h * g + r].double().numpy() - want)
+                assert np.all(err <= rtol * scale + 1e-12), "attention output head (%d,%d,%d): max err %.3g" % (
+                    bb, h, r, err.max())
+
+
+@pytest.mark.parametrize("dtype,d,g,lens", [("bf16", 128, 4, [700, 64, 257]), ("fp32", 64, 2, [130, 1, 99])])
+def test_grouped_prompt_scores_from_given_row_lse(gpu_device, dtype, d, g, lens):
+    H = 2
+    cfg = vs.scaled(vs.CONFIGS["llama7b_layer"], batch=len(lens), n_heads=H, head_dim=d, dtype=dtype,
+                    prompt_len=max(lens), decode_steps=0, q_per_kv=g)
+    inp = vs.make_inputs(cfg, seed=62)
+    inp.lens = lens
+    _say("gqa lse-in %s d=%d g=%d lens=%s" % (dtype, d, g, lens))
+    cap = max(lens)
+    lse = torch.zeros(len(lens), H * g, cap)
+    want = {}
+    for b, L in enumerate(lens):
+        for h in range(H):
+            Kh = inp.K[b, h, :L].double().numpy()
+            acc = np.zeros(L)
+            for r in range(g):
+                Qh = inp.Q[b, h * g + r, :L].double().numpy()
+                lse[b, h * g + r, :L] = torch.from_numpy(orc.row_lse(Qh, Kh)).float()
+                acc += orc.prefill_scores_given_lse(Qh, Kh, lse[b, h * g + r, :L].double().numpy())
+            want[(b, h)] = acc / g
+    dev = gpu_device
+    ctx = vatp.vatp_create(0)
+    try:
+        p = vatp.Params(len(lens), H, d, cfg.torch_dtype(), 0, 0, cap, lens, None, q_per_kv=g)
+        ws = torch.empty(max(256, vatp.vatp_workspace_bytes(ctx, p, vatp.CALL_PREFILL_SCORE)), dtype=torch.uint8, device=dev)
+        S = torch.full((len(lens), H, cap), -3.0, device=dev)
+        nrm = torch.full((len(lens), H, cap), -3.0, device=dev)
+        vatp.vatp_prefill_score_lse(ctx, p, inp.Q.to(dev), inp.K.to(dev), inp.V.to(dev), lse.to(dev), S, nrm, ws)
+        torch.cuda.synchronize()
+    finally:
+        vatp.vatp_destroy(ctx)
+    rtol = parity.rtol_for(cfg.torch_dtype())
+    for b, L in enumerate(lens):
+        for h in range(H):
+            parity.assert_scores_close(S[b, h, :L].cpu().numpy(), want[(b, h)], rtol, "grouped S from lse (%d,%d)" % (b, h))
+            parity.assert_scores_close(nrm[b, h, :L].cpu().numpy(), orc.l1norm(inp.V[b, h, :L].double().numpy()), rtol, "nrm")
+        assert torch.all(S[b, :, L:] == -3.0)
+
+
+def test_group_size_limits_and_window_calls_are_rejected(gpu_device):
+    lens, bud = [100], [50]
+    for g, call, want in [(9, vatp.CALL_PREFILL_SCORE, B.E_SHAPE), (-1, vatp.CALL_DECODE_STEP, B.E_SHAPE),
+                          (2, vatp.CALL_PREFILL_SCORE_WINDOW, B.E_SHAPE), (8, vatp.CALL_PREFILL_SCORE, B.OK),
+                          (8, vatp.CALL_DECODE_PRUNE_STEP, B.E_BUDGET)]:
+        p = vatp.Params(1, 4, 128, torch.bfloat16, 2, 8, 128, lens, bud, q_per_kv=g)
+        assert vatp.vatp_validate(p, call) == want, (g, call)
+    with pytest.raises(ValueError):
+        PrunedKVCache(1, 2, 128, torch.bfloat16, 2, 8, [50], gpu_device, window=10, q_per_kv=2)
+    # too many query heads in one call
+    p = vatp.Params(64, 64, 128, torch.bfloat16, 0, 0, 16, [8] * 64, None, q_per_kv=8)
+    assert vatp.vatp_validate(p, vatp.CALL_PREFILL_SCORE) == B.E_SHAPE
+
+
+def test_grouped_queries_at_model_size(gpu_device):
+    """8 K/V heads x 4 query heads each, head dimension 128, 4096 prompt tokens (the attention shape of current
+    8B-class models with grouped queries), sampled units, fused decode steps."""
+    cfg = vs.scaled(vs.CONFIGS["llama7b_layer"], n_heads=8, q_per_kv=4, decode_steps=16)
+    inp = vs.make_inputs(cfg, seed=11, device=gpu_device)
+    _say("gqa model size: 8 x 4 heads, L=4096")
+    rep = parity.run_trajectory(inp, gpu_device, units=[(0, 0), (0, 5)], fused=True, check_every=4)
+    _say("report %r" % rep)

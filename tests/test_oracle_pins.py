@@ -493,6 +493,13 @@ def test_group_of_one_and_group_of_equal_heads_reduce_to_a_single_head():
     np.testing.assert_array_equal(orc.prefill_scores_group(Q[None], K), S1)
     np.testing.assert_array_equal(orc.prefill_scores_group(np.stack([Q] * 4), K), S1)     # (4x)/4 is exact
     np.testing.assert_allclose(orc.prefill_scores_group(np.stack([Q] * 3), K), S1, rtol=1e-15)
+    # the many-heads form is the same function, unit by unit (ragged lengths included)
+    Qg = _rand(rng, 3, 2, L, d)
+    Ku = _rand(rng, 3, L, d)
+    lens = [L, 17, 1]
+    many = orc.prefill_scores_group_units(Qg, Ku, lens)
+    for u, n in enumerate(lens):
+        np.testing.assert_array_equal(many[u, :n], orc.prefill_scores_group(Qg[u, :, :n], Ku[u, :n]))
 
 
 def test_group_mean_is_taken_after_each_heads_softmax():

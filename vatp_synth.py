@@ -19,6 +19,8 @@ Recipe, per (batch, head) unit, with g* ~ N(0,1) i.i.d.:
   * sink values   v_s = 0.01 gV_s
   * other values  v_i = gV_i * exp(sigma z_i), z_i ~ N(0,1)   (lognormal row scale)
   * other keys    k_i = gK_i
+With grouped queries (q_per_kv = g > 1: g query heads per K/V head) every query head has its
+own u, and qbar of a sink key is the mean over its group's query heads.
 Everything is drawn in fp32 on the requested device from a torch.Generator seeded with
 (seed, layer), then rounded once (round-to-nearest-even) to the storage dtype.
 """
@@ -46,6 +48,7 @@ class VatpConfig:
     recent: int                # R
     decode_steps: int          # T
     ragged: Optional[tuple] = None   # (lo, hi) inclusive prompt-length range
+    q_per_kv: int = 1                # query heads per K/V head (n_heads counts K/V heads); > 1: grouped queries
 
     @property
     def n_sink_keep(self) -> int:
@@ -90,10 +93,10 @@ class VatpInputs:
     lens: List[int]            # prompt length per sequence
     budgets: List[int]         # B per sequence
     cap: int                   # rows allocated per (b, h) in Q/K/V
-    Q: torch.Tensor            # [b, H, cap, d]   prompt queries (rows >= len are zero)
+    Q: torch.Tensor            # [b, H * q_per_kv, cap, d]   prompt queries (rows >= len are zero)
     K: torch.Tensor            # [b, H, cap, d]
     V: torch.Tensor            # [b, H, cap, d]
-    qd: torch.Tensor           # [T, b, H, d]     decode-step queries
+    qd: torch.Tensor           # [T, b, H * q_per_kv, d]     decode-step queries
     kd: torch.Tensor           # [T, b, H, d]
     vd: torch.Tensor           # [T, b, H, d]
 
@@ -114,12 +117,13 @@ def make_inputs(cfg: VatpConfig, seed: int = 0, layer: int = 0,
     def randn(*shape):
         return torch.randn(*shape, generator=g, device=device, dtype=torch.float32)
 
-    u = randn(b, H, 1, d)
+    Hq = H * cfg.q_per_kv             # query heads: head h * q_per_kv + r attends to K/V head h
+    u = randn(b, Hq, 1, d)
     u = u / u.norm(dim=-1, keepdim=True)
 
-    Q = randn(b, H, cap, d)
+    Q = randn(b, Hq, cap, d)
     Q.add_(4.0 * u)
-    qd = randn(T, b, H, d)
+    qd = randn(T, b, Hq, d)
     qd.add_(4.0 * u.squeeze(2).unsqueeze(0))
     K = randn(b, H, cap, d)
     kd = randn(T, b, H, d)
@@ -139,7 +143,9 @@ def make_inputs(cfg: VatpConfig, seed: int = 0, layer: int = 0,
 
     ns = cfg.n_sinks
     if ns > 0:
-        qbar = Q.sum(dim=2, keepdim=True) / lens_t.to(torch.float32)        # [b,H,1,d]
+        qbar = Q.sum(dim=2, keepdim=True) / lens_t.to(torch.float32)        # [b,Hq,1,d]
+        if cfg.q_per_kv > 1:                                                 # a sink key serves its whole group
+            qbar = qbar.view(b, H, cfg.q_per_kv, 1, d).mean(dim=2)
         sink = (8.0 * math.sqrt(d)) * qbar / (qbar * qbar).sum(dim=-1, keepdim=True)
         K[:, :, :ns, :] = sink
 
