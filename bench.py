@@ -30,12 +30,13 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3
 
 
 def algorithmic_flops_prefill(cfg, lens, window=None):
-    """Both scoring passes, causal lower triangle only: 2 passes * 2*d flops per (query, key<=query) pair;
-    with a history window only the last window+1 query rows count."""
+    """Both scoring passes, causal lower triangle only: 2 passes * 2*d flops per (query, key<=query) pair and
+    query head (n_heads counts K/V heads, each with q_per_kv query heads); with a history window only the last
+    window+1 query rows count."""
     def pairs(L):
         first = 0 if window is None else max(0, L - 1 - window)
         return (L * (L + 1) - first * (first + 1)) // 2
-    return sum(cfg.n_heads * 2 * 2 * cfg.head_dim * pairs(L) for L in lens) * cfg.layers
+    return sum(cfg.n_heads * cfg.q_per_kv * 2 * 2 * cfg.head_dim * pairs(L) for L in lens) * cfg.layers
 
 
 def algorithmic_bytes_decode(cfg, n_rows, budget):
@@ -82,7 +83,8 @@ def run(args):
         cfg = vs.scaled(cfg, layers=args.layers)
     if args.decode_steps is not None:
         cfg = vs.scaled(cfg, decode_steps=args.decode_steps)
-    for field, value in (("batch", args.batch), ("budget_pct", args.budget_pct), ("recent", args.recent)):
+    for field, value in (("batch", args.batch), ("budget_pct", args.budget_pct), ("recent", args.recent),
+                         ("n_heads", args.heads), ("q_per_kv", args.q_per_kv)):
         if value is not None:
             cfg = vs.scaled(cfg, **{field: value})
     T = cfg.decode_steps
@@ -91,13 +93,16 @@ def run(args):
     if window is not None and not fused:
         print("bench.py: history-window scores run through the fused decode route only", file=sys.stderr)
         sys.exit(2)
+    if window is not None and cfg.q_per_kv > 1:
+        print("bench.py: history-window scores do not take grouped queries", file=sys.stderr)
+        sys.exit(2)
     layers = [vs.make_inputs(cfg, seed=args.seed, layer=l, device=dev) for l in range(cfg.layers)]
     lens, budgets = layers[0].lens, layers[0].budgets
     for inp in layers:      # per-step views of the new tokens, made once (indexing costs host time per call)
         inp.step_qkv = [(inp.qd[t], inp.kd[t], inp.vd[t]) for t in range(T)]
     ctx = vatp.vatp_create(0)
     caches = [PrunedKVCache(cfg.batch, cfg.n_heads, cfg.head_dim, cfg.torch_dtype(), cfg.n_sink_keep, cfg.recent,
-                            budgets, dev, ctx=ctx, window=window) for _ in layers]
+                            budgets, dev, ctx=ctx, window=window, q_per_kv=cfg.q_per_kv) for _ in layers]
     new_pos = [[L + t for L in lens] for t in range(T)]
 
     def one_step(ev=None):
@@ -331,6 +336,7 @@ def run(args):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if mfma else "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "batch": cfg.batch, "layers": cfg.layers, "n_heads": cfg.n_heads,
+                   "q_per_kv": cfg.q_per_kv,
                    "head_dim": cfg.head_dim, "prompt_len": lens if cfg.ragged else cfg.prompt_len,
                    "budget_pct": cfg.budget_pct, "recent": cfg.recent, "n_sink": cfg.n_sink_keep,
                    "decode_steps": T, "decode_route": args.decode_route, "score": "accumulated (Eq. 2)" if window is None
@@ -381,16 +387,22 @@ def cpu_baseline(cfg, inp, budget_s):
     H, d = cfg.n_heads, cfg.head_dim
     est_rate = 0.6e9 * threads                         # (query, key) pairs * d per second, rough
     Ls = L
-    while Ls > 256 and H * (Ls * Ls / 2) * d / est_rate > budget_s:
+    grp = cfg.q_per_kv
+    while Ls > 256 and grp * H * (Ls * Ls / 2) * d / est_rate > budget_s:
         Ls //= 2
     Q = inp.Q[0, :, :Ls].double().cpu().numpy()
     K = inp.K[0, :, :Ls].double().cpu().numpy()
     t0 = time.perf_counter()
-    orc.prefill_scores_units(Q, K, [Ls] * H)
+    if grp == 1:
+        orc.prefill_scores_units(Q, K, [Ls] * H)
+    else:
+        orc.prefill_scores_group_units(Q.reshape(H, grp, Ls, d), K, [Ls] * H)
     dt = time.perf_counter() - t0
     out = {"value": round(Ls / dt, 2), "unit": "tokens/s", "cores": threads, "kind": "oracle",
            "sample": "prompt scoring (both softmax passes of the float64 oracle), all %d heads of one layer, "
-                     "first %d of %d prompt tokens of sequence 0; %.2f s" % (H, Ls, L, dt)}
+                     "first %d of %d prompt tokens of sequence 0; %.2f s" % (H * grp, Ls, L, dt)}
+    if grp > 1:
+        return out          # (the oracle's many-heads decode routine takes one query per K/V head)
     # decode + prune at the steady-state cache size n = B + 1, a few steps, all heads of sequence 0
     n = min(B, L) + 1
     import ctypes
@@ -432,6 +444,9 @@ def main():
     ap.add_argument("--batch", type=int, default=None, help="override the batch size of the workload")
     ap.add_argument("--budget-pct", type=int, default=None, help="override the KV budget (percent of the prompt)")
     ap.add_argument("--recent", type=int, default=None, help="override the recent window R")
+    ap.add_argument("--heads", type=int, default=None, help="override the number of (K/V) heads of the workload")
+    ap.add_argument("--q-per-kv", type=int, default=None,
+                    help="grouped-query attention: query heads per K/V head (default 1, the paper's models)")
     ap.add_argument("--decode-route", default="fused", choices=["fused", "separate"],
                     help="fused: vatp_decode_prune_step; separate: vatp_decode_step + vatp_select_compact")
     ap.add_argument("--window", type=int, default=None,

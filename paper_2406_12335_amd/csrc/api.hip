@@ -143,8 +143,8 @@ size_t vatp_workspace_bytes(const vatp_ctx *, const vatp_params *p, int which_ca
     // everything kept in the workspace is per query head
     const size_t units = static_cast<size_t>(p->batch) * p->n_heads * (p->q_per_kv > 1 ? p->q_per_kv : 1);
     switch (which_call) {
-    case VATP_CALL_PREFILL_SCORE:           // lse2[units, cap]
-        return align_up(units * p->cap * sizeof(float));
+    case VATP_CALL_PREFILL_SCORE:           // lse2[units, cap] (+ as much again for partial column sums of a group)
+        return align_up(units * p->cap * sizeof(float)) * (p->q_per_kv > 1 ? 2 : 1);
     case VATP_CALL_PREFILL_SCORE_WINDOW:    // ... + partial row statistics per range of keys
         return align_up(units * p->cap * sizeof(float)) +
                align_up(static_cast<size_t>(prefill_window_splits(p->cap)) * units * p->cap * sizeof(float));
@@ -191,7 +191,8 @@ vatp_status prefill_score_impl(vatp_ctx *ctx, const vatp_params *p, const void *
     const bool mfma = p->dtype == VATP_BF16 && p->head_dim == 128;
     hipError_t e;
     if (mfma && window < 0) {                 // (the matrix-core column-sum pass writes the norms as well)
-        e = launch_prefill_mfma(Q, K, V, S, nrm, lse2, have_lse, pr.meta, pr.g, stream);
+        float *s_part = pr.g.group > 1 ? lse2 + align_up(units * pr.g.group * p->cap * sizeof(float)) / sizeof(float) : nullptr;
+        e = launch_prefill_mfma(Q, K, V, S, nrm, lse2, s_part, have_lse, pr.meta, pr.g, stream);
     } else if (mfma && prefill_mfma_window_fits(window, p->cap, static_cast<int>(units))) {
         e = launch_prefill_mfma_window(Q, K, V, S, nrm, lse2,
                                        lse2 + align_up(units * p->cap * sizeof(float)) / sizeof(float), window, hist,

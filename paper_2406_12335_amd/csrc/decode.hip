@@ -178,7 +178,8 @@ __global__ __launch_bounds__(256) void decode_logits_group_kernel(
     constexpr int kLanesPerRow = D / kE;
     constexpr int kRowsPerPass = 256 / kLanesPerRow;
     constexpr int kPasses = kDecodeChunk / kRowsPerPass;
-    constexpr int kGroup = kPasses < 16 ? kPasses : 16;        // loads issued back to back
+    constexpr int kGroup = kPasses;                            // all of a thread's row loads are issued back to back
+    static_assert(kGroup == kLanesPerRow / 2 && kGroup <= 16, "the butterfly below pairs rows with lanes");
 
     __shared__ float s_logit[kG][kDecodeChunk];
     __shared__ float s_max[kG];
@@ -196,10 +197,21 @@ __global__ __launch_bounds__(256) void decode_logits_group_kernel(
     const int rloc = tid / kLanesPerRow;
     const int lane = tid & 63, wave = tid >> 6;
 
+    // bf16 rows of 128 elements: the logits of a group are a (rows x 128) by (128 x g) product and go to the
+    // matrix cores (the chunk's rows staged in LDS, every wavefront one 32-row tile); other shapes use FMAs
+    constexpr bool kMfma = sizeof(T) == 2 && D == 128;
     uint4 q_raw[kG];
 #pragma unroll
-    for (int i = 0; i < kG; ++i)
-        q_raw[i] = i < group ? reinterpret_cast<const uint4 *>(q + (unit * group + i) * D)[sub] : make_uint4(0, 0, 0, 0);
+    for (int i = 0; i < kG; ++i) {
+        q_raw[i] = make_uint4(0, 0, 0, 0);
+        if constexpr (kMfma) {
+            // B operand of MFMA step i: this lane's 8 elements of query head lane & 31 (zero beyond the group)
+            if ((lane & 31) < group)
+                q_raw[i] = reinterpret_cast<const uint4 *>(q + (unit * group + (lane & 31)) * D)[i + 8 * (lane >> 5)];
+        } else {
+            if (i < group) q_raw[i] = reinterpret_cast<const uint4 *>(q + (unit * group + i) * D)[sub];
+        }
+    }
     const bool owns_new_row = n0 >= row0 && n0 < row0 + kDecodeChunk && tid < kLanesPerRow;
     uint4 kraw = make_uint4(0, 0, 0, 0), vraw = make_uint4(0, 0, 0, 0);
     if (owns_new_row) {
@@ -218,8 +230,10 @@ __global__ __launch_bounds__(256) void decode_logits_group_kernel(
             raw[u] = (r < n) ? *src : make_uint4(0, 0, 0, 0);
         }
         if (p0 == 0) {
+            if constexpr (!kMfma) {
 #pragma unroll
-            for (int i = 0; i < kG; ++i) Elt<T>::unpack(q_raw[i], qf[i]);
+                for (int i = 0; i < kG; ++i) Elt<T>::unpack(q_raw[i], qf[i]);
+            }
             if (owns_new_row) {                     // append k, v, |v| and pos
                 reinterpret_cast<uint4 *>(K + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = kraw;
                 reinterpret_cast<uint4 *>(V + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = vraw;
@@ -235,20 +249,66 @@ __global__ __launch_bounds__(256) void decode_logits_group_kernel(
                 }
             }
         }
+        if constexpr (kMfma) {
+            static_assert(!kMfma || (kG == 8 && kGroup == 8 && kLanesPerRow == 16), "8 MFMA steps of 16 over the 128 elements");
+            __shared__ uint4 s_k[kDecodeChunk * kLanesPerRow];
 #pragma unroll
-        for (int u = 0; u < kGroup; ++u) {
-            const int rl = (p0 + u) * kRowsPerPass + rloc;
-            float kf[kE];
-            Elt<T>::unpack(raw[u], kf);
+            for (int u = 0; u < kGroup; ++u) {
+                const int rl = u * kRowsPerPass + rloc;
+                s_k[rl * kLanesPerRow + swizzled_chunk(rl, sub)] = raw[u];
+            }
+            __syncthreads();
+            const int ln = lane & 31, gl = lane >> 5;
+            const int ar = 32 * wave + ln;             // this lane's row of the wavefront's tile
+            floatx16 acc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+            for (int st = 0; st < 8; ++st)
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    as_bf16x8(s_k[ar * kLanesPerRow + swizzled_chunk(ar, st + 8 * gl)]), as_bf16x8(q_raw[st]), acc, 0, 0, 0);
+            if (ln < group) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int rl = 32 * wave + acc_row(v) + 4 * gl;
+                    s_logit[ln][rl] = (row0 + rl < n) ? acc[v] * scale_log2 : -INFINITY;
+                }
+            }
+        } else {
+            float kf[kGroup][kE];
+#pragma unroll
+            for (int u = 0; u < kGroup; ++u) Elt<T>::unpack(raw[u], kf[u]);
 #pragma unroll
             for (int i = 0; i < kG; ++i) {
                 if (i >= group) continue;
-                float dot = 0.f;
+                // this lane's share of the dot products of head i with its kGroup rows ...
+                float part[kGroup];
 #pragma unroll
-                for (int e = 0; e < kE; ++e) dot = fmaf(qf[i][e], kf[e], dot);
+                for (int u = 0; u < kGroup; ++u) {
+                    part[u] = 0.f;
 #pragma unroll
-                for (int off = kLanesPerRow / 2; off > 0; off >>= 1) dot += __shfl_xor(dot, off);
-                if (sub == 0) s_logit[i][rl] = (row0 + rl < n) ? dot * scale_log2 : -INFINITY;
+                    for (int e = 0; e < kE; ++e) part[u] = fmaf(qf[i][e], kf[u][e], part[u]);
+                }
+                // ... summed over the row's lanes by a butterfly that halves the number of rows a lane is
+                // responsible for at every step (the lane with the offset bit set keeps the upper half and
+                // hands over the lower one): kGroup - 1 exchanges instead of kGroup * log2(lanes per row).
+                // The lane ends up with the whole sum of row sub / 2.
+#pragma unroll
+                for (int off = kLanesPerRow / 2; off >= 2; off >>= 1) {
+                    const int half = off / 2;
+                    const bool upper = (sub & off) != 0;
+#pragma unroll
+                    for (int j = 0; j < half; ++j) {
+                        const float send = upper ? part[j] : part[j + half];
+                        const float keep = upper ? part[j + half] : part[j];
+                        part[j] = keep + __shfl_xor(send, off);
+                    }
+                }
+                part[0] += __shfl_xor(part[0], 1);
+                if ((sub & 1) == 0) {
+                    const int rl = (p0 + (sub >> 1)) * kRowsPerPass + rloc;
+                    s_logit[i][rl] = (row0 + rl < n) ? part[0] * scale_log2 : -INFINITY;
+                }
             }
         }
     }
@@ -401,12 +461,14 @@ hipError_t launch_decode(int dtype, int head_dim, const void *q, const void *k, 
 #undef VATP_DEC
     if (finish) {   // (the fused decode-and-evict step has its own second launch)
         const dim3 fgrid(units, (g.max_len + 255) / 256);
-        if (g.group > 1)
-            hipLaunchKernelGGL(decode_finish_kernel<VATP_MAX_GROUP>, fgrid, block, 0, st, S, ws_logit, ws_part, ws_out,
-                               out, head_dim, meta, g.n_heads, g.cap, chunks_alloc, g.group);
-        else
-            hipLaunchKernelGGL(decode_finish_kernel<1>, fgrid, block, 0, st, S, ws_logit, ws_part, ws_out, out,
-                               head_dim, meta, g.n_heads, g.cap, chunks_alloc, 1);
+#define VATP_FIN(G)                                                                                               \
+    hipLaunchKernelGGL(decode_finish_kernel<G>, fgrid, block, 0, st, S, ws_logit, ws_part, ws_out, out, head_dim, meta, \
+                       g.n_heads, g.cap, chunks_alloc, g.group)
+        if (g.group > 4) VATP_FIN(VATP_MAX_GROUP);
+        else if (g.group > 2) VATP_FIN(4);
+        else if (g.group > 1) VATP_FIN(2);
+        else VATP_FIN(1);
+#undef VATP_FIN
     }
     return hipGetLastError();
 }

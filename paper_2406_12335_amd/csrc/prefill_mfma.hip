@@ -54,8 +54,6 @@ namespace vatp {
 
 namespace {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 typedef __attribute__((address_space(3))) char lds_char;
 
 constexpr int kD = 128;            // head_dim
@@ -75,13 +73,6 @@ constexpr int kStageBytes = kStage * kD * 2; // 16 KiB
 #endif
 constexpr int kLeadValu = VATP_LEAD_VALU;    // vector instructions asked for between the LDS reads and the first MFMA
 constexpr int kSlotValu = VATP_SLOT_VALU;    // vector instructions asked for after every MFMA
-
-__device__ __forceinline__ int swizzled_chunk(int row, int c) { return c ^ (row & 15); }
-
-__device__ __forceinline__ bf16x8 as_bf16x8(const uint4 &u) { return __builtin_bit_cast(bf16x8, u); }
-
-// Row offset inside a 32-row block of accumulator register v (lane half g adds 4g).
-__device__ __forceinline__ constexpr int acc_row(int v) { return 8 * (v / 4) + (v % 4); }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -223,7 +214,7 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
                                                            int n_heads, int n_units, int cap,
                                                            int n_blocks, float scale_log2, WindowPass win,
                                                            const bf16_t *__restrict__ V, float *__restrict__ nrm,
-                                                           int norm, int group)
+                                                           int norm, int group, int splits)
 {
     static_assert(!kWindow || kHalves == 1, "the windowed passes use 4-wavefront workgroups");
     static_assert(!kGrouped || (kColsum && !kWindow), "only the plain column-sum pass loops over a group's query heads");
@@ -243,9 +234,13 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
     // pulled into one XCD's L2 once instead of into all eight.
     const int n_pairs = kSplitKeys ? win.n_qb * win.n_splits : (n_blocks + 1) / 2;
     const int xcd = blockIdx.x & 7, in_xcd = blockIdx.x >> 3;
-    const int unit_i = xcd + 8 * (in_xcd / n_pairs);
+    const int slot_i = xcd + 8 * (in_xcd / n_pairs);
     const int pair = in_xcd % n_pairs;
-    if (unit_i >= n_units) return;
+    if (slot_i >= n_units) return;
+    // (grouped column sums on a small grid: `splits` workgroups share a K/V head, each taking group / splits
+    // of its query heads and leaving a partial column sum; n_units then counts K/V heads x splits)
+    const int unit_i = kGrouped ? slot_i / splits : slot_i;
+    const int split = kGrouped ? slot_i % splits : 0;
     const int b = unit_i / n_heads;
     const int len = meta.len[b];
     const int q_first = kWindow ? max(0, len - 1 - win.window) : 0;     // first query row that counts
@@ -301,7 +296,7 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
     const bool extra_copy = kColsum && cw == 0;
     // A job is one block of stationary rows; with grouped queries it is walked once per query head
     // (`run` and the stationary operand live on from one head to the next).
-    const int n_qh = kGrouped ? group : 1;
+    const int n_qh = kGrouped ? group / splits : 1;
     bf16x8 Bf[2][8] = {};
     Running<kColsum> run;
     for (int it = 0, n_it = (kSplitKeys ? 1 : 2) * n_qh; it < n_it; ++it) {
@@ -324,8 +319,8 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
         }
 
         if constexpr (kGrouped) {
-            strm = strm0 + static_cast<size_t>(qh) * cap * kD;
-            lse_u = lse_u0 + static_cast<size_t>(qh) * cap;
+            strm = strm0 + static_cast<size_t>(split * n_qh + qh) * cap * kD;
+            lse_u = lse_u0 + static_cast<size_t>(split * n_qh + qh) * cap;
         }
 #pragma unroll
         for (int k = 0; k < kAhead; ++k)
@@ -334,7 +329,7 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
         // The column-sum pass visits every block of keys once: it also leaves the norm of the value rows
         // of its block (paper Eq. 4), 64 rows per wavefront, while the first stages are on their way.
         if constexpr (kColsum) {
-            if (V != nullptr && half == 0 && qh == 0) {
+            if (V != nullptr && half == 0 && qh == 0 && split == 0) {
                 const uint4 *Vu = reinterpret_cast<const uint4 *>(V + unit * cap * kD);
                 float *nu = nrm + unit * cap;
                 switch (norm) {
@@ -566,6 +561,8 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
                         win.lse_part[(static_cast<size_t>(pair % win.n_splits) * n_units + unit) * cap + idx] =
                             fin_m[cb] + __log2f(fin_l[cb]);
                     else if (!kColsum) lse_u[idx] = fin_m[cb] + __log2f(fin_l[cb]);
+                    else if (kGrouped && splits > 1)     // partial sum [split, K/V head, cap], mean taken by the merge kernel
+                        S[(static_cast<size_t>(split) * (n_units / splits) + unit) * cap + idx] = fin_l[cb];
                     else S[unit * cap + idx] = kGrouped ? fin_l[cb] * inv_group : fin_l[cb];
                 }
             }
@@ -642,18 +639,35 @@ hipError_t launch_prefill_mfma_window(const void *Q, const void *K, const void *
     const int window_blocks = (window + 1 + kBlockCols - 1) / kBlockCols + 1;     // blocks a window can straddle
     win.n_qb = window_blocks < n_blocks ? window_blocks : n_blocks;
     hipLaunchKernelGGL((prefill_mfma_kernel<false, 1, true>), dim3(8u * win.n_qb * win.n_splits * unit_groups), dim3(256),
-                       0, st, q, k, lse2, S, meta, g.n_heads, n_units, g.cap, n_blocks, g.scale_log2, win, nullptr, nullptr, 0, 1);
+                       0, st, q, k, lse2, S, meta, g.n_heads, n_units, g.cap, n_blocks, g.scale_log2, win, nullptr, nullptr, 0, 1, 1);
     const int merge_rows = window + 1 + kStage;
     hipLaunchKernelGGL(merge_split_lse_kernel, dim3((merge_rows + 255) / 256, n_units), dim3(256), 0, st, lse_part, lse2,
                        meta, g.n_heads, n_units, g.cap, window, win.n_splits);
     hipLaunchKernelGGL((prefill_mfma_kernel<true, 1, true>), dim3(8u * ((n_blocks + 1) / 2) * unit_groups), dim3(256), 0,
                        st, q, k, lse2, S, meta, g.n_heads, n_units, g.cap, n_blocks, g.scale_log2, win,
-                       static_cast<const bf16_t *>(V), nrm, g.norm, 1);
+                       static_cast<const bf16_t *>(V), nrm, g.norm, 1, 1);
     return hipGetLastError();
 }
 
+namespace {
+
+// S = (1/g) * sum over the splits of the partial column sums a grouped column-sum pass left
+__global__ __launch_bounds__(256) void merge_group_partials_kernel(const float *__restrict__ part, float *__restrict__ S,
+                                                                   BatchMeta meta, int n_heads, int n_units, int cap,
+                                                                   int splits, float inv_group)
+{
+    const size_t unit = blockIdx.y;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= meta.len[unit / n_heads]) return;
+    float s = 0.f;
+    for (int k = 0; k < splits; ++k) s += part[(static_cast<size_t>(k) * n_units + unit) * cap + i];
+    S[unit * cap + i] = s * inv_group;
+}
+
+}  // namespace
+
 hipError_t launch_prefill_mfma(const void *Q, const void *K, const void *V, float *S, float *nrm, float *lse2,
-                               bool have_lse, const BatchMeta &meta, const Geometry &g, hipStream_t st)
+                               float *s_part, bool have_lse, const BatchMeta &meta, const Geometry &g, hipStream_t st)
 {
     if (g.max_len <= 0) return hipSuccess;
     const int n_blocks = (g.max_len + kBlockCols - 1) / kBlockCols;
@@ -665,27 +679,43 @@ hipError_t launch_prefill_mfma(const void *Q, const void *K, const void *V, floa
     // 4-wavefront workgroups per compute unit when the grid is large enough to keep pairs of them
     // resident, else 8-wavefront workgroups.
     const int kv_units = g.batch * g.n_heads, q_units = kv_units * g.group;
-    const unsigned wg_q = 8u * n_pairs * ((q_units + 7) / 8), wg_kv = 8u * n_pairs * ((kv_units + 7) / 8);
+    const unsigned wg_q = 8u * n_pairs * ((q_units + 7) / 8);
     if (!have_lse) {    // row statistics are computed here unless the caller supplied them
         if (wg_q >= 2u * kComputeUnits)
             hipLaunchKernelGGL((prefill_mfma_kernel<false, 1>), dim3(wg_q), dim3(256), 0, st, q, k, lse2, S, meta,
                                g.n_heads * g.group, q_units, g.cap, n_blocks, g.scale_log2, WindowPass{}, nullptr,
-                               nullptr, 0, g.group);
+                               nullptr, 0, g.group, 1);
         else
             hipLaunchKernelGGL((prefill_mfma_kernel<false, 2>), dim3(wg_q), dim3(512), 0, st, q, k, lse2, S, meta,
                                g.n_heads * g.group, q_units, g.cap, n_blocks, g.scale_log2, WindowPass{}, nullptr,
-                               nullptr, 0, g.group);
+                               nullptr, 0, g.group, 1);
     }
+    // Grouped column sums: a K/V head's query heads are walked by one workgroup (no partial sums) when that
+    // still fills the chip; otherwise they are dealt out to `splits` workgroups -- the smallest divisor of
+    // the group size that does -- whose partial sums a small kernel adds.
+    int splits = 1;
+    if (g.group > 1 && s_part != nullptr)
+        for (int s = 1; s <= g.group; ++s)
+            if (g.group % s == 0) {
+                splits = s;
+                if (8u * n_pairs * ((kv_units * s + 7) / 8) >= 2u * kComputeUnits) break;
+            }
+    const int slots = kv_units * splits;
+    const unsigned wg_kv = 8u * n_pairs * ((slots + 7) / 8);
+    float *dst = splits > 1 ? s_part : S;
 #define VATP_COLSUM(HALVES, GROUPED)                                                                              \
     hipLaunchKernelGGL((prefill_mfma_kernel<true, HALVES, false, GROUPED>), dim3(wg_kv), dim3(256 * HALVES), 0, st, q, k, \
-                       lse2, S, meta, g.n_heads, kv_units, g.cap, n_blocks, g.scale_log2, WindowPass{}, v, nrm, g.norm, \
-                       g.group)
+                       lse2, dst, meta, g.n_heads, slots, g.cap, n_blocks, g.scale_log2, WindowPass{}, v, nrm, g.norm,   \
+                       g.group, splits)
     if (wg_kv >= 2u * kComputeUnits) {
         if (g.group > 1) VATP_COLSUM(1, true); else VATP_COLSUM(1, false);
     } else {
         if (g.group > 1) VATP_COLSUM(2, true); else VATP_COLSUM(2, false);
     }
 #undef VATP_COLSUM
+    if (splits > 1)
+        hipLaunchKernelGGL(merge_group_partials_kernel, dim3((g.max_len + 255) / 256, kv_units), dim3(256), 0, st, s_part, S,
+                           meta, g.n_heads, kv_units, g.cap, splits, 1.f / static_cast<float>(g.group));
     return hipGetLastError();
 }
 

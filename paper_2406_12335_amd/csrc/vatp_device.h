@@ -79,6 +79,18 @@ template <> struct Elt<bf16_t> {
     }
 };
 
+// ---- v_mfma_f32_32x32x16_bf16: operand and accumulator conventions shared by the kernels that use it.
+// Lane (n = lane & 31, g = lane >> 5) supplies, as A operand, 8 consecutive contraction elements of row n
+// of the 32 x 16 left matrix and, as B operand, of column n of the right one (which 8 of the 16 is free as
+// long as both operands agree); it receives column n of the 32 x 32 result, rows acc_row(v) + 4 g.
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+__device__ __forceinline__ bf16x8 as_bf16x8(const uint4 &u) { return __builtin_bit_cast(bf16x8, u); }
+__device__ __forceinline__ constexpr int acc_row(int v) { return 8 * (v / 4) + (v % 4); }
+// rows of 256 bytes staged in LDS: 16-byte chunk c of row r sits at chunk c ^ (r & 15), so that the 16 lanes
+// that read one chunk index of 16 consecutive rows hit 16 different bank groups
+__device__ __forceinline__ int swizzled_chunk(int row, int c) { return c ^ (row & 15); }
+
 // Softmax denominator of one decode step from the per-chunk statistics (max_c, sum_c of
 // 2^(t - max_c)) that the logits launch left behind: M = max_c max_c and
 // L = sum_c sum_c * 2^(max_c - M).  Every wavefront computes both by itself: lanes take chunks
@@ -195,8 +207,9 @@ hipError_t launch_lse_to_base2(const float *lse, float *lse2, const BatchMeta &m
                                hipStream_t st);
 
 // (the matrix-core passes also write the value-row norms: no separate launch_l1norm)
+// (s_part: room for group * units * cap floats of partial column sums when query heads are grouped, else unused)
 hipError_t launch_prefill_mfma(const void *Q, const void *K, const void *V, float *S, float *nrm, float *lse2,
-                               bool have_lse, const BatchMeta &meta, const Geometry &g, hipStream_t st);
+                               float *s_part, bool have_lse, const BatchMeta &meta, const Geometry &g, hipStream_t st);
 
 // history-window prompt scores on the matrix cores (bf16, head_dim 128); lse_part: workspace of
 // prefill_window_splits(cap) * units * cap floats; usable if prefill_mfma_window_fits(window, cap, units)
