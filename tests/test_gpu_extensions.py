@@ -112,3 +112,18 @@ def test_decode_step_with_attention_output(gpu_device, dtype, d, n0s):
             want, scale = orc.attention_output(q[b, h].double().numpy(), Kfull, Vfull)
             err = np.abs(out[b, h].double().numpy() - want)
             assert np.all(err <= rtol * scale + 1e-12), "attention output unit (%d,%d): max err %.3g" % (b, h, err.max())
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_per_head_budgets_by_passing_heads_as_sequences(gpu_device, fused):
+    """Non-uniform budgets across heads (the paper uses uniform ones and names the non-uniform strategy as the
+    alternative, Implementation Details): len and budget are per sequence, and a [b, H, cap, d] tensor is the same
+    memory as [b*H, 1, cap, d], so every head can be handed over as a sequence of its own with its own budget."""
+    H, L = 6, 300
+    cfg = vs.scaled(vs.CONFIGS["llama7b_layer"], batch=H, n_heads=1, prompt_len=L, budget_pct=50, recent=8, decode_steps=12)
+    inp = vs.make_inputs(cfg, seed=123)
+    inp.budgets = [40, 150, 75, 299, 310, 18]          # one per head; 310 > L: that head never prunes during the prompt
+    _say("per-head budgets %s fused=%s" % (inp.budgets, fused))
+    rep = parity.run_trajectory(inp, gpu_device, fused=fused)
+    _say("report %r" % rep)
+    assert rep.prune_events == H * 13
