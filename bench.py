@@ -369,10 +369,10 @@ def run(args):
 # (FETCH_SIZE x2.000, WRITE_SIZE x1.000); summaries under profiles/.  Keyed by (workload, layers).
 MEASURED_TRAFFIC_BYTES = {
     # calibrated fetch + write bytes per call of the entry point (all of its kernels)
-    ("llama7b_layer", 1): {"prefill_score": 185507511, "decode_step": 18051834, "select_compact": 72839821,
-                           "decode_prune_step": 21023422},
-    ("llama7b_stack", 2): {"prefill_score": 2075447204, "decode_step": 57730736, "select_compact": 233079038,
-                           "decode_prune_step": 70600000},
+    ("llama7b_layer", 1): {"prefill_score": 184034008, "decode_step": 18055946, "select_compact": 72839875,
+                           "decode_prune_step": 21056138},
+    ("llama7b_stack", 2): {"prefill_score": 2067373001, "decode_step": 57727981, "select_compact": 233069566,
+                           "decode_prune_step": 71390000},
 }
 
 
