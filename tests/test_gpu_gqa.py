@@ -222,3 +222,14 @@ def test_grouped_queries_at_model_size(gpu_device):
     _say("gqa model size: 8 x 4 heads, L=4096")
     rep = parity.run_trajectory(inp, gpu_device, units=[(0, 0), (0, 5)], fused=True, check_every=4)
     _say("report %r" % rep)
+
+
+def test_grouped_queries_at_model_size_batch8(gpu_device):
+    """The same shape at batch 8 (64 K/V heads: the column-sum pass walks each group's four query heads in one
+    workgroup, no partial sums), sampled units, both decode routes."""
+    cfg = vs.scaled(vs.CONFIGS["llama7b_layer"], batch=8, n_heads=8, q_per_kv=4, decode_steps=8)
+    inp = vs.make_inputs(cfg, seed=12, device=gpu_device)
+    _say("gqa model size, batch 8")
+    for fused in (True, False):
+        rep = parity.run_trajectory(inp, gpu_device, units=[(0, 0), (7, 7), (3, 4)], fused=fused, check_every=4)
+        _say("report %r" % rep)
