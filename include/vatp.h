@@ -15,6 +15,9 @@
  *     per-row scalars (S, nrm, pos) are [batch, n_heads, cap].  Heads keep different
  *     tokens after pruning, so every (batch, head) unit owns `cap` rows of its own.
  *     Rows [0, len[b]) of a unit are valid; the others are never read.
+ *     len and budget are per sequence; heads that need row counts or budgets of their own
+ *     (non-uniform budgets, Implementation Details appendix) are passed as sequences:
+ *     [batch, n_heads, ...] with n_heads = 1 and batch = sequences * heads is the same memory.
  *   - dtype covers Q, K, V and the caches; S and nrm are always float32, pos int32.
  *   - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = the null
  *     stream) and return without synchronising.  Errors that can be seen before launch
