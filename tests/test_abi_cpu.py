@@ -128,5 +128,7 @@ def test_validate_grouped_queries():
     # the workspace holds one set of logits / row statistics per query head
     p1 = B.Params(2, 4, 128, torch.bfloat16, 0, 0, 512, [100, 100], None)
     p4 = B.Params(2, 4, 128, torch.bfloat16, 0, 0, 512, [100, 100], None, q_per_kv=4)
-    for call in (B.CALL_PREFILL_SCORE, B.CALL_DECODE_STEP, B.CALL_DECODE_ATTEND_STEP):
+    for call in (B.CALL_DECODE_STEP, B.CALL_DECODE_ATTEND_STEP):
         assert B.vatp_workspace_bytes(None, p4, call) == 4 * B.vatp_workspace_bytes(None, p1, call)
+    # (the prompt pass also keeps room for partial column sums of a group: as much again)
+    assert B.vatp_workspace_bytes(None, p4, B.CALL_PREFILL_SCORE) == 8 * B.vatp_workspace_bytes(None, p1, B.CALL_PREFILL_SCORE)
