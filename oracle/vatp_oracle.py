@@ -200,6 +200,19 @@ def prefill_scores_group(Qg, K, c: Optional[float] = None) -> np.ndarray:
     return S / g
 
 
+def prefill_window_group(Qg, K, w: int, c: Optional[float] = None):
+    """prefill_window with g query heads on one K/V head: (S, P), both means over the group (Eq. 3 applied to
+    the group-averaged attention weights).  Qg: [g, L, d]."""
+    Qg = _f64(Qg)
+    g = Qg.shape[0]
+    S, P = prefill_window(Qg[0], K, w, c)
+    for r in range(1, g):
+        s_r, p_r = prefill_window(Qg[r], K, w, c)
+        S = S + s_r
+        P = P + p_r
+    return S / g, P / g
+
+
 def prefill_scores_group_units(Qg, K, lens, c: Optional[float] = None) -> np.ndarray:
     """prefill_scores_group for many K/V heads at once (OpenMP over query heads).
     Qg: [units, g, cap, d], K: [units, cap, d]. Returns [units, cap]."""
@@ -301,7 +314,6 @@ class OracleHead:
         # group = g > 1: grouped-query attention, g query heads on this key/value head; queries then come as
         # [g, L, d] (prompt) and [g, d] (decode step) and scores are means over the group
         self.group = group
-        assert group == 1 or window is None
         # window = w: scores are sums over the last w+1 steps only (Eq. 3); `hist` then holds those
         # steps' attention rows (oldest first, one entry per cached row) and S is their plain sum
         self.window = window
@@ -319,7 +331,10 @@ class OracleHead:
 
     def prefill(self, Q, K, V):
         self.K, self.V = _f64(K).copy(), _f64(V).copy()
-        if self.group > 1:
+        if self.group > 1 and self.window is not None:
+            self.S, P = prefill_window_group(Q, self.K, self.window, self.c)
+            self.hist = [row.copy() for row in P]
+        elif self.group > 1:
             self.S = prefill_scores_group(Q, self.K, self.c)
         elif self.window is None:
             self.S = prefill_scores(Q, self.K, self.c)

@@ -521,3 +521,28 @@ def test_group_mean_is_taken_after_each_heads_softmax():
     # the attention-only ranking of the group therefore starts with token 0, then the oldest tokens
     kept = orc.select(S, 5, 0, 0)
     assert kept.tolist() == [0, 1, 2, 3, 4]
+
+
+def test_group_window_replay_matches_literal_equation_without_pruning():
+    """Grouped queries with a history window: after the prompt and after every decode step (no pruning) the
+    scores are Eq. 3 read off the g full attention matrices, averaged over the group."""
+    rng = np.random.default_rng(41)
+    g, L, T, d, w = 3, 11, 8, 4, 4
+    Qg, K, V = _rand(rng, g, L + T, d) * 1.3, _rand(rng, L + T, d) * 1.3, _rand(rng, L + T, d)
+    c = orc.default_scale(d)
+    A = [bf.attention_matrix(Qg[r].tolist(), K.tolist(), c) for r in range(g)]
+    want = lambda t: bf.group_mean([bf.windowed_scores(A[r], w, t) for r in range(g)])
+    h = orc.OracleHead(d, window=w, group=g)
+    h.prefill(Qg[:, :L], K[:L], V[:L])
+    np.testing.assert_allclose(h.S, want(L - 1), rtol=1e-13)
+    assert len(h.hist) == min(L, w + 1)
+    for t in range(L, L + T):
+        h.append_and_score(Qg[:, t], K[t], V[t], t)
+        np.testing.assert_allclose(h.S, want(t), rtol=1e-12, atol=1e-300)
+    # one head in the group, or a window that covers everything, reduce to what is pinned elsewhere
+    S1, P1 = orc.prefill_window_group(Qg[:1, :L], K[:L], w)
+    S0, P0 = orc.prefill_window(Qg[0, :L], K[:L], w)
+    np.testing.assert_array_equal(S1, S0)
+    np.testing.assert_array_equal(P1, P0)
+    Sall, _ = orc.prefill_window_group(Qg[:, :L], K[:L], L)
+    np.testing.assert_allclose(Sall, orc.prefill_scores_group(Qg[:, :L], K[:L]), rtol=1e-14)
