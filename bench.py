@@ -93,9 +93,6 @@ def run(args):
     if window is not None and not fused:
         print("bench.py: history-window scores run through the fused decode route only", file=sys.stderr)
         sys.exit(2)
-    if window is not None and cfg.q_per_kv > 1:
-        print("bench.py: history-window scores do not take grouped queries", file=sys.stderr)
-        sys.exit(2)
     layers = [vs.make_inputs(cfg, seed=args.seed, layer=l, device=dev) for l in range(cfg.layers)]
     lens, budgets = layers[0].lens, layers[0].budgets
     for inp in layers:      # per-step views of the new tokens, made once (indexing costs host time per call)

@@ -94,9 +94,8 @@ typedef struct {
  * the score of a row is the mean over the group of what the g heads give it,
  *     S[i] = (1/g) sum_r sum_j a_i^{j,r}   (prompt),     S[i] += (1/g) sum_r a_i^r   (decode),
  * and Eq. 4 multiplies it by the norm of the shared value row.  Supported by
- * vatp_prefill_score, vatp_prefill_score_lse, vatp_decode_step, vatp_decode_attend_step,
- * vatp_decode_prune_step and (no queries involved) vatp_select_compact; the history-window
- * calls return VATP_E_SHAPE for g > 1.
+ * every call that takes queries (vatp_select_compact* involve none).  With a history window
+ * (Eq. 3) the window runs over the group-averaged weights, and hist holds their means.
  */
 
 /* Creates a context for HIP device `device` (host memory only).  The device must be the

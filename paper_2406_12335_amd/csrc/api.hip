@@ -33,7 +33,6 @@ vatp_status check_params(const vatp_params *p, int which_call)
     if (p->batch < 1 || p->batch > VATP_MAX_BATCH || p->n_heads < 1) return VATP_E_SHAPE;
     if (p->q_per_kv < 0 || p->q_per_kv > VATP_MAX_GROUP) return VATP_E_SHAPE;
     const int group = p->q_per_kv > 1 ? p->q_per_kv : 1;
-    if (group > 1 && which_call == VATP_CALL_PREFILL_SCORE_WINDOW) return VATP_E_SHAPE;   // no grouped history window
     if (static_cast<int64_t>(p->batch) * p->n_heads * group > VATP_MAX_UNITS) return VATP_E_SHAPE;
     if (p->head_dim != 64 && p->head_dim != 128) return VATP_E_SHAPE;
     if (p->cap < 1 || p->cap_out < 0 || p->n_sink < 0 || p->recent < 0) return VATP_E_SHAPE;
@@ -193,10 +192,10 @@ vatp_status prefill_score_impl(vatp_ctx *ctx, const vatp_params *p, const void *
     if (mfma && window < 0) {                 // (the matrix-core column-sum pass writes the norms as well)
         float *s_part = pr.g.group > 1 ? lse2 + align_up(units * pr.g.group * p->cap * sizeof(float)) / sizeof(float) : nullptr;
         e = launch_prefill_mfma(Q, K, V, S, nrm, lse2, s_part, have_lse, pr.meta, pr.g, stream);
-    } else if (mfma && prefill_mfma_window_fits(window, p->cap, static_cast<int>(units))) {
+    } else if (mfma && prefill_mfma_window_fits(window, p->cap, static_cast<int>(units * pr.g.group))) {
         e = launch_prefill_mfma_window(Q, K, V, S, nrm, lse2,
-                                       lse2 + align_up(units * p->cap * sizeof(float)) / sizeof(float), window, hist,
-                                       pr.meta, pr.g, stream);
+                                       lse2 + align_up(units * pr.g.group * p->cap * sizeof(float)) / sizeof(float), window,
+                                       hist, pr.meta, pr.g, stream);
     } else {
         if (launch_l1norm(p->dtype, p->head_dim, V, nrm, pr.meta, pr.g, stream) != hipSuccess) return VATP_E_DEVICE;
         e = launch_prefill_generic(p->dtype, p->head_dim, Q, K, S, lse2, have_lse, window, hist, pr.meta, pr.g, stream);
@@ -309,7 +308,6 @@ vatp_status decode_prune_impl(vatp_ctx *ctx, const vatp_params *p, const void *q
     if (!ws || ws_bytes < need || misaligned(ws, kAlign)) return VATP_E_WORKSPACE;
     Prepared pr;
     prepare(p, VATP_CALL_DECODE_PRUNE_STEP, pos ? new_pos : nullptr, &pr);
-    if (win.hist && pr.g.group > 1) return VATP_E_SHAPE;                      // no grouped history window
     const size_t kv_units = static_cast<size_t>(p->batch) * p->n_heads;
     const size_t units = kv_units * pr.g.group;                               // query heads
     const size_t chunks = (static_cast<size_t>(p->cap) + kDecodeChunk - 1) / kDecodeChunk;
@@ -401,7 +399,6 @@ vatp_status vatp_select_compact_window(vatp_ctx *ctx, const vatp_params *p, cons
     if (window < 0 || window > kMaxWindow || hist == hist_out) return VATP_E_SHAPE;
     vatp_status st = check_params(p, VATP_CALL_SELECT_COMPACT);
     if (st != VATP_OK) return st;
-    if (p->q_per_kv > 1) return VATP_E_SHAPE;                                  // no grouped history window
     for (int b = 0; b < p->batch; ++b)
         if (cap_hist < (p->len[b] < p->budget[b] ? p->len[b] : p->budget[b])) return VATP_E_BUDGET;
     st = vatp_select_compact(ctx, p, K, V, S, nrm, pos, K_out, V_out, S_out, nrm_out, pos_out, kept_idx, ws, ws_bytes,

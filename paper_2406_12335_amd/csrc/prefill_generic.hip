@@ -163,6 +163,7 @@ __global__ __launch_bounds__(256) void prefill_colsum_generic(const T *__restric
     const int q_first = window >= 0 ? max(0, len - 1 - window) : 0;
     float *hu = hist ? hist + unit * static_cast<size_t>(window + 1) * cap : nullptr;
     float col[4] = {0.f, 0.f, 0.f, 0.f};
+    const float inv_group = 1.f / static_cast<float>(group);      // (exactly 1 for one head)
     // the query heads that share this K/V head, one after the other (grouped-query attention; one otherwise):
     // their column sums add up in the same registers and the mean is taken at the end
     for (int qh = 0; qh < group; ++qh) {
@@ -183,7 +184,9 @@ __global__ __launch_bounds__(256) void prefill_colsum_generic(const T *__restric
                         if (i <= j) {
                             const float pr = exp2f(acc[a][c] * scale_log2 - lj);
                             col[c] += pr;
-                            if (hrow) hrow[i] = pr;
+                            // (the group mean of the attention rows: this thread comes back to the same
+                            // entry once per query head)
+                            if (hrow) hrow[i] = qh == 0 ? pr * inv_group : hrow[i] + pr * inv_group;
                         }
                     }
                 }
@@ -198,7 +201,7 @@ __global__ __launch_bounds__(256) void prefill_colsum_generic(const T *__restric
 #pragma unroll
         for (int y = 0; y < 16; ++y) s += red[y][threadIdx.x];
         const int i = i0 + threadIdx.x;
-        if (i < len) S[unit * cap + i] = s * (1.f / static_cast<float>(group));      // (exact for one head)
+        if (i < len) S[unit * cap + i] = s * inv_group;
     }
 }
 

@@ -122,7 +122,9 @@ template <bool kColsum>
 struct Epilogue {
     float ref[2], corr[2], part[2], tmax[2];
 
-    template <bool kStore = false>
+    // kStore: 0 nothing, 1 the attention weights are stored through hist_rsrc, 2 they are added to what is there
+    // (a later query head of a group; the same lane added or stored the earlier heads' weights)
+    template <int kStore = 0>
     __device__ __forceinline__ void piece(int i, const Pending<kColsum> &p, const Running<kColsum> &run,
                                           float scale, __amdgpu_buffer_rsrc_t hist_rsrc, int row_bytes)
     {
@@ -134,9 +136,12 @@ struct Epilogue {
                 part[cb] += pr;
                 // offsets outside the descriptor (rows before or after the window, columns past the
                 // sequence) are dropped by the store unit
-                if constexpr (kStore)
+                if constexpr (kStore == 1)
                     __builtin_amdgcn_raw_buffer_store_b32(__float_as_int(pr), hist_rsrc,
                                                           p.hist_off[cb] + acc_row(i) * row_bytes, 0, 0);
+                else if constexpr (kStore == 2)
+                    (void)__builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(pr, hist_rsrc,
+                                                                          p.hist_off[cb] + acc_row(i) * row_bytes, 0, 0);
             }
         } else {
             if (i < 2) {                                   // tile maximum of column block i
@@ -217,7 +222,7 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
                                                            int norm, int group, int splits)
 {
     static_assert(!kWindow || kHalves == 1, "the windowed passes use 4-wavefront workgroups");
-    static_assert(!kGrouped || (kColsum && !kWindow), "only the plain column-sum pass loops over a group's query heads");
+    static_assert(!kGrouped || kColsum, "only the column-sum passes loop over a group's query heads");
     constexpr bool kSplitKeys = kWindow && !kColsum;      // windowed row statistics: one (block, key range) per workgroup
     // A ring slot holds kHalves sub-stages of 64 streamed rows; wavefront w works on sub-stage
     // w / 4 of every slot for the 64 stationary rows of column group w % 4.  With kHalves = 2
@@ -239,8 +244,8 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
     if (slot_i >= n_units) return;
     // (grouped column sums on a small grid: `splits` workgroups share a K/V head, each taking group / splits
     // of its query heads and leaving a partial column sum; n_units then counts K/V heads x splits)
-    const int unit_i = kGrouped ? slot_i / splits : slot_i;
-    const int split = kGrouped ? slot_i % splits : 0;
+    const int unit_i = kGrouped ? __builtin_amdgcn_readfirstlane(slot_i / splits) : slot_i;
+    const int split = kGrouped ? slot_i - unit_i * splits : 0;
     const int b = unit_i / n_heads;
     const int len = meta.len[b];
     const int q_first = kWindow ? max(0, len - 1 - win.window) : 0;     // first query row that counts
@@ -262,6 +267,7 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
         with_hist ? (win.window + 1) * cap * 4 : 0, 0x00020000);
 
     const float inv_group = 1.f / static_cast<float>(group);     // the group mean (exactly 1 for one head)
+    const float log2_group = log2f(static_cast<float>(group));
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int cw = wave & 3, half = wave >> 2;      // column group, sub-stage
@@ -296,11 +302,11 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
     const bool extra_copy = kColsum && cw == 0;
     // A job is one block of stationary rows; with grouped queries it is walked once per query head
     // (`run` and the stationary operand live on from one head to the next).
-    const int n_qh = kGrouped ? group / splits : 1;
+    const int n_qh = kGrouped ? __builtin_amdgcn_readfirstlane(group / splits) : 1;
     bf16x8 Bf[2][8] = {};
     Running<kColsum> run;
     for (int it = 0, n_it = (kSplitKeys ? 1 : 2) * n_qh; it < n_it; ++it) {
-        const int job = kGrouped ? it / n_qh : it, qh = kGrouped ? it % n_qh : 0;
+        const int job = kGrouped ? (it >= n_qh ? 1 : 0) : it, qh = kGrouped ? it - job * n_qh : 0;     // (at most two jobs)
         int blk = job == 0 ? pair : n_blocks - 1 - pair;
         if constexpr (kSplitKeys) blk = q_first / kBlockCols + pair / win.n_splits;
         if (!kSplitKeys && job == 1 && blk == pair) break;   // odd count: the middle block once
@@ -395,8 +401,9 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
         // colsum : streamed = queries, stationary = keys
         {
             {
-                auto do_stage = [&](int t, auto masked_tag) {
+                auto do_stage = [&](int t, auto masked_tag, auto store_tag) __attribute__((always_inline)) {
                     constexpr bool kMasked = decltype(masked_tag)::value;
+                    constexpr int kStoreMode = decltype(store_tag)::value;
                     const int slot = (t - t_begin) & (kRing - 1);
                     const int s0 = t * kSlotRows + kStage * half;   // first streamed row of the sub-stage
                     // the two instantiations must not share a hoisted prefix: the pending pair's
@@ -419,6 +426,10 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
                                     *reinterpret_cast<const float4 *>(&lse_stage[slot][kStage * half + 32 * kb + 8 * q4 + 4 * g]);
                                 next.lse[4 * q4 + 0] = x.x; next.lse[4 * q4 + 1] = x.y;
                                 next.lse[4 * q4 + 2] = x.z; next.lse[4 * q4 + 3] = x.w;
+                                if constexpr (kWindow && kGrouped) {      // weights of a group come out divided by its size
+#pragma unroll
+                                    for (int e = 0; e < 4; ++e) next.lse[4 * q4 + e] += log2_group;
+                                }
                             }
                         }
 #pragma unroll
@@ -438,9 +449,9 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
 #pragma unroll
                         for (int s = 0; s < 8; ++s) {
                             next.acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], Bf[0][s], next.acc[0], 0, 0, 0);
-                            epi.template piece<kWindow && kColsum>(2 * s, pend, run, scale, hist_rsrc, cap * 4);
+                            epi.template piece<kStoreMode>(2 * s, pend, run, scale, hist_rsrc, cap * 4);
                             next.acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], Bf[1][s], next.acc[1], 0, 0, 0);
-                            epi.template piece<kWindow && kColsum>(2 * s + 1, pend, run, scale, hist_rsrc, cap * 4);
+                            epi.template piece<kStoreMode>(2 * s + 1, pend, run, scale, hist_rsrc, cap * 4);
                         }
                         epi.finish(pend, run, scale);
                         // keep the pending pair's results inside this block (no sinking past it)
@@ -487,30 +498,39 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
                 const int du = u_diag - half;
                 const int t_first = du < 0 ? 0 : (du + kHalves - 1) / kHalves;
                 const bool on_diag = du >= 0 && du % kHalves == 0;
-                int t = t_begin;
-                if (w0 >= len) {
-                    for (; t <= t_end; ++t) stage_sync(t);              // no valid stationary row
-                } else if constexpr (!kColsum) {
-                    // (a range of keys may end before the diagonal or begin after it)
-                    for (; t < t_first && t <= t_end; ++t) { stage_sync(t); do_stage(t, std::false_type{}); }
-                    if (on_diag && t == t_first && t <= t_end) { stage_sync(t); do_stage(t, std::true_type{}); ++t; }
-                    for (; t <= t_end; ++t) stage_sync(t);               // keys past the diagonal
+                auto walk = [&](auto store_tag) __attribute__((always_inline)) {
+                    int t = t_begin;
+                    if (w0 >= len) {
+                        for (; t <= t_end; ++t) stage_sync(t);              // no valid stationary row
+                    } else if constexpr (!kColsum) {
+                        // (a range of keys may end before the diagonal or begin after it)
+                        for (; t < t_first && t <= t_end; ++t) { stage_sync(t); do_stage(t, std::false_type{}, store_tag); }
+                        if (on_diag && t == t_first && t <= t_end) { stage_sync(t); do_stage(t, std::true_type{}, store_tag); ++t; }
+                        for (; t <= t_end; ++t) stage_sync(t);               // keys past the diagonal
+                    } else {
+                        // last stage whose sub-stage has 64 valid rows: 64u + 63 < len
+                        const int t_full_end = (len / kStage - 1 - half + kHalves) / kHalves - 1;
+                        for (; t < t_first && t <= t_end; ++t) stage_sync(t);   // queries before the diagonal
+                        if (on_diag && t == t_first && t <= t_end) { stage_sync(t); do_stage(t, std::true_type{}, store_tag); ++t; }
+                        for (; t <= min(t_full_end, t_end); ++t) { stage_sync(t); do_stage(t, std::false_type{}, store_tag); }
+                        for (; t <= t_end; ++t) { stage_sync(t); do_stage(t, std::true_type{}, store_tag); }   // ragged tail
+                    }
+                    // the last pair still waits for its exponentials
+                    Epilogue<kColsum> epi;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        epi.template piece<decltype(store_tag)::value>(i, pend, run, scale_log2, hist_rsrc, cap * 4);
+                    epi.finish(pend, run, scale_log2);
+                };
+                // windowed column sums also leave the attention rows: stored by the first query head of a group (or
+                // the only one), added by the others (the same lane comes back to the same entry, in program order)
+                if constexpr (kWindow && kColsum && kGrouped) {
+                    if (qh == 0) walk(std::integral_constant<int, 1>{});
+                    else walk(std::integral_constant<int, 2>{});
                 } else {
-                    // last stage whose sub-stage has 64 valid rows: 64u + 63 < len
-                    const int t_full_end = (len / kStage - 1 - half + kHalves) / kHalves - 1;
-                    for (; t < t_first && t <= t_end; ++t) stage_sync(t);   // queries before the diagonal
-                    if (on_diag && t == t_first && t <= t_end) { stage_sync(t); do_stage(t, std::true_type{}); ++t; }
-                    for (; t <= min(t_full_end, t_end); ++t) { stage_sync(t); do_stage(t, std::false_type{}); }
-                    for (; t <= t_end; ++t) { stage_sync(t); do_stage(t, std::true_type{}); }   // ragged tail
+                    walk(std::integral_constant<int, (kWindow && kColsum) ? 1 : 0>{});
                 }
             }
-        }
-        // the last pair still waits for its exponentials
-        {
-            Epilogue<kColsum> epi;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) epi.template piece<kWindow && kColsum>(i, pend, run, scale_log2, hist_rsrc, cap * 4);
-            epi.finish(pend, run, scale_log2);
         }
 
         if (qh == n_qh - 1) {
@@ -563,7 +583,7 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
                     else if (!kColsum) lse_u[idx] = fin_m[cb] + __log2f(fin_l[cb]);
                     else if (kGrouped && splits > 1)     // partial sum [split, K/V head, cap], mean taken by the merge kernel
                         S[(static_cast<size_t>(split) * (n_units / splits) + unit) * cap + idx] = fin_l[cb];
-                    else S[unit * cap + idx] = kGrouped ? fin_l[cb] * inv_group : fin_l[cb];
+                    else S[unit * cap + idx] = (kGrouped && !kWindow) ? fin_l[cb] * inv_group : fin_l[cb];   // (windowed groups: weights already divided)
                 }
             }
         }
@@ -627,8 +647,8 @@ hipError_t launch_prefill_mfma_window(const void *Q, const void *K, const void *
 {
     if (g.max_len <= 0) return hipSuccess;
     const int n_blocks = (g.max_len + kBlockCols - 1) / kBlockCols;
-    const int n_units = g.batch * g.n_heads;
-    const unsigned unit_groups = (n_units + 7) / 8;
+    // row statistics per query head, column sums per K/V head (the same units without grouped queries)
+    const int kv_units = g.batch * g.n_heads, q_units = kv_units * g.group, q_heads = g.n_heads * g.group;
     const bf16_t *q = static_cast<const bf16_t *>(Q), *k = static_cast<const bf16_t *>(K);
     WindowPass win;
     win.window = window;
@@ -638,14 +658,20 @@ hipError_t launch_prefill_mfma_window(const void *Q, const void *K, const void *
     win.n_splits = ((g.max_len + kStage - 1) / kStage + kSplitStages - 1) / kSplitStages;
     const int window_blocks = (window + 1 + kBlockCols - 1) / kBlockCols + 1;     // blocks a window can straddle
     win.n_qb = window_blocks < n_blocks ? window_blocks : n_blocks;
-    hipLaunchKernelGGL((prefill_mfma_kernel<false, 1, true>), dim3(8u * win.n_qb * win.n_splits * unit_groups), dim3(256),
-                       0, st, q, k, lse2, S, meta, g.n_heads, n_units, g.cap, n_blocks, g.scale_log2, win, nullptr, nullptr, 0, 1, 1);
+    hipLaunchKernelGGL((prefill_mfma_kernel<false, 1, true>), dim3(8u * win.n_qb * win.n_splits * ((q_units + 7) / 8)),
+                       dim3(256), 0, st, q, k, lse2, S, meta, q_heads, q_units, g.cap, n_blocks, g.scale_log2, win, nullptr,
+                       nullptr, 0, g.group, 1);
     const int merge_rows = window + 1 + kStage;
-    hipLaunchKernelGGL(merge_split_lse_kernel, dim3((merge_rows + 255) / 256, n_units), dim3(256), 0, st, lse_part, lse2,
-                       meta, g.n_heads, n_units, g.cap, window, win.n_splits);
-    hipLaunchKernelGGL((prefill_mfma_kernel<true, 1, true>), dim3(8u * ((n_blocks + 1) / 2) * unit_groups), dim3(256), 0,
-                       st, q, k, lse2, S, meta, g.n_heads, n_units, g.cap, n_blocks, g.scale_log2, win,
-                       static_cast<const bf16_t *>(V), nrm, g.norm, 1, 1);
+    hipLaunchKernelGGL(merge_split_lse_kernel, dim3((merge_rows + 255) / 256, q_units), dim3(256), 0, st, lse_part, lse2,
+                       meta, q_heads, q_units, g.cap, window, win.n_splits);
+    const dim3 grid(8u * ((n_blocks + 1) / 2) * ((kv_units + 7) / 8));
+    if (g.group > 1)
+        hipLaunchKernelGGL((prefill_mfma_kernel<true, 1, true, true>), grid, dim3(256), 0, st, q, k, lse2, S, meta, g.n_heads,
+                           kv_units, g.cap, n_blocks, g.scale_log2, win, static_cast<const bf16_t *>(V), nrm, g.norm,
+                           g.group, 1);
+    else
+        hipLaunchKernelGGL((prefill_mfma_kernel<true, 1, true>), grid, dim3(256), 0, st, q, k, lse2, S, meta, g.n_heads,
+                           kv_units, g.cap, n_blocks, g.scale_log2, win, static_cast<const bf16_t *>(V), nrm, g.norm, 1, 1);
     return hipGetLastError();
 }
 

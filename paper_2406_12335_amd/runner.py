@@ -27,8 +27,6 @@ class PrunedKVCache:
         self.window = window
         # q_per_kv = g > 1: grouped-query attention; n_heads counts the K/V heads, query tensors have n_heads * g heads
         self.q_per_kv = int(q_per_kv)
-        if window is not None and self.q_per_kv > 1:
-            raise ValueError("vatp: the history-window calls do not take grouped queries")
         self.budgets = [int(x) for x in budgets]
         self.cap = int(cap_cache) if cap_cache else max(self.budgets) + 1
         self._own_ctx = ctx is None

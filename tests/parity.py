@@ -97,7 +97,6 @@ def run_trajectory(inp, device, units: Optional[Sequence[Tuple[int, int]]] = Non
     cfg = inp.cfg
     b, H, d = cfg.batch, cfg.n_heads, cfg.head_dim
     grp = cfg.q_per_kv                       # > 1: grouped queries, query heads h*grp .. h*grp+grp-1 on K/V head h
-    assert grp == 1 or window is None
     F = cfg.n_sink_keep if n_sink is None else n_sink
     R = cfg.recent
     T = cfg.decode_steps if steps is None else steps
@@ -129,9 +128,10 @@ def run_trajectory(inp, device, units: Optional[Sequence[Tuple[int, int]]] = Non
             Qh = np.stack([_unit_rows(inp.Q, bb, hh, Lmax) for bb, hh in units])
             if full_prefill_check and window is None:
                 S_or = orc.prefill_scores_units(Qh, Kh, [inp.lens[bb] for bb, _ in units])
-        elif full_prefill_check:
+        else:
             Qg = np.stack([np.stack([_unit_rows(inp.Q, bb, hh * grp + r, Lmax) for r in range(grp)]) for bb, hh in units])
-            S_or = orc.prefill_scores_group_units(Qg, Kh, [inp.lens[bb] for bb, _ in units])
+            if full_prefill_check and window is None:
+                S_or = orc.prefill_scores_group_units(Qg, Kh, [inp.lens[bb] for bb, _ in units])
         for ui, (bb, hh) in enumerate(units):
             L = inp.lens[bb]
             o = orc.OracleHead(d, norm_kind=norm_kind, window=window, group=grp)
@@ -140,7 +140,8 @@ def run_trajectory(inp, device, units: Optional[Sequence[Tuple[int, int]]] = Non
             o.pos = np.arange(L, dtype=np.int64)
             S_gpu = _unit_rows(cache.S_prompt, bb, hh, L)
             if window is not None:
-                o.S, P = orc.prefill_window(Qh[ui, :L], Kh[ui, :L], window)
+                o.S, P = orc.prefill_window(Qh[ui, :L], Kh[ui, :L], window) if grp == 1 \
+                    else orc.prefill_window_group(Qg[ui, :, :L], Kh[ui, :L], window)
                 o.hist = [row.copy() for row in P]
                 s_max[(bb, hh)] = float(o.S.max()) if L else 0.0
                 e = assert_scores_close(S_gpu, o.S, rtol, "windowed prefill S unit (%d,%d)" % (bb, hh))

@@ -200,18 +200,45 @@ def test_grouped_prompt_scores_from_given_row_lse(gpu_device, dtype, d, g, lens)
         assert torch.all(S[b, :, L:] == -3.0)
 
 
-def test_group_size_limits_and_window_calls_are_rejected(gpu_device):
+def test_group_size_limits(gpu_device):
     lens, bud = [100], [50]
     for g, call, want in [(9, vatp.CALL_PREFILL_SCORE, B.E_SHAPE), (-1, vatp.CALL_DECODE_STEP, B.E_SHAPE),
-                          (2, vatp.CALL_PREFILL_SCORE_WINDOW, B.E_SHAPE), (8, vatp.CALL_PREFILL_SCORE, B.OK),
+                          (2, vatp.CALL_PREFILL_SCORE_WINDOW, B.OK), (8, vatp.CALL_PREFILL_SCORE, B.OK),
                           (8, vatp.CALL_DECODE_PRUNE_STEP, B.E_BUDGET)]:
         p = vatp.Params(1, 4, 128, torch.bfloat16, 2, 8, 128, lens, bud, q_per_kv=g)
         assert vatp.vatp_validate(p, call) == want, (g, call)
-    with pytest.raises(ValueError):
-        PrunedKVCache(1, 2, 128, torch.bfloat16, 2, 8, [50], gpu_device, window=10, q_per_kv=2)
     # too many query heads in one call
     p = vatp.Params(64, 64, 128, torch.bfloat16, 0, 0, 16, [8] * 64, None, q_per_kv=8)
     assert vatp.vatp_validate(p, vatp.CALL_PREFILL_SCORE) == B.E_SHAPE
+
+
+@pytest.mark.parametrize("dtype,d,H,g,L,w", [("bf16", 128, 2, 4, 700, 100), ("bf16", 128, 3, 2, 333, 400), ("fp32", 64, 2, 3, 200, 20),
+                                             ("bf16", 128, 9, 8, 1100, 300), ("bf16", 64, 2, 4, 300, 50)])
+def test_grouped_queries_with_history_window(gpu_device, dtype, d, H, g, L, w):
+    """Eq. 3 on the group-averaged weights: windowed prompt pass (attention rows averaged over the group), prune that
+    carries them along, fused decode steps."""
+    cfg = vs.scaled(vs.CONFIGS["llama7b_layer"], n_heads=H, head_dim=d, prompt_len=L, dtype=dtype, budget_pct=40,
+                    recent=10, decode_steps=14, q_per_kv=g)
+    inp = vs.make_inputs(cfg, seed=300 + g)
+    _say("gqa window %s d=%d H=%d g=%d L=%d w=%d" % (dtype, d, H, g, L, w))
+    rep = parity.run_trajectory(inp, gpu_device, units=[(0, 0), (0, H - 1)], fused=True, window=w)
+    _say("report %r" % rep)
+    # the stored attention rows themselves: the group mean of each query head's softmax row
+    cache = PrunedKVCache(1, H, d, cfg.torch_dtype(), 2, cfg.recent, inp.budgets, gpu_device, window=w, q_per_kv=g)
+    try:
+        cache.prefill_score(inp.Q.to(gpu_device), inp.K.to(gpu_device), inp.V.to(gpu_device), inp.lens)
+        torch.cuda.synchronize()
+        hist = cache.hist_prompt.cpu().double().numpy()
+    finally:
+        cache.close()
+    rtol = parity.rtol_for(cfg.torch_dtype())
+    for h in (0, H - 1):
+        _, P = orc.prefill_window_group(inp.Q[0, h * g:(h + 1) * g].double().numpy(), inp.K[0, h].double().numpy(), w)
+        j0 = max(0, L - 1 - w)
+        for row in (0, P.shape[0] // 2, P.shape[0] - 1):
+            j = j0 + row
+            parity.assert_scores_close(hist[0, h, row, :j + 1], P[row, :j + 1], rtol, "window rows head %d row %d" % (h, row),
+                                       atol=1e-30)
 
 
 def test_grouped_queries_at_model_size(gpu_device):
