@@ -321,7 +321,7 @@ vatp_status decode_prune_impl(vatp_ctx *ctx, const vatp_params *p, const void *q
     for (int b = 0; b < p->batch; ++b) budgets.aux[b] = p->budget[b];
     // One launch with a workgroup per head when there are enough heads to fill the chip that way and
     // each is short enough for a single workgroup to stream quickly (measured per step at 256 heads x 820 rows:
-    // 24.0 against 30.5 us with 32 layers' caches in turn, 19.9 against 22.3 us with two; slower than two launches
+    // 22 against 30 us with 32 layers' caches in turn; slower than two launches
     // at 32 heads x 2049 rows, 23 against 14 us).
     const bool one = !out && !win.hist && pr.g.group == 1 && kv_units >= 128 && pr.g.max_len <= 1024 &&
                      pr.g.max_len <= decode_prune_one_max_rows();

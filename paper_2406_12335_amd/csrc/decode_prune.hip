@@ -250,7 +250,6 @@ __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
     __shared__ float s_score[kOneMaxRows];                 // old scores (0 for the appended row)
     __shared__ float s_norm[kOneMaxRows];
     __shared__ float2 s_part[kOneMaxRows / kDecodeChunk];
-    __shared__ float s_wave[kWaves];
     __shared__ float s_new_norm;
     __shared__ unsigned long long s_min[kWaves];
 
@@ -326,6 +325,27 @@ __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
             if (sub == 0 && r < n) s_logit[r] = dot * scale_log2;
         }
     }
+    // Rows that will most likely have to be copied to the other set are requested now, while the statistics
+    // and the scan below run on LDS alone: the row that leaves is almost always the one at the edge of the
+    // recent window, so the copy starts near min(synced, n - recent - 1).  At most kSpecRows rows, kSpecSlots per
+    // thread; whatever the guess misses is copied the ordinary way afterwards.  (The appended row comes from
+    // the step's input, not from the cache row other threads have just stored.)
+    constexpr int kSpecSlots = kRowsPerPass >= 64 ? 2 : 128 / kRowsPerPass, kSpecRows = kSpecSlots * kRowsPerPass;   // >= 128 rows
+    const int spec_first = max(max(min(synced, n - recent - 1), n - kSpecRows), 0);
+    uint4 spec_k[kSpecSlots], spec_v[kSpecSlots];
+    int spec_pos[kSpecSlots];
+#pragma unroll
+    for (int u = 0; u < kSpecSlots; ++u) {
+        const int r = spec_first + u * kRowsPerPass + rloc;
+        spec_k[u] = spec_v[u] = make_uint4(0, 0, 0, 0);
+        spec_pos[u] = 0;
+        if (r < n) {
+            spec_k[u] = r == n0 ? knew[sub] : Ku[static_cast<size_t>(r) * kLanesPerRow + sub];
+            spec_v[u] = r == n0 ? reinterpret_cast<const uint4 *>(v_new + unit * D)[sub]
+                                : Vu[static_cast<size_t>(r) * kLanesPerRow + sub];
+            if (pos && sub == 0) spec_pos[u] = r == n0 ? len_pos.aux[b] : pos[unit * cap + r];
+        }
+    }
 #pragma unroll
     for (int u = 0; u < kPre; ++u) {
         const int r = tid + u * kOneThreads;
@@ -334,27 +354,25 @@ __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
     __syncthreads();
     if (tid == 0) { s_score[n0] = 0.f; s_norm[n0] = s_new_norm; }      // the appended row (published by the syncs below)
 
-    // statistics of every 128-row chunk: two wavefronts per chunk, lane = row within the wavefront's 64
+    // Statistics of every 128-row chunk, one wavefront per chunk and no exchange between wavefronts: the lane
+    // takes rows lane and lane + 64 of the chunk.  Each half is summed by its own butterfly and the two sums are
+    // added last, which is the order in which decode_logits_kernel's two wavefronts per chunk combine theirs.
     const int n_chunks = (n + kDecodeChunk - 1) / kDecodeChunk;
-    for (int base = 0; base < n; base += kOneThreads) {
-        const int r = base + tid;
-        const float t = r < n ? s_logit[r] : -INFINITY;
-        float mx = t;
+    for (int chunk = wave; chunk < n_chunks; chunk += kWaves) {
+        const int r0 = chunk * kDecodeChunk + lane, r1 = r0 + 64;
+        const float t0 = r0 < n ? s_logit[r0] : -INFINITY, t1 = r1 < n ? s_logit[r1] : -INFINITY;
+        float mx = fmaxf(t0, t1);
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
-        if (lane == 0) s_wave[wave] = mx;
-        __syncthreads();
-        mx = fmaxf(s_wave[wave & ~1], s_wave[wave | 1]);
-        float e = exp2f(t - mx);
+        float e0 = exp2f(t0 - mx), e1 = exp2f(t1 - mx);
 #pragma unroll
-        for (int off = 32; off > 0; off >>= 1) e += __shfl_xor(e, off);
-        __syncthreads();
-        if (lane == 0) s_wave[wave] = e;
-        __syncthreads();
-        const int chunk = (base >> 7) + (wave >> 1);
-        if (lane == 0 && (wave & 1) == 0 && chunk < n_chunks) s_part[chunk] = make_float2(mx, s_wave[wave] + s_wave[wave + 1]);
-        __syncthreads();
+        for (int off = 32; off > 0; off >>= 1) {
+            e0 += __shfl_xor(e0, off);
+            e1 += __shfl_xor(e1, off);
+        }
+        if (lane == 0) s_part[chunk] = make_float2(mx, e0 + e1);
     }
+    __syncthreads();
     float M, L;
     merge_chunk_stats(s_part, n_chunks, M, L);
     const float lse2 = M + log2f(L);
@@ -385,22 +403,38 @@ __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
         evicted = static_cast<int>(~static_cast<unsigned>(best & 0xffffffffull));
     }
 
+    // rows of the other set that are out of date: from the first row in which it differs from the input
+    // set, or from the evicted row if that comes earlier.  Source row r goes to row r - (r > evicted).
+    const int first = min(synced, evicted);
+    if (tid == 0) synced_out[unit] = evicted;
+    uint4 *Ko = reinterpret_cast<uint4 *>(K_out + unit * cap_out * D);
+    uint4 *Vo = reinterpret_cast<uint4 *>(V_out + unit * cap_out * D);
+    // ... those requested ahead of time, each stored by the thread that holds it
+#pragma unroll
+    for (int u = 0; u < kSpecSlots; ++u) {
+        const int r = spec_first + u * kRowsPerPass + rloc;
+        const int o = r - (r > evicted ? 1 : 0);
+        if (r < n && r != evicted && o >= first) {
+            Ko[static_cast<size_t>(o) * kLanesPerRow + sub] = spec_k[u];
+            Vo[static_cast<size_t>(o) * kLanesPerRow + sub] = spec_v[u];
+            if (sub == 0) {
+                nrm_out[unit * cap_out + o] = s_norm[r];
+                if (pos_out) pos_out[unit * cap_out + o] = spec_pos[u];
+            }
+        }
+    }
+
     for (int o = tid; o < n_keep; o += kOneThreads) {
         const int src = o + (o >= evicted ? 1 : 0);
         S_out[unit * cap_out + o] = new_score(src);
         if (kept_idx) kept_idx[unit * cap_out + o] = src;
     }
 
-    const int first = min(synced, evicted);
-    if (tid == 0) synced_out[unit] = evicted;
-    // The appended row is read back below by other threads than the ones that stored it: make the
-    // stores visible inside the workgroup first.
-    __threadfence_block();
-    __syncthreads();
+    // ... and the rows before them, if the copy has to start earlier than guessed (source rows below
+    // spec_first: never the appended row, so everything is read from the cache as it was on entry)
     {
-        uint4 *Ko = reinterpret_cast<uint4 *>(K_out + unit * cap_out * D);
-        uint4 *Vo = reinterpret_cast<uint4 *>(V_out + unit * cap_out * D);
-        for (int o = first + rloc; o < n_keep; o += kRowsPerPass) {
+        const int o_end = min(n_keep, spec_first - (evicted < spec_first ? 1 : 0));
+        for (int o = first + rloc; o < o_end; o += kRowsPerPass) {
             const int src = o + (o >= evicted ? 1 : 0);
             const uint4 kr = Ku[static_cast<size_t>(src) * kLanesPerRow + sub];
             const uint4 vr = Vu[static_cast<size_t>(src) * kLanesPerRow + sub];
