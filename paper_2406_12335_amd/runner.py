@@ -67,6 +67,7 @@ class PrunedKVCache:
         self._cp_kept, self._cp_ws = vp(self.kept_idx), vp(self.ws)
         self._ws_bytes = self.ws.numel()
         self._npos = (ctypes.c_int32 * batch)()
+        self._fused_args = {}
         self._lib = B.load()
 
     def close(self):
@@ -135,7 +136,7 @@ class PrunedKVCache:
     def _qkv(q, k, v):
         if not (q.is_contiguous() and k.is_contiguous() and v.is_contiguous()):
             raise ValueError("vatp: tensors must be contiguous")
-        return ctypes.c_void_p(q.data_ptr()), ctypes.c_void_p(k.data_ptr()), ctypes.c_void_p(v.data_ptr())
+        return q.data_ptr(), k.data_ptr(), v.data_ptr()            # (plain integers convert to void* arguments)
 
     def decode_step(self, q, k, v, new_pos: Optional[Sequence[int]], stream=None):
         if self.window is not None:
@@ -178,11 +179,21 @@ class PrunedKVCache:
             self.cur, self.synced_cur = o, so
             self.lens = [min(n + 1, bud) for n, bud in zip(self.lens, self.budgets)]
             return
-        st = self._lib.vatp_decode_prune_step(
-            self.ctx, self._p_dec.ref(), *self._qkv(q, k, v), cp["K"][c], cp["V"][c], cp["S"][c], cp["nrm"][c],
-            cp["pos"][c], self._new_pos(new_pos), cp["K"][o], cp["V"][o], cp["S"][o], cp["nrm"][o], cp["pos"][o],
-            self._cp_kept if want_kept_idx else None, ctypes.c_void_p(self.synced[si].data_ptr()),
-            ctypes.c_void_p(self.synced[so].data_ptr()), B._ptr(out), self._cp_ws, self._ws_bytes, B._stream(stream))
-        B._check(st, "vatp_decode_prune_step")
+        # the arguments that do not change from step to step are laid out once per (cache set, synced array) pair
+        args = self._fused_args.get((c, si))
+        if args is None:
+            args = [self.ctx, self._p_dec.ref(), None, None, None, cp["K"][c], cp["V"][c], cp["S"][c], cp["nrm"][c],
+                    cp["pos"][c], None, cp["K"][o], cp["V"][o], cp["S"][o], cp["nrm"][o], cp["pos"][o], None,
+                    cp["synced"][si], cp["synced"][so], None, self._cp_ws, self._ws_bytes, None]
+            self._fused_args[(c, si)] = args
+        args[2], args[3], args[4] = self._qkv(q, k, v)
+        args[10] = self._new_pos(new_pos)
+        args[16] = self._cp_kept if want_kept_idx else None
+        args[17], args[18] = self.synced[si].data_ptr(), self.synced[so].data_ptr()
+        args[19] = B._ptr(out)
+        args[22] = B._stream(stream)
+        st = self._lib.vatp_decode_prune_step(*args)
+        if st:
+            B._check(st, "vatp_decode_prune_step")
         self.cur, self.synced_cur = o, so
         self.lens = [min(n + 1, bud) for n, bud in zip(self.lens, self.budgets)]
