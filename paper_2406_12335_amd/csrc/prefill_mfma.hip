@@ -122,11 +122,13 @@ template <bool kColsum>
 struct Epilogue {
     float ref[2], corr[2], part[2], tmax[2];
 
-    // kStore: 0 nothing, 1 the attention weights are stored through hist_rsrc, 2 they are added to what is there
-    // (a later query head of a group; the same lane added or stored the earlier heads' weights)
+    // kStore: 0 nothing, 1 the attention weights are stored through hist_rsrc, 2 they are added to the sums
+    // `group_sum` that a lane keeps for the query heads of a group (the stage's rows are stored once, after the
+    // last head)
     template <int kStore = 0>
     __device__ __forceinline__ void piece(int i, const Pending<kColsum> &p, const Running<kColsum> &run,
-                                          float scale, __amdgpu_buffer_rsrc_t hist_rsrc, int row_bytes)
+                                          float scale, __amdgpu_buffer_rsrc_t hist_rsrc, int row_bytes,
+                                          float (*group_sum)[16] = nullptr)
     {
         if constexpr (kColsum) {
             if (i == 0) { part[0] = 0.f; part[1] = 0.f; }
@@ -140,8 +142,7 @@ struct Epilogue {
                     __builtin_amdgcn_raw_buffer_store_b32(__float_as_int(pr), hist_rsrc,
                                                           p.hist_off[cb] + acc_row(i) * row_bytes, 0, 0);
                 else if constexpr (kStore == 2)
-                    (void)__builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(pr, hist_rsrc,
-                                                                          p.hist_off[cb] + acc_row(i) * row_bytes, 0, 0);
+                    group_sum[cb][i] += pr;
             }
         } else {
             if (i < 2) {                                   // tile maximum of column block i
@@ -302,7 +303,9 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
     const bool extra_copy = kColsum && cw == 0;
     // A job is one block of stationary rows; with grouped queries it is walked once per query head
     // (`run` and the stationary operand live on from one head to the next).
-    const int n_qh = kGrouped ? __builtin_amdgcn_readfirstlane(group / splits) : 1;
+    // (Windowed column sums of a group, kBand, go through the heads inside the stage loop instead: see there.)
+    constexpr bool kBand = kWindow && kColsum && kGrouped;
+    const int n_qh = (kGrouped && !kBand) ? __builtin_amdgcn_readfirstlane(group / splits) : 1;
     bf16x8 Bf[2][8] = {};
     Running<kColsum> run;
     for (int it = 0, n_it = (kSplitKeys ? 1 : 2) * n_qh; it < n_it; ++it) {
@@ -324,13 +327,31 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
             if (t_begin > t_end) continue;
         }
 
-        if constexpr (kGrouped) {
+        if constexpr (kGrouped && !kBand) {
             strm = strm0 + static_cast<size_t>(split * n_qh + qh) * cap * kD;
             lse_u = lse_u0 + static_cast<size_t>(split * n_qh + qh) * cap;
         }
+        // kBand: the ring holds "virtual" stages v = (stage t, query head h), h innermost, so that a lane meets
+        // the same (query row, key) entries of all heads of the group one after the other and can add them up
+        // in registers.  The copy front runs kAhead virtual stages ahead.
+        const int n_virtual = kBand ? (t_end - t_begin + 1) * group : 0;
+        int issued = 0, copy_t = t_begin, copy_h = 0, cur_v = 0;
+        auto issue_copy = [&]() __attribute__((always_inline)) {
+            strm = strm0 + static_cast<size_t>(copy_h) * cap * kD;
+            lse_u = lse_u0 + static_cast<size_t>(copy_h) * cap;
+            copy_stage(copy_t, issued & (kRing - 1));
+            ++issued;
+            if (++copy_h == group) { copy_h = 0; ++copy_t; }
+        };
+        if constexpr (kBand) {
 #pragma unroll
-        for (int k = 0; k < kAhead; ++k)
-            if (t_begin + k <= t_end) copy_stage(t_begin + k, k);
+            for (int k = 0; k < kAhead; ++k)
+                if (issued < n_virtual) issue_copy();
+        } else {
+#pragma unroll
+            for (int k = 0; k < kAhead; ++k)
+                if (t_begin + k <= t_end) copy_stage(t_begin + k, k);
+        }
 
         // The column-sum pass visits every block of keys once: it also leaves the norm of the value rows
         // of its block (paper Eq. 4), 64 rows per wavefront, while the first stages are on their way.
@@ -384,7 +405,8 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
         // Publish stage t: it is complete once only the copies of younger stages are outstanding.
         // Then the slot freed by stage t-1 (every wavefront is past it now) takes stage t+3.
         auto stage_sync = [&](int t) {
-            const int younger = min(t_end - t, kAhead - 1);
+            // (kBand: t is the virtual stage index)
+            const int younger = kBand ? min(n_virtual - 1 - t, kAhead - 1) : min(t_end - t, kAhead - 1);
             if (younger == 2) {
                 if (extra_copy) wait_copies_then_barrier<10>(); else wait_copies_then_barrier<8>();
             } else if (younger == 1) {
@@ -392,8 +414,22 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
             } else {
                 wait_copies_then_barrier<0>();
             }
-            if (t + kAhead <= t_end) copy_stage(t + kAhead, (t + kAhead - t_begin) & (kRing - 1));
+            if constexpr (kBand) {
+                if (issued < n_virtual) issue_copy();
+            } else {
+                if (t + kAhead <= t_end) copy_stage(t + kAhead, (t + kAhead - t_begin) & (kRing - 1));
+            }
         };
+        // kBand: this lane's sums over the group's heads of the weights of one stage: [pair][column block][row]
+        float group_sum[kBand ? 2 : 1][2][16];
+        if constexpr (kBand) {
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) group_sum[a][cb][v] = 0.f;
+        }
 
         // One stage = two pairs of tiles.  The body is branch-free (the masked variant is a
         // separate instantiation) so that MFMAs and exponentials share one basic block.
@@ -404,7 +440,7 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
                 auto do_stage = [&](int t, auto masked_tag, auto store_tag) __attribute__((always_inline)) {
                     constexpr bool kMasked = decltype(masked_tag)::value;
                     constexpr int kStoreMode = decltype(store_tag)::value;
-                    const int slot = (t - t_begin) & (kRing - 1);
+                    const int slot = kBand ? (cur_v & (kRing - 1)) : ((t - t_begin) & (kRing - 1));
                     const int s0 = t * kSlotRows + kStage * half;   // first streamed row of the sub-stage
                     // the two instantiations must not share a hoisted prefix: the pending pair's
                     // exponentials belong next to this stage's MFMAs (the scale is re-read through
@@ -449,9 +485,10 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
 #pragma unroll
                         for (int s = 0; s < 8; ++s) {
                             next.acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], Bf[0][s], next.acc[0], 0, 0, 0);
-                            epi.template piece<kStoreMode>(2 * s, pend, run, scale, hist_rsrc, cap * 4);
+                            // (the pending pair is the other pair: of the previous virtual stage for kb = 0)
+                            epi.template piece<kStoreMode>(2 * s, pend, run, scale, hist_rsrc, cap * 4, group_sum[kBand ? 1 - kb : 0]);
                             next.acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], Bf[1][s], next.acc[1], 0, 0, 0);
-                            epi.template piece<kStoreMode>(2 * s + 1, pend, run, scale, hist_rsrc, cap * 4);
+                            epi.template piece<kStoreMode>(2 * s + 1, pend, run, scale, hist_rsrc, cap * 4, group_sum[kBand ? 1 - kb : 0]);
                         }
                         epi.finish(pend, run, scale);
                         // keep the pending pair's results inside this block (no sinking past it)
@@ -522,11 +559,45 @@ __global__ __launch_bounds__(256 * kHalves) void prefill_mfma_kernel(const bf16_
                         epi.template piece<decltype(store_tag)::value>(i, pend, run, scale_log2, hist_rsrc, cap * 4);
                     epi.finish(pend, run, scale_log2);
                 };
-                // windowed column sums also leave the attention rows: stored by the first query head of a group (or
-                // the only one), added by the others (the same lane comes back to the same entry, in program order)
-                if constexpr (kWindow && kColsum && kGrouped) {
-                    if (qh == 0) walk(std::integral_constant<int, 1>{});
-                    else walk(std::integral_constant<int, 2>{});
+                // windowed column sums also leave the attention rows
+                if constexpr (kBand) {
+                    // every stage of queries once per query head of the group; after the last head the pending
+                    // pair is completed (not overlapped with anything: one pair in 2 * group) and the lane's sums
+                    // of the stage -- the group means, the weights being divided by the group size -- are stored
+                    const int t_full_end = (len / kStage - 1 - half + kHalves) / kHalves - 1;
+                    using add_tag = std::integral_constant<int, 2>;
+                    for (int t = t_begin; t <= t_end; ++t) {
+                        const bool idle = w0 >= len || t < t_first;
+                        const bool masked = (on_diag && t == t_first) || t > t_full_end;
+                        for (int h = 0; h < group; ++h, ++cur_v) {
+                            stage_sync(cur_v);
+                            if (idle) continue;
+                            if (masked) do_stage(t, std::true_type{}, add_tag{});
+                            else do_stage(t, std::false_type{}, add_tag{});
+                        }
+                        if (idle) continue;
+                        Epilogue<kColsum> epi;
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) epi.template piece<2>(i, pend, run, scale_log2, hist_rsrc, cap * 4, group_sum[1]);
+                        epi.finish(pend, run, scale_log2);
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) { pend.acc[0][v] = -INFINITY; pend.acc[1][v] = -INFINITY; }
+#pragma unroll
+                        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                            for (int cb = 0; cb < 2; ++cb) {
+                                const int col = w0 + 32 * cb + n;
+                                const unsigned off = col < len ? static_cast<unsigned>(t * kSlotRows + 32 * kb + 4 * g - q_first) *
+                                                                         static_cast<unsigned>(cap * 4) + col * 4
+                                                               : 0x80000000u;
+#pragma unroll
+                                for (int v = 0; v < 16; ++v) {
+                                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_int(group_sum[kb][cb][v]), hist_rsrc,
+                                                                          off + acc_row(v) * (cap * 4), 0, 0);
+                                    group_sum[kb][cb][v] = 0.f;
+                                }
+                            }
+                    }
                 } else {
                     walk(std::integral_constant<int, (kWindow && kColsum) ? 1 : 0>{});
                 }
