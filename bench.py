@@ -6,7 +6,7 @@ already resident in HBM: prompt scoring (vatp_prefill_score), the prompt prune
 for every layer of the workload: by default through vatp_decode_prune_step (two launches, only
 the rows that changed are rewritten), with --decode-route separate through vatp_decode_step +
 vatp_select_compact (three launches, the whole cache is copied every step).  Prints ONE JSON
-line (see the design doc for the byte and flop formulas behind `roofline`).
+line; the byte and flop formulas behind `roofline` are the algorithmic_* functions below.
 """
 from __future__ import annotations
 
