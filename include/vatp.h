@@ -39,7 +39,7 @@ extern "C" {
 
 #define VATP_MAX_BATCH 64          /* sequences per call                                  */
 #define VATP_MAX_UNITS 16384       /* batch * n_heads * max(q_per_kv, 1) per call         */
-#define VATP_MAX_GROUP 8           /* query heads per K/V head (grouped-query attention)  */
+#define VATP_MAX_GROUP 16          /* query heads per K/V head (grouped-query attention)  */
 #define VATP_MAX_CAP   4194304     /* rows per (batch, head) unit: cap and cap_out        */
 
 typedef struct vatp_ctx vatp_ctx;  /* opaque */

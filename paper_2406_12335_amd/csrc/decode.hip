@@ -200,9 +200,10 @@ __global__ __launch_bounds__(256) void decode_logits_group_kernel(
     // bf16 rows of 128 elements: the logits of a group are a (rows x 128) by (128 x g) product and go to the
     // matrix cores (the chunk's rows staged in LDS, every wavefront one 32-row tile); other shapes use FMAs
     constexpr bool kMfma = sizeof(T) == 2 && D == 128;
-    uint4 q_raw[kG];
+    constexpr int kQ = kMfma ? 8 : kG;      // per lane: 8 MFMA steps' worth of one head, or a slice of every head
+    uint4 q_raw[kQ];
 #pragma unroll
-    for (int i = 0; i < kG; ++i) {
+    for (int i = 0; i < kQ; ++i) {
         q_raw[i] = make_uint4(0, 0, 0, 0);
         if constexpr (kMfma) {
             // B operand of MFMA step i: this lane's 8 elements of query head lane & 31 (zero beyond the group)
@@ -250,7 +251,7 @@ __global__ __launch_bounds__(256) void decode_logits_group_kernel(
             }
         }
         if constexpr (kMfma) {
-            static_assert(!kMfma || (kG == 8 && kGroup == 8 && kLanesPerRow == 16), "8 MFMA steps of 16 over the 128 elements");
+            static_assert(!kMfma || (kG <= 32 && kGroup == 8 && kLanesPerRow == 16), "8 MFMA steps of 16 over the 128 elements, a head per column");
             __shared__ uint4 s_k[kDecodeChunk * kLanesPerRow];
 #pragma unroll
             for (int u = 0; u < kGroup; ++u) {
@@ -409,22 +410,13 @@ __global__ __launch_bounds__(256) void decode_finish_kernel(float *__restrict__ 
     // the softmax denominators from the unit's chunk statistics (per wavefront, one round trip)
     const int n_chunks = (n + kDecodeChunk - 1) / kDecodeChunk;
     const float2 *part = ws_part + unit * group * chunks_alloc;
-    float M[kMaxG], L[kMaxG], lse2[kMaxG];
-    merge_group_stats<kMaxG>(part, chunks_alloc, group, n_chunks, M, L, lse2);
+    float lse2[kMaxG];
+    merge_group_stats<kMaxG>(part, chunks_alloc, group, n_chunks, lse2);
     if (r < n) S[unit * cap + r] = s_old + group_weight<kMaxG>(logit, lse2, group);
     // attention output of the new token, per query head: the chunks' partial sums, rescaled to the common maximum
-    if (out && blockIdx.y == 0) {
-        for (int idx = threadIdx.x; idx < group * head_dim; idx += 256) {
-            const int i = idx / head_dim, x = idx % head_dim;
-            float Mi = M[0], Li = L[0];
-#pragma unroll
-            for (int k = 1; k < kMaxG; ++k)
-                if (k == i) { Mi = M[k]; Li = L[k]; }
-            const size_t qh = unit * group + i;
-            out[qh * head_dim + x] = merge_chunk_outputs(ws_out + qh * chunks_alloc * head_dim,
-                                                         part + static_cast<size_t>(i) * chunks_alloc, n_chunks, head_dim, x, Mi, Li);
-        }
-    }
+    if (out && blockIdx.y == 0)
+        merge_group_outputs(out + unit * group * head_dim, ws_out + unit * group * chunks_alloc * head_dim, part, chunks_alloc,
+                            n_chunks, group, head_dim, 256);
 }
 
 }  // namespace
@@ -464,7 +456,8 @@ hipError_t launch_decode(int dtype, int head_dim, const void *q, const void *k, 
 #define VATP_FIN(G)                                                                                               \
     hipLaunchKernelGGL(decode_finish_kernel<G>, fgrid, block, 0, st, S, ws_logit, ws_part, ws_out, out, head_dim, meta, \
                        g.n_heads, g.cap, chunks_alloc, g.group)
-        if (g.group > 4) VATP_FIN(VATP_MAX_GROUP);
+        if (g.group > 8) VATP_FIN(VATP_MAX_GROUP);
+        else if (g.group > 4) VATP_FIN(8);
         else if (g.group > 2) VATP_FIN(4);
         else if (g.group > 1) VATP_FIN(2);
         else VATP_FIN(1);

@@ -70,7 +70,7 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
 
     // the unprotected rows this thread looks at (logit, old score, norm), requested before the
     // denominator is known so that both round trips to memory overlap
-    constexpr int kScan = 4;
+    constexpr int kScan = kMaxG > 8 ? 1 : 4;                 // rows per thread and round trip (each brings kMaxG logits)
     float t_r[kScan][kMaxG], s_r[kScan], w_r[kScan], x_r[kScan];
 #pragma unroll
     for (int u = 0; u < kScan; ++u) {
@@ -85,8 +85,8 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
     // log2 of the softmax denominator of every query head of the group from the chunk statistics
     const int n_chunks = (n + kDecodeChunk - 1) / kDecodeChunk;
     const float2 *part = ws_part + unit * group * chunks_alloc;
-    float M[kMaxG], L[kMaxG], lse2[kMaxG];
-    merge_group_stats<kMaxG>(part, chunks_alloc, group, n_chunks, M, L, lse2);
+    float lse2[kMaxG];
+    merge_group_stats<kMaxG>(part, chunks_alloc, group, n_chunks, lse2);
 
     // new score from the old one, this step's attention weight and (windowed) the weight that leaves;
     // rounding may leave a windowed sum a hair below zero: it is a sum of non-negative terms
@@ -207,18 +207,9 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
     }
 
     // attention output of the new token (optional), per query head: the chunks' partial sums on a common maximum
-    if (out && g == 0) {
-        for (int idx = tid; idx < group * D; idx += kThreads) {
-            const int i = idx / D, x = idx % D;
-            float Mi = M[0], Li = L[0];
-#pragma unroll
-            for (int k = 1; k < kMaxG; ++k)
-                if (k == i) { Mi = M[k]; Li = L[k]; }
-            const size_t qh = unit * group + i;
-            out[qh * D + x] = merge_chunk_outputs(ws_out + qh * chunks_alloc * D, part + static_cast<size_t>(i) * chunks_alloc,
-                                                  n_chunks, D, x, Mi, Li);
-        }
-    }
+    if (out && g == 0)
+        merge_group_outputs(out + unit * group * D, ws_out + unit * group * chunks_alloc * D, part, chunks_alloc, n_chunks,
+                            group, D, kThreads);
 }
 
 // The whole step in one launch, one workgroup of 16 wavefronts per head: logits of the new query
@@ -470,10 +461,11 @@ hipError_t launch_decode_prune(int dtype, int head_dim, const void *K, const voi
                        static_cast<const T *>(V), S, nrm, pos, static_cast<T *>(K_out), static_cast<T *>(V_out), \
                        S_out, nrm_out, pos_out, kept_idx, synced_in, synced_out, ws_logit, ws_part, ws_out, out, \
                        win, meta, g.n_heads, g.cap, g.cap_out, chunks_alloc, g.n_sink, g.recent, g.group)
-    // (instantiated for group sizes up to 2, 4 and 8: the smallest that fits)
+    // (instantiated for group sizes up to 2, 4, 8 and 16: the smallest that fits)
 #define VATP_DP(T, D)                                      \
     do {                                                   \
-        if (g.group > 4) VATP_DPG(T, D, VATP_MAX_GROUP);   \
+        if (g.group > 8) VATP_DPG(T, D, VATP_MAX_GROUP);   \
+        else if (g.group > 4) VATP_DPG(T, D, 8);           \
         else if (g.group > 2) VATP_DPG(T, D, 4);           \
         else if (g.group > 1) VATP_DPG(T, D, 2);           \
         else VATP_DPG(T, D, 1);                            \

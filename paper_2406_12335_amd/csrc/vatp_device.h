@@ -140,12 +140,12 @@ __device__ __forceinline__ float merge_chunk_outputs(const float *__restrict__ w
 // as merge_chunk_stats followed by 2^(t - lse2).
 template <int kMaxG>
 __device__ __forceinline__ void merge_group_stats(const float2 *__restrict__ part, int chunks_alloc, int g,
-                                                  int n_chunks, float (&M)[kMaxG], float (&L)[kMaxG],
-                                                  float (&lse2)[kMaxG])
+                                                  int n_chunks, float (&lse2)[kMaxG])
 {
     if constexpr (kMaxG == 1) {
-        merge_chunk_stats(part, n_chunks, M[0], L[0]);
-        lse2[0] = M[0] + log2f(L[0]);
+        float M, L;
+        merge_chunk_stats(part, n_chunks, M, L);
+        lse2[0] = M + log2f(L);
     } else {
         const int lane = threadIdx.x & 63;
         float2 mine[kMaxG];
@@ -157,7 +157,7 @@ __device__ __forceinline__ void merge_group_stats(const float2 *__restrict__ par
         const float log2g = log2f(static_cast<float>(g));
 #pragma unroll
         for (int i = 0; i < kMaxG; ++i) {
-            M[i] = 0.f; L[i] = 1.f; lse2[i] = 0.f;
+            lse2[i] = 0.f;
             if (i >= g) continue;
             const float2 *pi = part + static_cast<size_t>(i) * chunks_alloc;
             float m = mine[i].x;
@@ -168,10 +168,25 @@ __device__ __forceinline__ void merge_group_stats(const float2 *__restrict__ par
             for (int c = lane + 64; c < n_chunks; c += 64) l += pi[c].y * exp2f(pi[c].x - m);
 #pragma unroll
             for (int off = 32; off > 0; off >>= 1) l += __shfl_xor(l, off);
-            M[i] = m;
-            L[i] = l;
             lse2[i] = m + log2f(l) + log2g;
         }
+    }
+}
+
+// Attention outputs of the new token (paper Eq. 1), one per query head of the unit: thread idx -> (head idx / D,
+// component idx % D).  A wavefront works on one head at a time (D is a multiple of 64 or divides it evenly into
+// whole heads... D = 64 or 128), so it forms that head's softmax statistics itself, by the same operations as above.
+__device__ __forceinline__ void merge_group_outputs(float *__restrict__ out_unit, const float *__restrict__ ws_out_unit,
+                                                    const float2 *__restrict__ part, int chunks_alloc, int n_chunks,
+                                                    int g, int head_dim, int n_threads)
+{
+    for (int idx = threadIdx.x; idx < g * head_dim; idx += n_threads) {
+        const int i = idx / head_dim, x = idx % head_dim;
+        const float2 *pi = part + static_cast<size_t>(i) * chunks_alloc;
+        float M, L;
+        merge_chunk_stats(pi, n_chunks, M, L);
+        out_unit[static_cast<size_t>(i) * head_dim + x] =
+            merge_chunk_outputs(ws_out_unit + static_cast<size_t>(i) * chunks_alloc * head_dim, pi, n_chunks, head_dim, x, M, L);
     }
 }
 

@@ -114,11 +114,11 @@ def test_validate_rejects_unknown_norm():
 
 
 def test_validate_grouped_queries():
-    """q_per_kv: 0 and 1 are plain multi-head attention, up to 8 query heads per K/V head."""
+    """q_per_kv: 0 and 1 are plain multi-head attention, up to 16 query heads per K/V head."""
     import torch
     from paper_2406_12335_amd import binding as B
     for g, call, want in [(0, B.CALL_PREFILL_SCORE, B.OK), (1, B.CALL_DECODE_STEP, B.OK), (8, B.CALL_PREFILL_SCORE, B.OK),
-                          (9, B.CALL_PREFILL_SCORE, B.E_SHAPE), (-1, B.CALL_DECODE_STEP, B.E_SHAPE),
+                          (16, B.CALL_PREFILL_SCORE, B.OK), (17, B.CALL_PREFILL_SCORE, B.E_SHAPE), (-1, B.CALL_DECODE_STEP, B.E_SHAPE),
                           (2, B.CALL_PREFILL_SCORE_WINDOW, B.OK), (4, B.CALL_DECODE_PRUNE_STEP, B.OK)]:
         p = B.Params(1, 4, 128, torch.bfloat16, 2, 8, 128, [40], [50], q_per_kv=g)
         assert B.vatp_validate(p, call) == want, (g, call)

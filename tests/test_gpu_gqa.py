@@ -29,6 +29,8 @@ CASES = [
     ("bf16", 128, 40, 8, 520, 1),       # 4-wavefront workgroups in both passes
     ("bf16", 64, 2, 8, 150, 1),
     ("fp32", 128, 1, 5, 97, 2),
+    ("bf16", 128, 2, 16, 400, 1),       # the largest group: 16 query heads per K/V head
+    ("fp32", 64, 1, 12, 130, 1),
 ]
 
 
@@ -108,7 +110,7 @@ def test_group_of_one_is_plain_multi_head_attention(gpu_device):
 
 
 @pytest.mark.parametrize("dtype,d,g,n0s", [("bf16", 128, 4, [1500, 0, 130]), ("fp32", 64, 3, [300, 127]), ("bf16", 64, 8, [257, 5]),
-                                           ("fp32", 128, 2, [129, 64])])
+                                           ("fp32", 128, 2, [129, 64]), ("bf16", 128, 16, [700, 3]), ("fp32", 64, 16, [200])])
 def test_grouped_decode_step_with_attention_output(gpu_device, dtype, d, g, n0s):
     """vatp_decode_attend_step with groups: every query head gets its own attention output (Eq. 1) over the
     rows of its K/V head; the scores grow by the group mean of the heads' weights."""
@@ -202,8 +204,8 @@ def test_grouped_prompt_scores_from_given_row_lse(gpu_device, dtype, d, g, lens)
 
 def test_group_size_limits(gpu_device):
     lens, bud = [100], [50]
-    for g, call, want in [(9, vatp.CALL_PREFILL_SCORE, B.E_SHAPE), (-1, vatp.CALL_DECODE_STEP, B.E_SHAPE),
-                          (2, vatp.CALL_PREFILL_SCORE_WINDOW, B.OK), (8, vatp.CALL_PREFILL_SCORE, B.OK),
+    for g, call, want in [(17, vatp.CALL_PREFILL_SCORE, B.E_SHAPE), (-1, vatp.CALL_DECODE_STEP, B.E_SHAPE),
+                          (2, vatp.CALL_PREFILL_SCORE_WINDOW, B.OK), (16, vatp.CALL_PREFILL_SCORE, B.OK),
                           (8, vatp.CALL_DECODE_PRUNE_STEP, B.E_BUDGET)]:
         p = vatp.Params(1, 4, 128, torch.bfloat16, 2, 8, 128, lens, bud, q_per_kv=g)
         assert vatp.vatp_validate(p, call) == want, (g, call)
@@ -213,7 +215,8 @@ def test_group_size_limits(gpu_device):
 
 
 @pytest.mark.parametrize("dtype,d,H,g,L,w", [("bf16", 128, 2, 4, 700, 100), ("bf16", 128, 3, 2, 333, 400), ("fp32", 64, 2, 3, 200, 20),
-                                             ("bf16", 128, 9, 8, 1100, 300), ("bf16", 64, 2, 4, 300, 50)])
+                                             ("bf16", 128, 9, 8, 1100, 300), ("bf16", 64, 2, 4, 300, 50),
+                                             ("bf16", 128, 2, 16, 500, 120)])
 def test_grouped_queries_with_history_window(gpu_device, dtype, d, H, g, L, w):
     """Eq. 3 on the group-averaged weights: windowed prompt pass (attention rows averaged over the group), prune that
     carries them along, fused decode steps."""

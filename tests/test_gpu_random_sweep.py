@@ -20,7 +20,7 @@ def _say(msg):
 def _draw(rng, big):
     dtype = "bf16" if big else rng.choice(["bf16", "bf16", "fp32"])
     d = 128 if big else rng.choice([64, 128, 128])
-    g = rng.choice([1, 1, 1, 2, 3, 4, 8])
+    g = rng.choice([1, 1, 1, 2, 3, 4, 8, 16])
     H = rng.choice([1, 2, 9, 33, 70] if big else [1, 2, 3, 5])
     b = rng.choice([1, 1, 2, 3])
     L = rng.choice([255, 257, 700, 1025, 1300, 2049, 2500, 3100] if big else
