@@ -17,7 +17,7 @@
  *     Rows [0, len[b]) of a unit are valid; the others are never read.
  *     len and budget are per sequence; heads that need row counts or budgets of their own
  *     (non-uniform budgets, Implementation Details appendix) are passed as sequences:
- *     [batch, n_heads, ...] with n_heads = 1 and batch = sequences * heads is the same memory.
+ *     [batch, n_heads, ...] with n_heads = 1 and batch = sequences * heads (<= VATP_MAX_BATCH) is the same memory.
  *   - dtype covers Q, K, V and the caches; S and nrm are always float32, pos int32.
  *   - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = the null
  *     stream) and return without synchronising.  Errors that can be seen before launch
@@ -37,7 +37,7 @@
 extern "C" {
 #endif
 
-#define VATP_MAX_BATCH 64          /* sequences per call                                  */
+#define VATP_MAX_BATCH 256         /* sequences per call                                  */
 #define VATP_MAX_UNITS 16384       /* batch * n_heads * max(q_per_kv, 1) per call         */
 #define VATP_MAX_GROUP 16          /* query heads per K/V head (grouped-query attention)  */
 #define VATP_MAX_CAP   4194304     /* rows per (batch, head) unit: cap and cap_out        */

@@ -20,7 +20,7 @@ VATP_F32, VATP_BF16 = 0, 1
 NORM_L1, NORM_L2, NORM_LINF, NORM_NONE = 0, 1, 2, 3
 CALL_PREFILL_SCORE, CALL_DECODE_STEP, CALL_SELECT_COMPACT, CALL_DECODE_ATTEND_STEP, CALL_DECODE_PRUNE_STEP = 0, 1, 2, 3, 4
 CALL_PREFILL_SCORE_WINDOW = 5
-VATP_MAX_BATCH, VATP_MAX_UNITS, VATP_MAX_GROUP = 64, 16384, 16
+VATP_MAX_BATCH, VATP_MAX_UNITS, VATP_MAX_GROUP = 256, 16384, 16
 OK, E_NULL, E_SHAPE, E_DTYPE, E_BUDGET, E_WORKSPACE, E_DEVICE = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = ("vatp_create", "vatp_destroy", "vatp_strerror", "vatp_validate", "vatp_workspace_bytes",

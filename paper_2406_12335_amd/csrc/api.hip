@@ -1,6 +1,7 @@
 // C ABI of libvatp: argument checks, workspace carving and kernel dispatch.
 // Declarations and the contract of every call are in include/vatp.h.
 #include <math.h>
+#include <string.h>
 #include <new>
 
 #include "vatp_device.h"
@@ -74,7 +75,7 @@ void prepare(const vatp_params *p, int which_call, const int32_t *new_pos, Prepa
     const double c = p->scale > 0.f ? static_cast<double>(p->scale) : 1.0 / sqrt(static_cast<double>(p->head_dim));
     g.scale_log2 = static_cast<float>(c * 1.4426950408889634074);
     g.max_len = 0;
-    for (int b = 0; b < VATP_MAX_BATCH; ++b) { out->meta.len[b] = 0; out->meta.aux[b] = 0; }
+    memset(&out->meta, 0, sizeof(out->meta));
     for (int b = 0; b < p->batch; ++b) {
         const int len = p->len[b];
         out->meta.len[b] = len;
@@ -326,8 +327,10 @@ vatp_status decode_prune_impl(vatp_ctx *ctx, const vatp_params *p, const void *q
     const bool one = !out && !win.hist && pr.g.group == 1 && kv_units >= 128 && pr.g.max_len <= 1024 &&
                      pr.g.max_len <= decode_prune_one_max_rows();
     if (one) {
+        BudgetList blist;
+        memcpy(blist.v, budgets.aux, sizeof(blist.v));
         if (launch_decode_prune_one(p->dtype, p->head_dim, q, k, v, K, V, S, nrm, pos, K_out, V_out, S_out, nrm_out,
-                                    pos_out, kept_idx, synced_in, synced_out, pr.meta, budgets, pr.g, stream) !=
+                                    pos_out, kept_idx, synced_in, synced_out, pr.meta, blist, pr.g, stream) !=
             hipSuccess)
             return VATP_E_DEVICE;
         return VATP_OK;

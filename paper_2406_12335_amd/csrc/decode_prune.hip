@@ -227,7 +227,7 @@ __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
     T *__restrict__ V, const float *__restrict__ S, float *__restrict__ nrm, int32_t *__restrict__ pos,
     T *__restrict__ K_out, T *__restrict__ V_out, float *__restrict__ S_out, float *__restrict__ nrm_out,
     int32_t *__restrict__ pos_out, int32_t *__restrict__ kept_idx, const int32_t *__restrict__ synced_in,
-    int32_t *__restrict__ synced_out, BatchMeta len_pos, BatchMeta len_budget, int n_heads, int cap, int cap_out,
+    int32_t *__restrict__ synced_out, BatchMeta len_pos, BudgetList budget, int n_heads, int cap, int cap_out,
     int n_sink, int recent, float scale_log2, int norm)
 {
     constexpr int kE = Elt<T>::kPer16B;
@@ -246,7 +246,7 @@ __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
 
     const size_t unit = blockIdx.x;
     const int b = static_cast<int>(unit / n_heads);
-    const int n0 = len_pos.len[b], n = n0 + 1, B = len_budget.aux[b];
+    const int n0 = len_pos.len[b], n = n0 + 1, B = budget.v[b];
     const int n_keep = n < B ? n : B;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int sub = tid % kLanesPerRow, rloc = tid / kLanesPerRow;
@@ -489,7 +489,7 @@ hipError_t launch_decode_prune_one(int dtype, int head_dim, const void *q, const
                                    void *V, const float *S, float *nrm, int32_t *pos, void *K_out, void *V_out,
                                    float *S_out, float *nrm_out, int32_t *pos_out, int32_t *kept_idx,
                                    const int32_t *synced_in, int32_t *synced_out, const BatchMeta &len_pos,
-                                   const BatchMeta &len_budget, const Geometry &g, hipStream_t st)
+                                   const BudgetList &budget, const Geometry &g, hipStream_t st)
 {
     const unsigned units = static_cast<unsigned>(g.batch) * g.n_heads;
     dim3 grid(units), block(kOneThreads);
@@ -497,7 +497,7 @@ hipError_t launch_decode_prune_one(int dtype, int head_dim, const void *q, const
     hipLaunchKernelGGL((decode_prune_one_kernel<T, D>), grid, block, 0, st, static_cast<const T *>(q),            \
                        static_cast<const T *>(k), static_cast<const T *>(v), static_cast<T *>(K),                \
                        static_cast<T *>(V), S, nrm, pos, static_cast<T *>(K_out), static_cast<T *>(V_out), S_out, \
-                       nrm_out, pos_out, kept_idx, synced_in, synced_out, len_pos, len_budget, g.n_heads, g.cap, \
+                       nrm_out, pos_out, kept_idx, synced_in, synced_out, len_pos, budget, g.n_heads, g.cap,     \
                        g.cap_out, g.n_sink, g.recent, g.scale_log2, g.norm)
     if (dtype == VATP_F32 && head_dim == 64) VATP_DP1(float, 64);
     else if (dtype == VATP_F32) VATP_DP1(float, 128);

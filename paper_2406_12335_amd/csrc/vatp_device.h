@@ -10,11 +10,15 @@ namespace vatp {
 
 typedef uint16_t bf16_t;   // raw bfloat16 bits
 
-// Per-sequence host facts, passed to kernels by value (lives in the kernarg segment,
-// read with scalar loads indexed by blockIdx.z): no device copy, no sync.
+// Per-sequence host facts, passed to kernels by value (lives in the kernarg segment, 2 KiB of the 4 KiB a
+// launch may carry, read with scalar loads): no device copy, no sync.
 struct BatchMeta {
     int32_t len[VATP_MAX_BATCH];   // rows valid per sequence on entry
     int32_t aux[VATP_MAX_BATCH];   // budget (select/compact) or new_pos (decode)
+};
+
+struct BudgetList {                // the third per-sequence fact of the one-launch decode-and-evict kernel
+    int32_t v[VATP_MAX_BATCH];
 };
 
 struct Geometry {
@@ -254,7 +258,7 @@ hipError_t launch_decode_prune_one(int dtype, int head_dim, const void *q, const
                                    void *V, const float *S, float *nrm, int32_t *pos, void *K_out, void *V_out,
                                    float *S_out, float *nrm_out, int32_t *pos_out, int32_t *kept_idx,
                                    const int32_t *synced_in, int32_t *synced_out, const BatchMeta &len_pos,
-                                   const BatchMeta &len_budget, const Geometry &g, hipStream_t st);
+                                   const BudgetList &budget, const Geometry &g, hipStream_t st);
 
 hipError_t launch_select(const float *S, const float *nrm, int32_t *kept_idx,
                          const BatchMeta &meta, const Geometry &g, hipStream_t st);

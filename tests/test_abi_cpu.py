@@ -45,7 +45,7 @@ def test_validate_accepts_good_params():
     (dict(dtype=7), 0, binding.E_DTYPE),
     (dict(head_dim=96), 0, binding.E_SHAPE),
     (dict(batch=0, len=[], budget=[]), 0, binding.E_SHAPE),
-    (dict(batch=65, len=[1] * 65, budget=[32] * 65), 0, binding.E_SHAPE),
+    (dict(batch=257, len=[1] * 257, budget=[32] * 257), 0, binding.E_SHAPE),
     (dict(n_heads=16384), 0, binding.E_SHAPE),
     (dict(len=[65, 1]), 0, binding.E_SHAPE),
     (dict(len=[-1, 1]), 0, binding.E_SHAPE),

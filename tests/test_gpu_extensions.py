@@ -127,3 +127,16 @@ def test_per_head_budgets_by_passing_heads_as_sequences(gpu_device, fused):
     rep = parity.run_trajectory(inp, gpu_device, fused=fused)
     _say("report %r" % rep)
     assert rep.prune_events == H * 13
+
+
+@pytest.mark.parametrize("fused,window", [(False, None), (True, None), (True, 20)])
+def test_batch_of_256_sequences(gpu_device, fused, window):
+    """The per-call limit: 256 sequences of their own lengths and budgets (also what lets a whole layer of
+    8 x 32 heads be handed over with one budget per head)."""
+    cfg = vs.scaled(vs.CONFIGS["ragged16"], batch=256, n_heads=1, ragged=(1, 300), recent=8, decode_steps=6)
+    inp = vs.make_inputs(cfg, seed=31)
+    inp.budgets = [max(b, cfg.n_sinks + cfg.recent) for b in inp.budgets]
+    _say("256 sequences, fused=%s window=%s, lens %s..." % (fused, window, inp.lens[:6]))
+    units = [(b, 0) for b in (0, 1, 63, 64, 65, 128, 200, 255)]
+    rep = parity.run_trajectory(inp, gpu_device, units=units, fused=fused, window=window)
+    _say("report %r" % rep)
