@@ -132,3 +132,19 @@ def test_validate_grouped_queries():
         assert B.vatp_workspace_bytes(None, p4, call) == 4 * B.vatp_workspace_bytes(None, p1, call)
     # (the prompt pass also keeps room for partial column sums of a group: as much again)
     assert B.vatp_workspace_bytes(None, p4, B.CALL_PREFILL_SCORE) == 8 * B.vatp_workspace_bytes(None, p1, B.CALL_PREFILL_SCORE)
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/vatp.h compiles as C99 with nothing but the standard headers, and a C caller can take the address
+    of every entry point it declares."""
+    import os
+    import subprocess
+    from paper_2406_12335_amd import binding as B
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "use_vatp.c"
+    lines = ['#include "vatp.h"', "typedef void (*fn)(void);", "fn table[] = {"]
+    lines += ["    (fn)%s," % name for name in B.EXPORTS]
+    lines += ["};", "int n_entries(void) { vatp_params p; p.q_per_kv = 0; (void)p; return (int)(sizeof table / sizeof table[0]); }"]
+    src.write_text("\n".join(lines) + "\n")
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(root, "include"),
+                           "-c", str(src), "-o", str(tmp_path / "use_vatp.o")])
