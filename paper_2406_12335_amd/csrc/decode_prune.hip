@@ -88,11 +88,13 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
     float lse2[kMaxG];
     merge_group_stats<kMaxG>(part, chunks_alloc, group, n_chunks, lse2);
 
-    // new score from the old one, this step's attention weight and (windowed) the weight that leaves;
-    // rounding may leave a windowed sum a hair below zero: it is a sum of non-negative terms
+    // new score from the old one, this step's attention weight and (windowed) the weight that leaves.  The
+    // leaving weight is subtracted first: when it is most of the old sum the difference is exact and the small
+    // new weight is not rounded away against the large old one (with a window of one step the score is then
+    // exactly the new weight).  Rounding may still leave a windowed sum a hair below zero: it is a sum of
+    // non-negative terms, and its bits are compared as unsigned integers.
     auto combine = [&](float s_old, float p, float gone) {
-        const float s = s_old + p;
-        return windowed ? fmaxf(s - gone, 0.f) : s;
+        return windowed ? fmaxf((s_old - gone) + p, 0.f) : s_old + p;
     };
 
     // the row that leaves: minimise (importance bits, ~row) over the unprotected rows
