@@ -1,5 +1,6 @@
 """Seeded random configurations through the trajectory harness: dtype, head dimension, query heads per K/V head,
-ragged batches, prompt lengths around the tile sizes, budgets down to F + R, both decode routes, history windows."""
+ragged batches, prompt lengths around the tile sizes, budgets down to F + R, both decode routes, history windows,
+value norms, cache capacity beyond the budget."""
 import random
 import sys
 
@@ -34,20 +35,22 @@ def _draw(rng, big):
     ragged = (1, L) if rng.random() < 0.4 and L > 1 else None
     cfg = vs.scaled(vs.CONFIGS["llama7b_layer"], batch=b, n_heads=H, head_dim=d, prompt_len=L, dtype=dtype, n_sinks=min(F, L),
                     budget_pct=pct, recent=R, decode_steps=T, q_per_kv=g, ragged=ragged)
-    return cfg, F, R, fused, window, rng.randrange(1 << 20)
+    return cfg, F, R, fused, window, rng.randrange(1 << 20), rng.choice([0, 0, 1, 2, 3]), rng.choice([None, None, 1, 7, 130])
 
 
 @pytest.mark.parametrize("big,count,seed", [(False, 150, 11), (True, 16, 12)])
 def test_random_configurations(gpu_device, big, count, seed):
     rng = random.Random(seed)
     for case in range(count):
-        cfg, F, R, fused, window, sd = _draw(rng, big)
+        cfg, F, R, fused, window, sd, norm_kind, slack = _draw(rng, big)
         inp = vs.make_inputs(cfg, seed=sd)
         inp.budgets = [max(B, F + R) for B in inp.budgets]
         _say("%d: %s d=%d g=%d H=%d lens=%s R=%d F=%d B=%s T=%d fused=%s window=%s seed=%d" % (
             case, cfg.dtype, cfg.head_dim, cfg.q_per_kv, cfg.n_heads, inp.lens, R, F, inp.budgets, cfg.decode_steps, fused,
-            window, sd))
+            window, sd) + " norm=%d slack=%s" % (norm_kind, slack))
         units = None
         if big:
             units = [(bb, hh) for bb in range(cfg.batch) for hh in sorted({0, cfg.n_heads - 1})][:3]
-        parity.run_trajectory(inp, gpu_device, fused=fused, window=window, n_sink=F, units=units)
+        cap_cache = None if slack is None else max(inp.budgets) + 1 + slack        # rows allocated beyond the budget
+        parity.run_trajectory(inp, gpu_device, fused=fused, window=window, n_sink=F, units=units, norm_kind=norm_kind,
+                              cap_cache=cap_cache)
