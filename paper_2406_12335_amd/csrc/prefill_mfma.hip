@@ -44,6 +44,15 @@
 // window's attention rows (row j - j_first of a [w+1, cap] matrix per head) through a buffer
 // descriptor whose bounds check drops the rows outside the window by itself.
 //
+// Grouped queries (g query heads per K/V head; paper, Limitations section): the token score is the mean over
+// the group of the heads' column sums.  Row statistics are per query head (one unit per query head, streaming
+// its K/V head's keys).  The column-sum pass keeps one unit per K/V head (kGrouped): a job streams the queries
+// of the group's heads one after the other into the same accumulators, so K is loaded once per group; on a
+// small grid the heads are dealt out to several workgroups whose partial sums a small kernel adds.  With a
+// history window the heads go innermost instead (every 64-row stage of queries once per head): a lane then
+// meets the same (query, key) entries of all heads in turn, adds their weights in registers and stores the
+// stage's attention rows, already averaged, once.
+//
 // The contraction index (head dimension) may be permuted freely as long as both operands
 // agree: lane half g takes the 16-byte chunk  s + 8g  of a row for MFMA step s.
 #include <type_traits>
