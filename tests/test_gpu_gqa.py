@@ -263,3 +263,13 @@ def test_grouped_queries_at_model_size_batch8(gpu_device):
     for fused in (True, False):
         rep = parity.run_trajectory(inp, gpu_device, units=[(0, 0), (7, 7), (3, 4)], fused=fused, check_every=4)
         _say("report %r" % rep)
+
+
+def test_grouped_history_window_at_long_prompt(gpu_device):
+    """8 K/V heads x 4 query heads, 32768 prompt tokens, w = 400: windowed row statistics over 16 key ranges per query
+    head, heads-innermost column sums over 128 key blocks; sampled units through prompt pass, prune and fused steps."""
+    cfg = vs.scaled(vs.CONFIGS["long32k"], n_heads=8, q_per_kv=4, decode_steps=6)
+    inp = vs.make_inputs(cfg, seed=13, device=gpu_device)
+    _say("gqa window at L=32768")
+    rep = parity.run_trajectory(inp, gpu_device, units=[(0, 0), (0, 7)], fused=True, window=400, check_every=2)
+    _say("report %r" % rep)
