@@ -71,11 +71,21 @@ def test_fused_step_is_bit_identical_to_separate_calls_with_groups(gpu_device, d
         for c in caches:
             c.prefill_score(Q, K, V, inp.lens)
             c.prune_prompt(K, V)
+        ws_att = torch.empty(vatp.vatp_workspace_bytes(caches[0].ctx, caches[0]._p_dec, vatp.CALL_DECODE_ATTEND_STEP) + 256,
+                             dtype=torch.uint8, device=dev)
         for t in range(T):
-            caches[0].decode_step(qd[t], kd[t], vd[t], [L + t])
-            caches[0].prune()
-            caches[1].decode_prune_step(qd[t], kd[t], vd[t], [L + t])
+            # separate calls, with the attention output of every query head; fused call likewise
+            out_c = torch.zeros(1, H * g, d, device=dev)
+            out_f = torch.ones(1, H * g, d, device=dev)
+            a = caches[0]
+            a._p_dec.set_len(a.lens)
+            vatp.vatp_decode_attend_step(a.ctx, a._p_dec, qd[t], kd[t], vd[t], a.K[a.cur], a.V[a.cur], a.S[a.cur], a.nrm[a.cur],
+                                         a.pos[a.cur], [L + t], out_c, ws_att)
+            a.lens = [n + 1 for n in a.lens]
+            a.prune()
+            caches[1].decode_prune_step(qd[t], kd[t], vd[t], [L + t], out=out_f)
             torch.cuda.synchronize()
+            assert torch.equal(out_c, out_f), "attention outputs differ at step %d" % t
             n = caches[0].lens[0]
             assert caches[1].lens[0] == n
             a, b = caches[0], caches[1]
