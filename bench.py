@@ -3,10 +3,16 @@
 One "step" is one pass of the whole hot path over one batch of synthetic input that is
 already resident in HBM: prompt scoring (vatp_prefill_score), the prompt prune
 (vatp_select_compact), then T decode steps, each followed by the eviction back to the budget,
-for every layer of the workload: by default through vatp_decode_prune_step (two launches, only
-the rows that changed are rewritten), with --decode-route separate through vatp_decode_step +
-vatp_select_compact (three launches, the whole cache is copied every step).  Prints ONE JSON
-line; the byte and flop formulas behind `roofline` are the algorithmic_* functions below.
+for every layer of the workload: by default through vatp_decode_prune_step (only the rows that
+changed are rewritten), with --decode-route separate through vatp_decode_step +
+vatp_select_compact (three launches, the whole cache is copied every step).
+
+The default workload is the largest one that fits one GPU, llama7b_stack (32 layers, batch 8,
+prompt 4096, 256 decode steps: 25.8 GB of prompt tensors, 2.3 GB touched per token step), whose
+figures are the headline fields of the ONE JSON line printed.  With the default workload the
+line also carries `per_workload`: the same measurements, in short, for the other four named
+workloads (fewer timed steps each).  The byte and flop formulas behind `roofline` are the
+algorithmic_* functions below.
 """
 from __future__ import annotations
 
@@ -15,6 +21,7 @@ import json
 import os
 import sys
 import time
+import traceback
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
@@ -65,20 +72,25 @@ def algorithmic_bytes_window(cfg, n_rows, window, rows_moved):
     return 12 * n_rows + 4 * window + 8 * rows_moved
 
 
-def run(args):
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (got --gpus %d)" % args.gpus, file=sys.stderr)
-        sys.exit(2)
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(2)
+def fused_step_kernels(cfg, lens, budgets, window):
+    """Names of the kernels one vatp_decode_prune_step call launches for this workload (the library's rule:
+    a single launch with one workgroup per head when there are at least 128 heads of at most 1024 rows and
+    neither grouped queries nor a history window; otherwise the logits launch plus the evict-and-copy launch)."""
+    rows = max(min(L, B) for L, B in zip(lens, budgets)) + 1
+    if window is None and cfg.q_per_kv == 1 and cfg.batch * cfg.n_heads >= 128 and rows <= 1024:
+        return "decode_prune_one_kernel"
+    first = "decode_logits_group_kernel" if cfg.q_per_kv > 1 else "decode_logits_kernel"
+    return first + " + decode_prune_kernel"
+
+
+def measure(args, workload, steps, warmup, main_line):
+    """Runs one workload and returns its JSON object.  main_line: this is the workload of the headline fields
+    (machine yardsticks, input digests and the CPU baseline are taken only there)."""
     from paper_2406_12335_amd.runner import PrunedKVCache
     import paper_2406_12335_amd as vatp
-    vatp.load()
 
     dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-    cfg = vs.CONFIGS[args.workload]
+    cfg = vs.CONFIGS[workload]
     if args.layers:
         cfg = vs.scaled(cfg, layers=args.layers)
     if args.decode_steps is not None:
@@ -90,10 +102,11 @@ def run(args):
     T = cfg.decode_steps
     fused = args.decode_route == "fused"
     window = args.window
-    if window is not None and not fused:
-        print("bench.py: history-window scores run through the fused decode route only", file=sys.stderr)
-        sys.exit(2)
     layers = [vs.make_inputs(cfg, seed=args.seed, layer=l, device=dev) for l in range(cfg.layers)]
+    digests = {}
+    if main_line:
+        for l in range(min(cfg.layers, args.digest_layers)):
+            digests.update({"layer%d.%s" % (l, k): v[:16] for k, v in vs.buffer_digests(layers[l]).items()})
     lens, budgets = layers[0].lens, layers[0].budgets
     for inp in layers:      # per-step views of the new tokens, made once (indexing costs host time per call)
         inp.step_qkv = [(inp.qd[t], inp.kd[t], inp.vd[t]) for t in range(T)]
@@ -121,14 +134,15 @@ def run(args):
         for t in range(T):
             for inp, cache in zip(layers, caches):
                 if fused:
-                    cache.decode_prune_step(*inp.step_qkv[t], new_pos[t], want_kept_idx=False)
+                    cache.decode_prune_step(*inp.step_qkv[t], new_pos[t])
                 else:
                     cache.decode_step(*inp.step_qkv[t], new_pos[t])
                     cache.prune()
         if ev is not None:
             ev["decode_loop"].append((e3, mark()))
 
-    if args.copy_calibration:
+    copy_gbps = gemm_tflops = None
+    if args.copy_calibration and main_line:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)          # 256 MiB
         dst = torch.empty_like(src)
         for _ in range(3):
@@ -136,51 +150,52 @@ def run(args):
         torch.cuda.synchronize()
         del src, dst
 
-    # yardstick beside the data-sheet HBM figure: what a plain device-to-device copy reaches here
-    src = torch.empty(128 * 1024 * 1024, dtype=torch.float32, device=dev).normal_()      # 512 MiB
-    dst = torch.empty_like(src)
-    for _ in range(3):
-        dst.copy_(src)
-    torch.cuda.synchronize()
-    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    c0.record()
-    for _ in range(10):
-        dst.copy_(src)
-    c1.record()
-    torch.cuda.synchronize()
-    copy_gbps = 10 * 2 * src.numel() * 4 / (c0.elapsed_time(c1) * 1e-3) / 1e9
-    del src, dst
-    # the vendor library's bf16 GEMM (8192^3, random operands): what the matrix cores sustain here on a plain product
-    ga = torch.randn(8192, 8192, device=dev).to(torch.bfloat16)
-    gb = torch.randn(8192, 8192, device=dev).to(torch.bfloat16)
-    for _ in range(3):
-        gc = torch.matmul(ga, gb)
-    torch.cuda.synchronize()
-    c0.record()
-    for _ in range(5):
-        gc = torch.matmul(ga, gb)
-    c1.record()
-    torch.cuda.synchronize()
-    gemm_tflops = 5 * 2 * 8192 ** 3 / (c0.elapsed_time(c1) * 1e-3) / 1e12
-    del ga, gb, gc
+    if main_line:
+        # yardstick beside the data-sheet HBM figure: what a plain device-to-device copy reaches here
+        src = torch.empty(128 * 1024 * 1024, dtype=torch.float32, device=dev).normal_()      # 512 MiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        c0.record()
+        for _ in range(10):
+            dst.copy_(src)
+        c1.record()
+        torch.cuda.synchronize()
+        copy_gbps = 10 * 2 * src.numel() * 4 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+        del src, dst
+        # the vendor library's bf16 GEMM (8192^3, random operands): what the matrix cores sustain here on a plain product
+        ga = torch.randn(8192, 8192, device=dev).to(torch.bfloat16)
+        gb = torch.randn(8192, 8192, device=dev).to(torch.bfloat16)
+        for _ in range(3):
+            gc = torch.matmul(ga, gb)
+        torch.cuda.synchronize()
+        c0.record()
+        for _ in range(5):
+            gc = torch.matmul(ga, gb)
+        c1.record()
+        torch.cuda.synchronize()
+        gemm_tflops = 5 * 2 * 8192 ** 3 / (c0.elapsed_time(c1) * 1e-3) / 1e12
+        del ga, gb, gc
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         one_step()
     torch.cuda.synchronize()
     ev = {"prefill_score": [], "prompt_prune": [], "decode_loop": []}
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         one_step(ev)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
+    ms_per_step = wall * 1e3 / steps
 
     def total_ms(pairs):
         return sum(a.elapsed_time(b) for a, b in pairs)
 
-    prefill_ms = total_ms(ev["prefill_score"]) / args.steps          # all layers of one step
-    prune_ms = total_ms(ev["prompt_prune"]) / args.steps
-    decode_ms = total_ms(ev["decode_loop"]) / args.steps
+    prefill_ms = total_ms(ev["prefill_score"]) / steps          # all layers of one step
+    prune_ms = total_ms(ev["prompt_prune"]) / steps
+    decode_ms = total_ms(ev["decode_loop"]) / steps
 
     # Replays outside the timed region.  Each is a loop bracketed by ONE pair of events on the stream
     # the library launches on (event pairs around single calls inside a deep queue proved unreliable).
@@ -240,7 +255,7 @@ def run(args):
         t_host = time.perf_counter()
         for t in range(T):
             for inp, cache in zip(layers, caches):
-                cache.decode_prune_step(*inp.step_qkv[t], new_pos[t], want_kept_idx=False)
+                cache.decode_prune_step(*inp.step_qkv[t], new_pos[t])
         host_us_per_call = (time.perf_counter() - t_host) * 1e6 / n_calls    # enqueue only, no sync yet
     reset()
     fused_call_ms = timed(fused_loop) / n_calls
@@ -248,7 +263,7 @@ def run(args):
     for t in range(T):
         for inp, cache in zip(layers, caches):
             n_after = [n + 1 for n in cache.lens]
-            cache.decode_prune_step(*inp.step_qkv[t], new_pos[t], want_kept_idx=False)
+            cache.decode_prune_step(*inp.step_qkv[t], new_pos[t])
             first = torch.minimum(cache.synced[0], cache.synced[1]).view(cfg.batch, cfg.n_heads).cpu()
             for bb in range(cfg.batch):
                 keep = min(n_after[bb], budgets[bb])
@@ -280,39 +295,50 @@ def run(args):
 
     mfma = cfg.dtype == "bf16"
     peak_tf = MFMA_BF16_PEAK_TFLOPS if mfma else FP32_VECTOR_PEAK_TFLOPS
-    traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name, cfg.layers), {})
+    profiled = PROFILED_TRAFFIC_BYTES.get(cfg.name if window is None and cfg.q_per_kv == 1 else None, {})
+    traffic = profiled.get("bytes_per_call", {})
     prefill_tflops = flops / (prefill_ms * 1e-3) / 1e12 if prefill_ms > 0 else 0.0
-    roof_prefill = {"kernel": "vatp_prefill_score = prefill rowstat + prefill colsum (value norms inside)" if window is None
+    prefill_kernels = "prefill_mfma_kernel<rowstat> + prefill_mfma_kernel<colsum, value norms inside>" \
+        if mfma and cfg.head_dim == 128 else "l1norm_kernel + prefill_rowstat_generic + prefill_colsum_generic"
+    roof_prefill = {"kernel": "vatp_prefill_score = " + prefill_kernels if window is None
                     else "vatp_prefill_score_window = rowstat over key ranges + merge + colsum with rows and norms",
                     "bound": "mfma" if mfma else "alu",
                     "achieved": round(prefill_tflops, 3), "peak": peak_tf, "unit": "TFLOP/s",
                     "frac": round(prefill_tflops / peak_tf, 5), "traffic": traffic.get("prefill_score"),
-                    "avg_launch_ms": round(prefill_ms / cfg.layers, 5)}
+                    "avg_launch_ms": round(prefill_ms / cfg.layers, 5),
+                    # both passes recompute the logits; the rate of distinct (query, key) products is half of `achieved`
+                    "single_pass_TFLOPs": round(prefill_tflops / 2, 3)}
     loop_bytes = fused_bytes if fused else dec_bytes + sel_bytes
     decode_gbps = loop_bytes / (decode_ms * 1e-3) / 1e9 if decode_ms > 0 and T else 0.0
-    fused_gbps = fused_bytes / n_calls / (fused_call_ms * 1e-3) / 1e9 if T and fused_call_ms > 0 else 0.0
-    roof_fused = {"kernel": "vatp_decode_prune_step = decode_logits_kernel + decode_prune_kernel", "bound": "hbm",
+    # the fused call's duration: from the events around the decode loops of the timed steps when that loop ran
+    # through it (the default), else from the replay
+    fused_ms_per_call = decode_ms / n_calls if fused and T else fused_call_ms
+    fused_gbps = fused_bytes / n_calls / (fused_ms_per_call * 1e-3) / 1e9 if T and fused_ms_per_call > 0 else 0.0
+    fused_kernels = fused_step_kernels(cfg, lens, budgets, window)
+    roof_fused = {"kernel": ("vatp_decode_prune_step = " if window is None else "vatp_decode_prune_step_window = ") + fused_kernels,
+                  "bound": "hbm",
                   "achieved": round(fused_gbps, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                   "frac": round(fused_gbps / HBM_PEAK_GBPS, 5), "traffic": traffic.get("decode_prune_step"),
-                  "avg_launch_ms": round(fused_call_ms, 5),
+                  "avg_launch_ms": round(fused_ms_per_call, 5),
+                  "algorithmic_bytes_per_call": int(fused_bytes / n_calls),
                   "host_enqueue_us_per_call": round(host_us_per_call, 2),
                   # for orientation only, not used in `achieved`: the bytes the out-of-place route moves for the
                   # same step (K read, S read + written, whole cache copied), over this route's time
-                  "out_of_place_equivalent_GBps": round((dec_bytes + sel_bytes) / n_calls / (fused_call_ms * 1e-3) / 1e9, 2)
-                  if T and fused_call_ms > 0 and window is None else None,
+                  "out_of_place_equivalent_GBps": round((dec_bytes + sel_bytes) / n_calls / (fused_ms_per_call * 1e-3) / 1e9, 2)
+                  if T and fused_ms_per_call > 0 and window is None else None,
                   "rows_moved_per_head_step": round(fused_rows_moved / max(1, n_calls * cfg.batch * cfg.n_heads), 2)}
     dec_k_gbps = dec_call_bytes / (dec_call_ms * 1e-3) / 1e9 if T and dec_call_ms > 0 else 0.0
     sel_k_gbps = sel_call_bytes / (sel_call_ms * 1e-3) / 1e9 if T and sel_call_ms > 0 else 0.0
     roof_decode = {"kernel": "vatp_decode_step = decode_logits_kernel + decode_finish_kernel", "bound": "hbm",
                    "achieved": round(dec_k_gbps, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                    "frac": round(dec_k_gbps / HBM_PEAK_GBPS, 5), "traffic": traffic.get("decode_step"),
-                   "avg_launch_ms": round(dec_call_ms, 5)}
+                   "avg_launch_ms": round(dec_call_ms, 5), "algorithmic_bytes_per_call": dec_call_bytes}
     roof_gather = {"kernel": "vatp_select_compact = gather_kernel (evict-one select + compact)", "bound": "hbm",
                    "achieved": round(sel_k_gbps, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                    "frac": round(sel_k_gbps / HBM_PEAK_GBPS, 5), "traffic": traffic.get("select_compact"),
-                   "avg_launch_ms": round(sel_call_ms, 5)}
+                   "avg_launch_ms": round(sel_call_ms, 5), "algorithmic_bytes_per_call": sel_call_bytes}
     if fused:
-        phases = {"prefill_score": prefill_ms, "decode_prune_step": fused_call_ms * n_calls}
+        phases = {"prefill_score": prefill_ms, "decode_prune_step": fused_ms_per_call * n_calls}
     else:
         phases = {"prefill_score": prefill_ms, "decode_step": dec_call_ms * n_calls,
                   "select_compact": sel_call_ms * n_calls}
@@ -320,15 +346,15 @@ def run(args):
     roofline_all = {"prefill_score": roof_prefill, "decode_prune_step": roof_fused}
     if window is None:
         roofline_all.update({"decode_step": roof_decode, "select_compact": roof_gather})
-    else:
-        roof_fused["kernel"] = "vatp_decode_prune_step_window = decode_logits_kernel + decode_prune_kernel (history window)"
-    roofline = roofline_all[dominant]
+    roofline = dict(roofline_all[dominant])
+    # `traffic` is not counted in this run: it is the figure of the committed rocprofv3 counter summary named here
+    roofline["traffic_source"] = profiled.get("source") if roofline.get("traffic") is not None else None
 
     out = {
         "metric": "prefill scoring tokens/s (% MFMA peak) + decode prune step GB/s (% HBM peak)",
         "value": round(n_tokens / (prefill_ms * 1e-3), 1) if prefill_ms > 0 else 0.0,
         "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if mfma else "f32", "data": "synthetic",
@@ -337,42 +363,84 @@ def run(args):
                    "head_dim": cfg.head_dim, "prompt_len": lens if cfg.ragged else cfg.prompt_len,
                    "budget_pct": cfg.budget_pct, "recent": cfg.recent, "n_sink": cfg.n_sink_keep,
                    "decode_steps": T, "decode_route": args.decode_route, "score": "accumulated (Eq. 2)" if window is None
-                   else "history window w=%d (Eq. 3)" % window},
+                   else "history window w=%d (Eq. 3)" % window,
+                   "kept_idx_written_every_step": True},
         "prefill_ms": round(prefill_ms, 4), "prompt_prune_ms": round(prune_ms, 4), "decode_loop_ms": round(decode_ms, 4),
         "prefill_pct_mfma_peak": round(100 * roof_prefill["frac"], 3) if mfma else None,
         "decode_prune_GBps": round(decode_gbps, 2),
         "decode_prune_pct_hbm_peak": round(100 * decode_gbps / HBM_PEAK_GBPS, 3),
-        # read + write rate of a plain 512 MiB device copy (torch copy_) on this machine, for comparison with
-        # the 8000 GB/s data-sheet figure the fractions are taken against
-        "measured_copy_GBps": round(copy_gbps, 1),
-        # rate of the vendor library's 8192^3 bf16 GEMM on this machine, beside the 2500 TFLOP/s data-sheet figure
-        "measured_gemm_TFLOPs": round(gemm_tflops, 1),
         "roofline": roofline,
         "roofline_all": roofline_all,
-        # the same decode loop through the other route (per-call event times of the replays)
+        # the same decode loop through either route (event times of replays outside the timed steps)
         "decode_loop_ms_by_route": {"fused": round(fused_call_ms * n_calls / 1, 4),
                                     "separate": round(sep_loop_ms, 4) if window is None else None},
     }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, layers[0], args.cpu_seconds)
+    if main_line:
+        # read + write rate of a plain 512 MiB device copy (torch copy_) on this machine, for comparison with
+        # the 8000 GB/s data-sheet figure the fractions are taken against
+        out["measured_copy_GBps"] = round(copy_gbps, 1)
+        # rate of the vendor library's 8192^3 bf16 GEMM on this machine, beside the 2500 TFLOP/s data-sheet figure
+        out["measured_gemm_TFLOPs"] = round(gemm_tflops, 1)
+        # first 16 hex digits of the SHA-256 of each generated buffer (seed %d; see vatp_synth.buffer_digests)
+        out["input_sha256"] = digests
+        if not args.no_cpu_baseline:
+            out["cpu_baseline"] = cpu_baseline(cfg, layers[0], args.cpu_seconds)
     for c in caches:
         c.close()
     vatp.vatp_destroy(ctx)
+    return out
+
+
+def condensed(r):
+    """The figures of one workload that go into `per_workload`."""
+    keep = ("kernel", "bound", "achieved", "peak", "unit", "frac", "traffic", "avg_launch_ms")
+    return {"config": r["config"], "dtype": r["dtype"], "steps": r["steps"], "warmup": r["warmup"],
+            "value": r["value"], "unit": r["unit"], "ms_per_step": r["ms_per_step"],
+            "prefill_ms": r["prefill_ms"], "prompt_prune_ms": r["prompt_prune_ms"], "decode_loop_ms": r["decode_loop_ms"],
+            "decode_loop_ms_by_route": r["decode_loop_ms_by_route"],
+            "roofline_all": {k: {f: v[f] for f in keep} for k, v in r["roofline_all"].items()}}
+
+
+def run(args):
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (got --gpus %d)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    if args.window is not None and args.decode_route != "fused":
+        print("bench.py: history-window scores run through the fused decode route only", file=sys.stderr)
+        sys.exit(2)
+    import paper_2406_12335_amd as vatp
+    vatp.load()
+    torch.cuda.set_device(0)
+    out = measure(args, args.workload, args.steps, args.warmup, True)
+    overridden = any(v is not None for v in (args.batch, args.budget_pct, args.recent, args.heads, args.q_per_kv,
+                                             args.decode_steps, args.window)) or args.layers
+    if args.workload == DEFAULT_WORKLOAD and not args.no_per_workload and not overridden:
+        # the other named workloads, in short; a failure there is reported in its entry and does not cost the line
+        out["per_workload"] = {}
+        for name in ("tiny", "llama7b_layer", "long32k", "ragged16"):
+            torch.cuda.empty_cache()
+            try:
+                out["per_workload"][name] = condensed(measure(args, name, args.other_steps, 1, False))
+            except Exception as e:      # noqa: BLE001
+                out["per_workload"][name] = {"error": "%s: %s" % (type(e).__name__, e),
+                                             "traceback": traceback.format_exc().splitlines()[-3:]}
     print(json.dumps(out), flush=True)
 
 
-# HBM bytes per launch (fetch + write) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# file, scaled by what the same counters read for the plain copy of --copy-calibration
-# (FETCH_SIZE x2.000, WRITE_SIZE x1.000); summaries under profiles/.  Keyed by (workload, layers).
-MEASURED_TRAFFIC_BYTES = {
-    # calibrated fetch + write bytes per call of the entry point (all of its kernels); a call works on one layer, so
-    # the figures counted on 2 layers of llama7b_stack also stand for its 32
-    ("llama7b_layer", 1): {"prefill_score": 184034008, "decode_step": 18055946, "select_compact": 72839875,
-                           "decode_prune_step": 21056138},
-    ("llama7b_stack", 2): {"prefill_score": 2067373001, "decode_step": 57727981, "select_compact": 233069566,
-                           "decode_prune_step": 71390000},
+DEFAULT_WORKLOAD = "llama7b_stack"
+
+# HBM bytes per call of an entry point (fetch + write, all of its kernels), as counted by rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE runs of this file and scaled by what the same counters read for the plain copy of
+# --copy-calibration.  NOT measured by the run that prints them: a static table, copied from the committed
+# summary named in "source", which also gives the commands and the commit of the kernels they were counted on.
+PROFILED_TRAFFIC_BYTES = {
+    "llama7b_layer": {"source": "profiles/hbm_traffic_fetch_write.md",
+                      "bytes_per_call": {"prefill_score": 184034008, "decode_step": 18055946,
+                                         "select_compact": 72839875, "decode_prune_step": 21056138}},
 }
-MEASURED_TRAFFIC_BYTES[("llama7b_stack", 32)] = MEASURED_TRAFFIC_BYTES[("llama7b_stack", 2)]
 
 
 def cpu_baseline(cfg, inp, budget_s):
@@ -437,7 +505,12 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="llama7b_layer", choices=sorted(vs.CONFIGS))
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(vs.CONFIGS))
+    ap.add_argument("--no-per-workload", action="store_true",
+                    help="with the default workload: leave out the short measurements of the other four workloads")
+    ap.add_argument("--other-steps", type=int, default=3, help="timed steps of each workload in per_workload")
+    ap.add_argument("--digest-layers", type=int, default=1,
+                    help="layers whose generated buffers are hashed (SHA-256) into the line; 0 = none")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers of the workload")
     ap.add_argument("--decode-steps", type=int, default=None)
     ap.add_argument("--batch", type=int, default=None, help="override the batch size of the workload")

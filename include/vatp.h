@@ -52,7 +52,8 @@ typedef enum {
     VATP_E_BUDGET = -4,      /* budget[b] < n_sink + recent, survivors exceed cap_out (or  */
                              /* cap_hist), or a fused step would have to remove two rows  */
     VATP_E_WORKSPACE = -5,   /* workspace missing, too small or not 256-byte aligned       */
-    VATP_E_DEVICE = -6       /* HIP reported an error (no device, launch failure)          */
+    VATP_E_DEVICE = -6       /* HIP reported an error (no device, launch failure), or the  */
+                             /* context's device is not the current one                    */
 } vatp_status;
 
 enum { VATP_F32 = 0, VATP_BF16 = 1 };
@@ -99,7 +100,8 @@ typedef struct {
  */
 
 /* Creates a context for HIP device `device` (host memory only).  The device must be the
- * current HIP device whenever a call that takes the context is made. */
+ * current HIP device whenever a call that takes the context is made: a call made while
+ * another device is current returns VATP_E_DEVICE and enqueues nothing. */
 vatp_status vatp_create(vatp_ctx **ctx, int device);
 void        vatp_destroy(vatp_ctx *ctx);
 const char *vatp_strerror(vatp_status st);

@@ -226,17 +226,10 @@ void vatp_oracle_vnorm(const double *V, int64_t n, int64_t d, int kind, double *
 
 /*
  * Value-aware importance, Eq. 4:  I_r = S_r * ||v_r||_1.
- * decide_f32 != 0 rounds each product to binary32 first: that is the precision in
- * which the GPU library compares importances, so that a test which feeds both sides
- * the same binary32 S and norm values takes the keep/evict decision identically.
  */
-void vatp_oracle_importance(const double *S, const double *nrm, int64_t n, int decide_f32,
-                            double *I)
+void vatp_oracle_importance(const double *S, const double *nrm, int64_t n, double *I)
 {
-    for (int64_t r = 0; r < n; ++r) {
-        double v = S[r] * nrm[r];
-        I[r] = decide_f32 ? (double)(float)v : v;
-    }
+    for (int64_t r = 0; r < n; ++r) I[r] = S[r] * nrm[r];
 }
 
 /*
@@ -322,7 +315,7 @@ void vatp_oracle_decode_prune_units(const double *q, const double *K, const doub
         double *scratch = (double *)malloc((size_t)(nu > 0 ? nu : 1) * sizeof(double));
         double *I = (double *)malloc((size_t)(nu > 0 ? nu : 1) * sizeof(double));
         vatp_oracle_decode_scores(q + u * d, K + u * cap * d, nu, d, c, S + u * cap, NULL, scratch);
-        vatp_oracle_importance(S + u * cap, nrm + u * cap, nu, 0, I);
+        vatp_oracle_importance(S + u * cap, nrm + u * cap, nu, I);
         int64_t nk = vatp_oracle_select(I, nu, B[u], F, R, kept + u * cap);
         n_out[u] = nk;
         if (nk >= 0) {

@@ -63,7 +63,7 @@ def lib():
         L.vatp_oracle_l1norm.restype = None
         L.vatp_oracle_vnorm.argtypes = [_f64p, _i64, _i64, ctypes.c_int, _f64p]
         L.vatp_oracle_vnorm.restype = None
-        L.vatp_oracle_importance.argtypes = [_f64p, _f64p, _i64, ctypes.c_int, _f64p]
+        L.vatp_oracle_importance.argtypes = [_f64p, _f64p, _i64, _f64p]
         L.vatp_oracle_importance.restype = None
         L.vatp_oracle_select.argtypes = [_f64p, _i64, _i64, _i64, _i64, _i32p]
         L.vatp_oracle_select.restype = _i64
@@ -257,11 +257,11 @@ def vnorm(V, kind: int = 0) -> np.ndarray:
     return out
 
 
-def importance(S, nrm, decide_f32: bool = False) -> np.ndarray:
-    """Eq. 4. decide_f32 rounds each product to binary32 (the GPU's comparison precision)."""
+def importance(S, nrm) -> np.ndarray:
+    """Eq. 4: the score times the norm of the value row."""
     S, nrm = _f64(S), _f64(nrm)
     out = np.zeros_like(S)
-    lib().vatp_oracle_importance(_p(S), _p(nrm), S.shape[0], int(decide_f32), _p(out))
+    lib().vatp_oracle_importance(_p(S), _p(nrm), S.shape[0], _p(out))
     return out
 
 
@@ -344,8 +344,8 @@ class OracleHead:
         self.nrm = l1norm(self.V) if self.norm_kind == 0 else vnorm(self.V, self.norm_kind)
         self.pos = np.arange(self.K.shape[0], dtype=np.int64)
 
-    def importance(self, decide_f32: bool = False) -> np.ndarray:
-        return importance(self.S, self.nrm, decide_f32)
+    def importance(self) -> np.ndarray:
+        return importance(self.S, self.nrm)
 
     def prune(self, B: int, F: int, R: int, forced: Optional[Sequence[int]] = None) -> np.ndarray:
         kept = select(self.importance(), B, F, R) if forced is None \

@@ -48,13 +48,16 @@ _vp = ctypes.c_void_p
 
 
 def load() -> ctypes.CDLL:
-    """Loads the built library; builds it first only when no built library exists."""
+    """Loads the built library.  It is built first when there is none, or when the one that is there was built
+    from other sources than the present ones (a digest of sources, headers and flags is kept beside it)."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(LIB_PATH):
-        from . import build as _build
+    from . import build as _build
+    if LIB_PATH == _build.LIB and not _build.is_current():
         _build.build_library()
+    elif not os.path.exists(LIB_PATH):
+        raise FileNotFoundError("vatp: no library at %s" % LIB_PATH)
     L = ctypes.CDLL(LIB_PATH)
     pp = ctypes.POINTER(_Params)
     L.vatp_create.argtypes = [ctypes.POINTER(_vp), ctypes.c_int]

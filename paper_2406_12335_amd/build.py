@@ -41,6 +41,32 @@ EXTRA_FLAGS = {
 }
 
 
+STAMP = LIB + ".stamp"
+
+
+def source_digest() -> str:
+    """SHA-256 over everything the library is built from: the HIP sources, the internal and public headers and
+    the compiler flags.  build_library() leaves it beside the library; binding.load() compares."""
+    import hashlib
+    h = hashlib.sha256()
+    files = sources() + sorted(glob.glob(os.path.join(CSRC, "*.h"))) + [os.path.join(ROOT, "include", "vatp.h")]
+    for path in files:
+        h.update(os.path.basename(path).encode() + b"\0")
+        with open(path, "rb") as f:
+            h.update(f.read())
+    h.update(repr((HIPCC_FLAGS[:-4], sorted(EXTRA_FLAGS.items()))).encode())
+    return h.hexdigest()
+
+
+def is_current() -> bool:
+    """True when a built library exists and was built from the sources as they are now."""
+    try:
+        with open(STAMP) as f:
+            return os.path.exists(LIB) and f.read().strip() == source_digest()
+    except OSError:
+        return False
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
     extra = EXTRA_FLAGS.get(os.path.basename(src), [])
@@ -56,6 +82,8 @@ def build_library(verbose: bool = False) -> str:
     tmp = LIB + ".tmp%d" % os.getpid()
     subprocess.check_call([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])
     os.replace(tmp, LIB)
+    with open(STAMP, "w") as f:
+        f.write(source_digest() + "\n")
     if verbose:
         print("built", LIB)
     return LIB

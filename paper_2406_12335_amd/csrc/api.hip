@@ -92,6 +92,17 @@ void prepare(const vatp_params *p, int which_call, const int32_t *new_pos, Prepa
     }
 }
 
+// the context's device must be the current one: kernels are launched on the current device
+inline bool wrong_device(const vatp_ctx *ctx)
+{
+    int cur = -1;
+    if (hipGetDevice(&cur) != hipSuccess) {
+        (void)hipGetLastError();
+        return true;
+    }
+    return cur != ctx->device;
+}
+
 inline bool misaligned(const void *ptr, size_t a) { return (reinterpret_cast<uintptr_t>(ptr) & (a - 1)) != 0; }
 
 }  // namespace
@@ -177,6 +188,7 @@ vatp_status prefill_score_impl(vatp_ctx *ctx, const vatp_params *p, const void *
     if (window < -1 || window > kMaxWindow) return VATP_E_SHAPE;
     const vatp_status st = check_params(p, window < 0 ? VATP_CALL_PREFILL_SCORE : VATP_CALL_PREFILL_SCORE_WINDOW);
     if (st != VATP_OK) return st;
+    if (wrong_device(ctx)) return VATP_E_DEVICE;
     if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(hist, 4)) return VATP_E_SHAPE;
     const size_t need = vatp_workspace_bytes(ctx, p, window < 0 ? VATP_CALL_PREFILL_SCORE : VATP_CALL_PREFILL_SCORE_WINDOW);
     if (!ws || ws_bytes < need || misaligned(ws, kAlign)) return VATP_E_WORKSPACE;
@@ -244,6 +256,7 @@ vatp_status decode_step_impl(vatp_ctx *ctx, const vatp_params *p, int which_call
     if (pos && !new_pos) return VATP_E_NULL;
     const vatp_status st = check_params(p, which_call);
     if (st != VATP_OK) return st;
+    if (wrong_device(ctx)) return VATP_E_DEVICE;
     if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(K, 16) || misaligned(V, 16))
         return VATP_E_SHAPE;
     const size_t need = vatp_workspace_bytes(ctx, p, which_call);
@@ -300,6 +313,7 @@ vatp_status decode_prune_impl(vatp_ctx *ctx, const vatp_params *p, const void *q
     if ((pos == nullptr) != (pos_out == nullptr) || (pos && !new_pos)) return VATP_E_NULL;
     const vatp_status st = check_params(p, VATP_CALL_DECODE_PRUNE_STEP);
     if (st != VATP_OK) return st;
+    if (wrong_device(ctx)) return VATP_E_DEVICE;
     if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(K, 16) || misaligned(V, 16) ||
         misaligned(K_out, 16) || misaligned(V_out, 16))
         return VATP_E_SHAPE;
@@ -425,6 +439,7 @@ vatp_status vatp_select_compact(vatp_ctx *ctx, const vatp_params *p, const void 
     if ((pos == nullptr) != (pos_out == nullptr)) return VATP_E_NULL;
     const vatp_status st = check_params(p, VATP_CALL_SELECT_COMPACT);
     if (st != VATP_OK) return st;
+    if (wrong_device(ctx)) return VATP_E_DEVICE;
     if (misaligned(K, 16) || misaligned(V, 16) || misaligned(K_out, 16) || misaligned(V_out, 16)) return VATP_E_SHAPE;
     if (K_out == K || V_out == V || S_out == S || nrm_out == nrm || (pos && pos_out == pos)) return VATP_E_SHAPE;
     Prepared pr;

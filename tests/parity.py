@@ -87,9 +87,14 @@ def _vec(t: torch.Tensor) -> np.ndarray:
 
 def run_trajectory(inp, device, units: Optional[Sequence[Tuple[int, int]]] = None, steps: Optional[int] = None,
                    n_sink: Optional[int] = None, check_every: int = 1, cap_cache: Optional[int] = None,
-                   full_prefill_check: bool = True, norm_kind: int = 0, fused: bool = False,
-                   window: Optional[int] = None) -> TrajectoryReport:
+                   prefill_oracle: Optional[Dict[Tuple[int, int], np.ndarray]] = None, norm_kind: int = 0,
+                   fused: bool = False, window: Optional[int] = None) -> TrajectoryReport:
     """Prompt pass -> prune -> decode/prune steps on the GPU, mirrored by OracleHead on the chosen units.
+
+    The oracle's state never takes a value from the GPU: its prompt scores are computed here, by the oracle, for
+    every chosen unit -- or handed in through prefill_oracle ({unit: the oracle's S for that unit}) by a test
+    that has already computed them, so that an expensive prompt pass is not run twice.  Either way the GPU's
+    prompt scores are compared with them element by element, and the prompt prune is judged on the oracle's.
 
     fused: every decode step and its prune go through vatp_decode_prune_step instead of
     vatp_decode_step + vatp_select_compact; the state after each step is compared with the oracle's.
@@ -126,13 +131,17 @@ def run_trajectory(inp, device, units: Optional[Sequence[Tuple[int, int]]] = Non
         Lmax = max(inp.lens)
         Kh = np.stack([_unit_rows(inp.K, bb, hh, Lmax) for bb, hh in units])
         S_or = None
+        have = prefill_oracle is not None and window is None
+        if have:
+            assert all(u in prefill_oracle for u in units), "prefill_oracle must cover every chosen unit"
         if grp == 1:
-            Qh = np.stack([_unit_rows(inp.Q, bb, hh, Lmax) for bb, hh in units])
-            if full_prefill_check and window is None:
+            if window is not None or not have:
+                Qh = np.stack([_unit_rows(inp.Q, bb, hh, Lmax) for bb, hh in units])
+            if window is None and not have:
                 S_or = orc.prefill_scores_units(Qh, Kh, [inp.lens[bb] for bb, _ in units])
         else:
             Qg = np.stack([np.stack([_unit_rows(inp.Q, bb, hh * grp + r, Lmax) for r in range(grp)]) for bb, hh in units])
-            if full_prefill_check and window is None:
+            if window is None and not have:
                 S_or = orc.prefill_scores_group_units(Qg, Kh, [inp.lens[bb] for bb, _ in units])
         for ui, (bb, hh) in enumerate(units):
             L = inp.lens[bb]
@@ -148,12 +157,10 @@ def run_trajectory(inp, device, units: Optional[Sequence[Tuple[int, int]]] = Non
                 s_max[(bb, hh)] = float(o.S.max()) if L else 0.0
                 e = assert_scores_close(S_gpu, o.S, rtol, "windowed prefill S unit (%d,%d)" % (bb, hh))
                 rep.max_rel_err_prefill = max(rep.max_rel_err_prefill, e)
-            elif full_prefill_check:
-                o.S = S_or[ui, :L].copy()
+            else:
+                o.S = np.array(prefill_oracle[(bb, hh)][:L], dtype=np.float64) if have else S_or[ui, :L].copy()
                 e = assert_scores_close(S_gpu, o.S, rtol, "prefill S unit (%d,%d)" % (bb, hh))
                 rep.max_rel_err_prefill = max(rep.max_rel_err_prefill, e)
-            else:
-                o.S = S_gpu.copy()        # trajectory continues from the GPU's prompt scores
             assert_scores_close(_unit_rows(cache.nrm_prompt, bb, hh, L), o.nrm, rtol, "nrm unit (%d,%d)" % (bb, hh))
             heads[(bb, hh)] = o
 

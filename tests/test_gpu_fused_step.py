@@ -226,10 +226,9 @@ def test_fused_route_full_size(gpu_device, name, units, steps, window):
         order = np.argsort(inp.lens)
         units = [(int(order[0]), 3), (int(order[-1]), 30), (int(order[8]), 12)]
     _say("fused route full size %s units=%s steps=%d window=%s" % (name, units, steps, window))
-    # with a window the oracle's prompt pass is only the band of w+1 rows, so it is checked in full;
-    # without one the trajectory continues from the GPU's prompt scores (checked by the other full-size tests)
+    # (the oracle runs the prompt pass of the chosen units itself: the whole triangle, or the window's band)
     rep = parity.run_trajectory(inp, gpu_device, units=units, steps=steps, fused=True, window=window,
-                                full_prefill_check=False, check_every=4)
+                                check_every=4)
     _say("report %r" % rep)
     assert rep.prune_events == len(units) * (steps + 1)
 
@@ -241,7 +240,7 @@ def test_long32k_full_size_history_window(gpu_device):
     w = 400
     _say("long32k, history window %d" % w)
     rep = parity.run_trajectory(inp, gpu_device, units=[(0, 1), (0, 26)], steps=12, fused=True, window=w,
-                                full_prefill_check=False, check_every=3)
+                                check_every=3)
     _say("report %r" % rep)
 
 

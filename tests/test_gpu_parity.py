@@ -96,16 +96,19 @@ def test_llama7b_layer_full_size(gpu_device):
     for h in range(cfg.n_heads):
         parity.assert_scores_close(S[0, h].cpu().numpy(), S_or[h], 1e-3, "prompt S head %d" % h)
     units = [(0, h) for h in (0, 5, 11, 13, 17, 22, 29, 31)]
-    rep = parity.run_trajectory(inp, gpu_device, units=units, full_prefill_check=False)
+    rep = parity.run_trajectory(inp, gpu_device, units=units, prefill_oracle={(0, h): S_or[h] for _, h in units})
     _say("report %r" % rep)
 
 
-def test_llama7b_stack_one_layer_full_size(gpu_device):
+@pytest.mark.parametrize("layer,units,steps", [
+    (3, [(0, 0), (3, 17), (7, 31), (5, 8)], 256),
+    (29, [(2, 9), (6, 24)], 96),                     # a second layer of the stack (its own seeded tensors)
+])
+def test_llama7b_stack_one_layer_full_size(gpu_device, layer, units, steps):
     cfg = vs.CONFIGS["llama7b_stack"]
-    _say("llama7b_stack layer 3, batch 8 x 32 heads, sampled units, 256 steps")
-    inp = vs.make_inputs(cfg, seed=0, layer=3, device=gpu_device)
-    units = [(0, 0), (3, 17), (7, 31), (5, 8)]
-    rep = parity.run_trajectory(inp, gpu_device, units=units)
+    _say("llama7b_stack layer %d, batch 8 x 32 heads, units %s, %d steps" % (layer, units, steps))
+    inp = vs.make_inputs(cfg, seed=0, layer=layer, device=gpu_device)
+    rep = parity.run_trajectory(inp, gpu_device, units=units, steps=steps)
     _say("report %r" % rep)
 
 
@@ -120,8 +123,12 @@ def test_ragged16_full_size(gpu_device):
 
 
 def test_long32k_full_size(gpu_device):
+    """Prompt of 32768 rows.  Four heads get the oracle's whole prompt pass (Eq. 1-2 over all 32768 query rows,
+    about half a minute of host time with one thread per head) and every one of their scores is compared; two of
+    them then go through the prompt prune (judged on the oracle's scores) and the 64 decode steps.  All 32 heads:
+    the invariants, and the last 384 keys against the oracle."""
     cfg = vs.CONFIGS["long32k"]
-    _say("long32k full size: invariants on all heads, tail of S on 3 heads, decode on 2 heads")
+    _say("long32k full size: every score of 4 heads, invariants on all heads, tail of S on 3 more, decode on 2 heads")
     inp = vs.make_inputs(cfg, seed=0, device=gpu_device)
     S = _prompt_scores_gpu(inp, gpu_device)
     L = cfg.prompt_len
@@ -132,7 +139,17 @@ def test_long32k_full_size(gpu_device):
     for h in (0, 14, 31):
         want = orc.prefill_scores_tail(inp.Q[0, h].double().cpu().numpy(), inp.K[0, h].double().cpu().numpy(), j0)
         parity.assert_scores_close(S[0, h, j0:].cpu().numpy(), want, 1e-3, "tail S head %d" % h)
-    rep = parity.run_trajectory(inp, gpu_device, units=[(0, 2), (0, 27)], full_prefill_check=False)
+    full = [2, 27, 9, 20]
+    _say("long32k: oracle prompt pass of heads %s" % full)
+    Qh = np.stack([inp.Q[0, h].double().cpu().numpy() for h in full])
+    Kh = np.stack([inp.K[0, h].double().cpu().numpy() for h in full])
+    S_or = orc.prefill_scores_units(Qh, Kh, [L] * len(full))
+    worst = 0.0
+    for i, h in enumerate(full):
+        worst = max(worst, parity.assert_scores_close(S[0, h].cpu().numpy(), S_or[i], 1e-3, "prompt S head %d" % h))
+    _say("long32k: %d scores compared, worst relative error %.3g" % (len(full) * L, worst))
+    rep = parity.run_trajectory(inp, gpu_device, units=[(0, 2), (0, 27)],
+                                prefill_oracle={(0, 2): S_or[0], (0, 27): S_or[1]})
     _say("report %r" % rep)
 
 
@@ -215,7 +232,10 @@ def test_select_compact_bit_exact_with_planted_ties(gpu_device, n, B, F, R, seed
         vatp.vatp_destroy(ctx)
     nk = min(n, B)
     for h in range(H):
-        I = orc.importance(S[0, h].double().numpy(), nrm[0, h].double().numpy(), decide_f32=True)
+        # Both sides are given the same binary32 S and nrm, and both decide in the kernel's precision: the
+        # importance handed to the oracle's selection is the binary32 product (rounded here, in the test's
+        # input preparation, not in the oracle).
+        I = (S[0, h].numpy().astype(np.float32) * nrm[0, h].numpy().astype(np.float32)).astype(np.float64)
         want = orc.select(I, B, F, R)
         got = out["kept"][0, h, :nk].cpu().numpy()
         np.testing.assert_array_equal(got, want)

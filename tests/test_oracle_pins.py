@@ -42,8 +42,6 @@ def test_l1norm_and_importance_match_bruteforce():
     nrm = orc.l1norm(V)
     np.testing.assert_allclose(nrm, bf.l1(V.tolist()), rtol=1e-15)
     np.testing.assert_array_equal(orc.importance(S, nrm), S * nrm)
-    i32 = orc.importance(S, nrm, decide_f32=True)
-    np.testing.assert_array_equal(i32, (S * nrm).astype(np.float32).astype(np.float64))
 
 
 @pytest.mark.parametrize("n,B,F,R,seed", [(32, 16, 2, 4, 0), (32, 31, 0, 0, 1), (17, 9, 3, 6, 2),

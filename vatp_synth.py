@@ -151,3 +151,14 @@ def make_inputs(cfg: VatpConfig, seed: int = 0, layer: int = 0,
 
     return VatpInputs(cfg, lens, cfg.budgets(lens), cap,
                       Q.to(dt), K.to(dt), V.to(dt), qd.to(dt), kd.to(dt), vd.to(dt))
+
+
+def buffer_digests(inp: VatpInputs) -> Dict[str, str]:
+    """SHA-256 of every generated buffer (the bytes of the storage dtype, as the oracle and the HIP path receive
+    them), so that a run can state exactly which inputs it was measured or checked on."""
+    import hashlib
+    out = {}
+    for name in ("Q", "K", "V", "qd", "kd", "vd"):
+        t = getattr(inp, name).detach().contiguous().cpu()
+        out[name] = hashlib.sha256(t.view(torch.uint8).numpy().tobytes()).hexdigest()
+    return out
