@@ -41,6 +41,7 @@ extern "C" {
 #define VATP_MAX_UNITS 16384       /* batch * n_heads * max(q_per_kv, 1) per call         */
 #define VATP_MAX_GROUP 16          /* query heads per K/V head (grouped-query attention)  */
 #define VATP_MAX_CAP   4194304     /* rows per (batch, head) unit: cap and cap_out        */
+#define VATP_STATIC_SCRATCH_BYTES 16777216   /* scratch of vatp_decode_prune_step_static, per GPU */
 
 typedef struct vatp_ctx vatp_ctx;  /* opaque */
 
@@ -99,7 +100,9 @@ typedef struct {
  * (Eq. 3) the window runs over the group-averaged weights, and hist holds their means.
  */
 
-/* Creates a context for HIP device `device` (host memory only).  The device must be the
+/* Creates a context for HIP device `device` (host memory only; it also looks up the address of the
+ * library's static scratch array on that device, making the device current for the lookup and
+ * restoring the caller's device afterwards).  The device must be the
  * current HIP device whenever a call that takes the context is made: a call made while
  * another device is current returns VATP_E_DEVICE and enqueues nothing. */
 vatp_status vatp_create(vatp_ctx **ctx, int device);
@@ -222,6 +225,27 @@ vatp_status vatp_decode_prune_step(vatp_ctx *ctx, const vatp_params *p,
                                    int32_t *pos_out, int32_t *kept_idx,
                                    const int32_t *synced_in, int32_t *synced_out, float *out,
                                    void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * vatp_decode_prune_step for callers that cannot allocate device memory and have no workspace to
+ * hand over: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same results bit for bit, but no ws / ws_bytes: the step's scratch (logits, per-chunk
+ * softmax statistics, partial attention outputs) lives in a static device array of
+ * VATP_STATIC_SCRATCH_BYTES (16 MiB) that every GPU the library runs on holds until the process ends.
+ * The call allocates and frees nothing.  It returns VATP_E_WORKSPACE, and enqueues nothing, when
+ * vatp_workspace_bytes(ctx, p, VATP_CALL_DECODE_PRUNE_STEP) exceeds VATP_STATIC_SCRATCH_BYTES (16 MiB
+ * cover a layer of 512 heads with 2458-row caches).  All calls on one GPU, from any context,
+ * share that GPU's array: calls that overlap in time on one GPU (different streams) race; calls ordered
+ * by one stream do not.  Nothing in the array has to start at zero: every call writes what it reads.
+ */
+vatp_status vatp_decode_prune_step_static(vatp_ctx *ctx, const vatp_params *p,
+                                          const void *q, const void *k, const void *v,
+                                          void *K, void *V, const float *S, float *nrm, int32_t *pos,
+                                          const int32_t *new_pos,
+                                          void *K_out, void *V_out, float *S_out, float *nrm_out,
+                                          int32_t *pos_out, int32_t *kept_idx,
+                                          const int32_t *synced_in, int32_t *synced_out, float *out,
+                                          void *hip_stream);
 
 /*
  * History-window scores (Eq. 3: S_k^t = sum of a_k^j over the last w+1 steps j only, the score

@@ -21,11 +21,12 @@ NORM_L1, NORM_L2, NORM_LINF, NORM_NONE = 0, 1, 2, 3
 CALL_PREFILL_SCORE, CALL_DECODE_STEP, CALL_SELECT_COMPACT, CALL_DECODE_ATTEND_STEP, CALL_DECODE_PRUNE_STEP = 0, 1, 2, 3, 4
 CALL_PREFILL_SCORE_WINDOW = 5
 VATP_MAX_BATCH, VATP_MAX_UNITS, VATP_MAX_GROUP = 256, 16384, 16
+VATP_STATIC_SCRATCH_BYTES = 16777216
 OK, E_NULL, E_SHAPE, E_DTYPE, E_BUDGET, E_WORKSPACE, E_DEVICE = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = ("vatp_create", "vatp_destroy", "vatp_strerror", "vatp_validate", "vatp_workspace_bytes",
            "vatp_prefill_score", "vatp_prefill_score_lse", "vatp_decode_step", "vatp_decode_attend_step", "vatp_select_compact",
-           "vatp_decode_prune_step", "vatp_prefill_score_window", "vatp_select_compact_window",
+           "vatp_decode_prune_step", "vatp_decode_prune_step_static", "vatp_prefill_score_window", "vatp_select_compact_window",
            "vatp_decode_prune_step_window")
 
 
@@ -82,6 +83,8 @@ def load() -> ctypes.CDLL:
     L.vatp_decode_prune_step.argtypes = [_vp, pp] + [_vp] * 8 + [ctypes.POINTER(ctypes.c_int32)] + [_vp] * 9 + \
         [_vp, ctypes.c_size_t, _vp]
     L.vatp_decode_prune_step.restype = ctypes.c_int
+    L.vatp_decode_prune_step_static.argtypes = [_vp, pp] + [_vp] * 8 + [ctypes.POINTER(ctypes.c_int32)] + [_vp] * 9 + [_vp]
+    L.vatp_decode_prune_step_static.restype = ctypes.c_int
     i32, i32p = ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)
     L.vatp_prefill_score_window.argtypes = [_vp, pp, _vp, _vp, _vp, i32, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
     L.vatp_prefill_score_window.restype = ctypes.c_int
@@ -204,6 +207,17 @@ def vatp_decode_prune_step(ctx, p: Params, q, k, v, K, V, S, nrm, pos, new_pos: 
                                          _ptr(pos_out), _ptr(kept_idx), _ptr(synced_in), _ptr(synced_out), _ptr(out),
                                          _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0,
                                          _stream(stream)), "vatp_decode_prune_step")
+
+
+def vatp_decode_prune_step_static(ctx, p: Params, q, k, v, K, V, S, nrm, pos, new_pos: Optional[Sequence[int]], K_out,
+                                  V_out, S_out, nrm_out, pos_out, kept_idx, synced_in, synced_out, out,
+                                  stream=None) -> None:
+    npos = (ctypes.c_int32 * len(new_pos))(*[int(x) for x in new_pos]) if new_pos is not None else None
+    _check(load().vatp_decode_prune_step_static(ctx, p.ref(), _ptr(q), _ptr(k), _ptr(v), _ptr(K), _ptr(V), _ptr(S),
+                                                _ptr(nrm), _ptr(pos), npos, _ptr(K_out), _ptr(V_out), _ptr(S_out),
+                                                _ptr(nrm_out), _ptr(pos_out), _ptr(kept_idx), _ptr(synced_in),
+                                                _ptr(synced_out), _ptr(out), _stream(stream)),
+           "vatp_decode_prune_step_static")
 
 
 def _nbytes(ws) -> int:

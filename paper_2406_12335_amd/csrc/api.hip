@@ -10,7 +10,14 @@ using namespace vatp;
 
 struct vatp_ctx {
     int device;
+    void *scratch;       // this device's copy of the static scratch array (address looked up at creation)
 };
+
+// Scratch memory of vatp_decode_prune_step_static, the entry point for callers that cannot allocate: a
+// file-scope device array, so every GPU the library runs on holds VATP_STATIC_SCRATCH_BYTES of it until the
+// process ends.  In host code the name is only a handle: the address on a device comes from
+// hipGetSymbolAddress (vatp_create, with that device current), and only that address is ever used.
+static __device__ __align__(256) unsigned char scratch[VATP_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -133,9 +140,27 @@ vatp_status vatp_create(vatp_ctx **ctx, int device)
         (void)hipGetLastError();
         return VATP_E_DEVICE;
     }
+    // the static scratch array's address on this device, looked up with the device current
+    int prev = -1;
+    if (hipGetDevice(&prev) != hipSuccess) {
+        (void)hipGetLastError();
+        return VATP_E_DEVICE;
+    }
+    if (prev != device && hipSetDevice(device) != hipSuccess) {
+        (void)hipGetLastError();
+        return VATP_E_DEVICE;
+    }
+    void *ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (prev != device) (void)hipSetDevice(prev);
+    if (e != hipSuccess || !ptr) {
+        (void)hipGetLastError();
+        return VATP_E_DEVICE;
+    }
     vatp_ctx *c = new (std::nothrow) vatp_ctx;
     if (!c) return VATP_E_DEVICE;
     c->device = device;
+    c->scratch = ptr;
     *ctx = c;
     return VATP_OK;
 }
@@ -375,6 +400,25 @@ vatp_status vatp_decode_prune_step(vatp_ctx *ctx, const vatp_params *p, const vo
     WindowArgs win = {};
     return decode_prune_impl(ctx, p, q, k, v, K, V, S, nrm, pos, new_pos, K_out, V_out, S_out, nrm_out, pos_out,
                              kept_idx, synced_in, synced_out, win, out, ws, ws_bytes, hip_stream);
+}
+
+vatp_status vatp_decode_prune_step_static(vatp_ctx *ctx, const vatp_params *p, const void *q, const void *k,
+                                          const void *v, void *K, void *V, const float *S, float *nrm, int32_t *pos,
+                                          const int32_t *new_pos, void *K_out, void *V_out, float *S_out,
+                                          float *nrm_out, int32_t *pos_out, int32_t *kept_idx,
+                                          const int32_t *synced_in, int32_t *synced_out, float *out,
+                                          void *hip_stream)
+{
+    if (!ctx) return VATP_E_NULL;
+    const vatp_status st = check_params(p, VATP_CALL_DECODE_PRUNE_STEP);
+    if (st != VATP_OK) return st;
+    // the step's workspace is the device's static array: nothing is allocated, sizes beyond it are refused
+    const size_t need = vatp_workspace_bytes(ctx, p, VATP_CALL_DECODE_PRUNE_STEP);
+    if (need > static_cast<size_t>(VATP_STATIC_SCRATCH_BYTES)) return VATP_E_WORKSPACE;
+    WindowArgs win = {};
+    return decode_prune_impl(ctx, p, q, k, v, K, V, S, nrm, pos, new_pos, K_out, V_out, S_out, nrm_out, pos_out,
+                             kept_idx, synced_in, synced_out, win, out, ctx->scratch, VATP_STATIC_SCRATCH_BYTES,
+                             hip_stream);
 }
 
 vatp_status vatp_decode_prune_step_window(vatp_ctx *ctx, const vatp_params *p, const void *q, const void *k,
