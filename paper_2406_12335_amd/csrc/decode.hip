@@ -34,7 +34,6 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(
     constexpr int kGroup = kPasses < 16 ? kPasses : 16;        // loads issued back to back
 
     __shared__ float s_logit[kDecodeChunk];
-    __shared__ float s_red[8];
 
     // unit in the fast grid dimension: workgroups go to the 8 XCDs round-robin by linear id, so (with a
     // unit count that is a multiple of 8) a head's chunks, and the launch that consumes their logits,
@@ -50,6 +49,7 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(
     const int tid = threadIdx.x;
     const int sub = tid % kLanesPerRow;
     const int rloc = tid / kLanesPerRow;
+    const int lane = tid & 63, wave = tid >> 6;
 
     // Every load of this phase is requested before the first result is used: the query, the new row (in the
     // workgroup that owns it), then all of the workgroup's K rows.
@@ -60,7 +60,6 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(
         kraw = knew[sub];
         vraw = reinterpret_cast<const uint4 *>(v_new + unit * D)[sub];
     }
-    float qf[kE];
 
     // logits of the chunk's rows; the new row is read from the step's input, not from the cache
 #pragma unroll
@@ -72,59 +71,39 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(
             const uint4 *src = (r == n0) ? knew + sub : Ku + static_cast<size_t>(r) * kLanesPerRow + sub;
             raw[u] = (r < n) ? *src : make_uint4(0, 0, 0, 0);
         }
-        if (p0 == 0) {
-            Elt<T>::unpack(q_raw, qf);         // this lane's slice of the query, widened once
+        if (p0 == 0 && owns_new_row) {
             // the workgroup that owns the new row stores k, v, |v| and pos into the caches
-            if (owns_new_row) {
-                reinterpret_cast<uint4 *>(K + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = kraw;
-                reinterpret_cast<uint4 *>(V + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = vraw;
-                float vf[kE], a = 0.f;
-                Elt<T>::unpack(vraw, vf);
-#pragma unroll
-                for (int e = 0; e < kE; ++e) a = norm_accum(norm, a, vf[e]);
-#pragma unroll
-                for (int off = kLanesPerRow / 2; off > 0; off >>= 1) a = norm_combine(norm, a, __shfl_xor(a, off));
-                if (sub == 0) {
-                    nrm[unit * cap + n0] = norm_finish(norm, a);
-                    if (pos) pos[unit * cap + n0] = meta.aux[b];
-                }
+            reinterpret_cast<uint4 *>(K + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = kraw;
+            reinterpret_cast<uint4 *>(V + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = vraw;
+            const float new_norm = row_norm<T, kLanesPerRow>(norm, vraw);
+            if (sub == 0) {
+                nrm[unit * cap + n0] = new_norm;
+                if (pos) pos[unit * cap + n0] = meta.aux[b];
             }
         }
 #pragma unroll
         for (int u = 0; u < kGroup; ++u) {
             const int rl = (p0 + u) * kRowsPerPass + rloc;
-            float kf[kE], dot = 0.f;
-            Elt<T>::unpack(raw[u], kf);
-#pragma unroll
-            for (int e = 0; e < kE; ++e) dot = fmaf(qf[e], kf[e], dot);
-#pragma unroll
-            for (int off = kLanesPerRow / 2; off > 0; off >>= 1) dot += __shfl_xor(dot, off);
+            const float dot = group_all_reduce<kLanesPerRow>(dot_16_bytes<T>(raw[u], q_raw), OpSum{});
             if (sub == 0) s_logit[rl] = (row0 + rl < n) ? dot * scale_log2 : -INFINITY;
         }
     }
     __syncthreads();
 
-    // chunk statistics: maximum and sum of 2^(t - max) over the chunk's rows
-    const int lane = tid & 63, wave = tid >> 6;
-    const float t = tid < kDecodeChunk ? s_logit[tid] : -INFINITY;
-    float mx = t;
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
-    if (lane == 0) s_red[wave] = mx;
-    __syncthreads();
-    mx = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
-    float e = exp2f(t - mx);                         // 2^(-inf) = 0 for rows past the end
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) e += __shfl_xor(e, off);
-    if (lane == 0) s_red[4 + wave] = e;
-    if (tid < kDecodeChunk && row0 + tid < n) ws_logit[unit * cap + row0 + tid] = t;
-    __syncthreads();
-    if (tid == 0)
-        ws_part[unit * chunks_alloc + chunk] = make_float2(mx, s_red[4] + s_red[5] + s_red[6] + s_red[7]);
+    // the chunk's logits go to the workspace; its statistics (maximum, sum of 2^(t - max)) are formed by one
+    // wavefront, two rows per lane, without any exchange between wavefronts
+    if (tid < kDecodeChunk && row0 + tid < n) ws_logit[unit * cap + row0 + tid] = s_logit[tid];
+    float2 st = make_float2(0.f, 0.f);
+    if (wave == 0 || kAttend) {
+        st = chunk_stats_64x2(s_logit[lane], s_logit[lane + 64]);
+        if (tid == 0) ws_part[unit * chunks_alloc + chunk] = st;
+    }
 
     if constexpr (kAttend) {
         // this chunk's share of the attention output (paper Eq. 1), unnormalised and relative to the
         // chunk maximum:  o_c = sum_r 2^(t_r - max_c) v_r ; the finish launch rescales and adds the chunks
+        // (every wavefront has formed the chunk maximum for itself above)
+        const float mx = st.x;
         __shared__ float s_o[kRowsPerPass][D];
         const uint4 *Vu = reinterpret_cast<const uint4 *>(V + unit * cap * D);
         const uint4 *vnew = reinterpret_cast<const uint4 *>(v_new + unit * D);
@@ -238,14 +217,9 @@ __global__ __launch_bounds__(256) void decode_logits_group_kernel(
             if (owns_new_row) {                     // append k, v, |v| and pos
                 reinterpret_cast<uint4 *>(K + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = kraw;
                 reinterpret_cast<uint4 *>(V + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = vraw;
-                float vf[kE], a = 0.f;
-                Elt<T>::unpack(vraw, vf);
-#pragma unroll
-                for (int e = 0; e < kE; ++e) a = norm_accum(norm, a, vf[e]);
-#pragma unroll
-                for (int off = kLanesPerRow / 2; off > 0; off >>= 1) a = norm_combine(norm, a, __shfl_xor(a, off));
+                const float new_norm = row_norm<T, kLanesPerRow>(norm, vraw);
                 if (sub == 0) {
-                    nrm[unit * cap + n0] = norm_finish(norm, a);
+                    nrm[unit * cap + n0] = new_norm;
                     if (pos) pos[unit * cap + n0] = meta.aux[b];
                 }
             }
@@ -317,16 +291,10 @@ __global__ __launch_bounds__(256) void decode_logits_group_kernel(
 
     // chunk statistics, one wavefront per query head (two rows per lane): no exchange between wavefronts
     for (int i = wave; i < group; i += 4) {
-        const float t0 = s_logit[i][lane], t1 = s_logit[i][lane + 64];
-        float mx = fmaxf(t0, t1);
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
-        float e = exp2f(t0 - mx) + exp2f(t1 - mx);           // 2^(-inf) = 0 for rows past the end
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) e += __shfl_xor(e, off);
+        const float2 st = chunk_stats_64x2(s_logit[i][lane], s_logit[i][lane + 64]);
         if (lane == 0) {
-            ws_part[(unit * group + i) * chunks_alloc + chunk] = make_float2(mx, e);
-            s_max[i] = mx;
+            ws_part[(unit * group + i) * chunks_alloc + chunk] = st;
+            s_max[i] = st.x;
         }
     }
     for (int idx = tid; idx < group * kDecodeChunk; idx += 256) {

@@ -130,11 +130,7 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
                 if (r < hi) consider(r, combine(s4[u], group_weight<kMaxG>(t4[u], lse2, group), x4[u]), w4[u]);
             }
         }
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-            const unsigned long long o = __shfl_xor(best, off);
-            best = o < best ? o : best;
-        }
+        best = wave_min_u64(best);
         if ((tid & 63) == 0) s_min[tid >> 6] = best;
         __syncthreads();
         best = s_min[0];
@@ -275,8 +271,6 @@ __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
         pre_s[u] = r < n0 ? Su[r] : 0.f;
         pre_w[u] = r < n0 ? Nu[r] : 0.f;
     }
-    float qf[kE];
-
     // logits of all rows into LDS; the new row is read from the step's input, not from the cache
     for (int r0 = 0; r0 < n; r0 += kGroup * kRowsPerPass) {
         uint4 raw[kGroup];
@@ -286,35 +280,21 @@ __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
             const uint4 *src = (r == n0) ? knew + sub : Ku + static_cast<size_t>(r) * kLanesPerRow + sub;
             raw[u] = (r < n) ? *src : make_uint4(0, 0, 0, 0);
         }
-        if (r0 == 0) {
-            Elt<T>::unpack(q_raw, qf);
+        if (r0 == 0 && tid < kLanesPerRow) {
             // append the new row: k, v, |v|, pos
-            if (tid < kLanesPerRow) {
-                reinterpret_cast<uint4 *>(K + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = k_raw;
-                reinterpret_cast<uint4 *>(V + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = v_raw;
-                float vf[kE], a = 0.f;
-                Elt<T>::unpack(v_raw, vf);
-#pragma unroll
-                for (int e = 0; e < kE; ++e) a = norm_accum(norm, a, vf[e]);
-#pragma unroll
-                for (int off = kLanesPerRow / 2; off > 0; off >>= 1) a = norm_combine(norm, a, __shfl_xor(a, off));
-                if (sub == 0) {
-                    const float new_norm = norm_finish(norm, a);
-                    s_new_norm = new_norm;
-                    Nu[n0] = new_norm;
-                    if (pos) pos[unit * cap + n0] = len_pos.aux[b];
-                }
+            reinterpret_cast<uint4 *>(K + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = k_raw;
+            reinterpret_cast<uint4 *>(V + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = v_raw;
+            const float new_norm = row_norm<T, kLanesPerRow>(norm, v_raw);
+            if (sub == 0) {
+                s_new_norm = new_norm;
+                Nu[n0] = new_norm;
+                if (pos) pos[unit * cap + n0] = len_pos.aux[b];
             }
         }
 #pragma unroll
         for (int u = 0; u < kGroup; ++u) {
             const int r = r0 + u * kRowsPerPass + rloc;
-            float kf[kE], dot = 0.f;
-            Elt<T>::unpack(raw[u], kf);
-#pragma unroll
-            for (int e = 0; e < kE; ++e) dot = fmaf(qf[e], kf[e], dot);
-#pragma unroll
-            for (int off = kLanesPerRow / 2; off > 0; off >>= 1) dot += __shfl_xor(dot, off);
+            const float dot = group_all_reduce<kLanesPerRow>(dot_16_bytes<T>(raw[u], q_raw), OpSum{});
             if (sub == 0 && r < n) s_logit[r] = dot * scale_log2;
         }
     }
@@ -348,22 +328,13 @@ __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
     if (tid == 0) { s_score[n0] = 0.f; s_norm[n0] = s_new_norm; }      // the appended row (published by the syncs below)
 
     // Statistics of every 128-row chunk, one wavefront per chunk and no exchange between wavefronts: the lane
-    // takes rows lane and lane + 64 of the chunk.  Each half is summed by its own butterfly and the two sums are
-    // added last, which is the order in which decode_logits_kernel's two wavefronts per chunk combine theirs.
+    // takes rows lane and lane + 64 of the chunk -- the same function, on the same values, as in
+    // decode_logits_kernel.
     const int n_chunks = (n + kDecodeChunk - 1) / kDecodeChunk;
     for (int chunk = wave; chunk < n_chunks; chunk += kWaves) {
         const int r0 = chunk * kDecodeChunk + lane, r1 = r0 + 64;
-        const float t0 = r0 < n ? s_logit[r0] : -INFINITY, t1 = r1 < n ? s_logit[r1] : -INFINITY;
-        float mx = fmaxf(t0, t1);
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
-        float e0 = exp2f(t0 - mx), e1 = exp2f(t1 - mx);
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-            e0 += __shfl_xor(e0, off);
-            e1 += __shfl_xor(e1, off);
-        }
-        if (lane == 0) s_part[chunk] = make_float2(mx, e0 + e1);
+        const float2 st = chunk_stats_64x2(r0 < n ? s_logit[r0] : -INFINITY, r1 < n ? s_logit[r1] : -INFINITY);
+        if (lane == 0) s_part[chunk] = st;
     }
     __syncthreads();
     float M, L;
@@ -383,11 +354,7 @@ __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
                 (static_cast<unsigned long long>(key) << 32) | static_cast<unsigned>(~static_cast<unsigned>(r));
             best = c < best ? c : best;
         }
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-            const unsigned long long o = __shfl_xor(best, off);
-            best = o < best ? o : best;
-        }
+        best = wave_min_u64(best);
         if (lane == 0) s_min[wave] = best;
         __syncthreads();
         best = s_min[0];

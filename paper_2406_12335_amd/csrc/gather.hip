@@ -57,11 +57,7 @@ __global__ __launch_bounds__(256) void gather_kernel(
                                              static_cast<unsigned>(~static_cast<unsigned>(r));
                 best = c < best ? c : best;
             }
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) {
-                const unsigned long long o = __shfl_xor(best, off);
-                best = o < best ? o : best;
-            }
+            best = wave_min_u64(best);
             if ((tid & 63) == 0) s_min[tid >> 6] = best;
             __syncthreads();
             best = s_min[0];

@@ -39,13 +39,8 @@ __global__ __launch_bounds__(256) void l1norm_kernel(const T *__restrict__ V,
 #pragma unroll
         for (int u = 0; u < kGroup; ++u) {
             const int r = row0 + (p0 + u) * kRowsPerPass + rloc;
-            float x[kE], acc = 0.f;
-            Elt<T>::unpack(raw[u], x);
-#pragma unroll
-            for (int e = 0; e < kE; ++e) acc = norm_accum(norm, acc, x[e]);
-#pragma unroll
-            for (int off = kLanesPerRow / 2; off > 0; off >>= 1) acc = norm_combine(norm, acc, __shfl_xor(acc, off));
-            if (sub == 0 && r < len) nu[r] = norm_finish(norm, acc);
+            const float value = row_norm<T, kLanesPerRow>(norm, raw[u]);
+            if (sub == 0 && r < len) nu[r] = value;
         }
     }
 }

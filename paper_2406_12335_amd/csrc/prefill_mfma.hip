@@ -195,8 +195,8 @@ struct Epilogue {
 };
 
 // Norms of 64 consecutive value rows by one wavefront.  Same arithmetic as l1norm_kernel: 16 lanes per
-// row, 8 elements each in order, then a butterfly over the 16 lanes; all 16 loads of a lane are issued
-// before the first is used.
+// row, 8 elements each in order, then an all-reduce over the row's 16 lanes; all 16 loads of a lane are
+// issued before the first is used.
 template <int kNorm>
 __device__ __forceinline__ void value_norms_64(const uint4 *__restrict__ Vu, float *__restrict__ nu, int row0, int len,
                                                int lane)
@@ -211,13 +211,8 @@ __device__ __forceinline__ void value_norms_64(const uint4 *__restrict__ Vu, flo
 #pragma unroll
     for (int p = 0; p < 16; ++p) {
         const int row = row0 + 4 * p + rr;
-        float x[8], acc = 0.f;
-        Elt<bf16_t>::unpack(raw[p], x);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc = norm_accum(kNorm, acc, x[e]);
-#pragma unroll
-        for (int off = 8; off > 0; off >>= 1) acc = norm_combine(kNorm, acc, __shfl_xor(acc, off));
-        if (sub == 0 && row < len) nu[row] = norm_finish(kNorm, acc);
+        const float value = row_norm<bf16_t, 16>(kNorm, raw[p]);
+        if (sub == 0 && row < len) nu[row] = value;
     }
 }
 

@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 #include "vatp.h"
 
@@ -83,6 +84,125 @@ template <> struct Elt<bf16_t> {
     }
 };
 
+// ---- reductions across lanes without LDS traffic -----------------------------------------------------------
+// Data-parallel-primitive (DPP) operand modifiers move a value between the lanes of a 16-lane row as part of
+// a vector-ALU instruction; the shuffles of the HIP headers (ds_bpermute) go through the LDS pipeline instead,
+// which a compute unit's 16 wavefronts share.  Lane patterns used: swap within pairs, swap pairs within
+// quads, mirror within 8 lanes, mirror within 16 lanes.  Each step combines a lane's value with its partner's
+// (both lanes compute the same commutative operation on the same two values), so after step k all lanes of an
+// aligned group of 2^k lanes hold identical bits.
+template <int kCtrl>
+__device__ __forceinline__ float dpp_move(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), kCtrl, 0xf, 0xf, false));
+}
+template <int kCtrl>
+__device__ __forceinline__ unsigned dpp_move(unsigned x) {
+    return static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), kCtrl, 0xf, 0xf, false));
+}
+constexpr int kDppSwapPairs = 0xB1;      // quad_perm [1,0,3,2]
+constexpr int kDppSwapQuadHalves = 0x4E; // quad_perm [2,3,0,1]
+constexpr int kDppMirror8 = 0x141;       // row_half_mirror
+constexpr int kDppMirror16 = 0x140;      // row_mirror
+
+struct OpSum { __device__ __forceinline__ float operator()(float a, float b) const { return a + b; } };
+struct OpMax { __device__ __forceinline__ float operator()(float a, float b) const { return fmaxf(a, b); } };
+
+// All-reduce over aligned groups of kLanes lanes (a power of two up to 64): every lane of a group ends up with
+// the same value.  Groups wider than a 16-lane row finish with one or two LDS-pipeline shuffles.
+template <int kLanes, typename Op>
+__device__ __forceinline__ float group_all_reduce(float x, Op op)
+{
+    static_assert(kLanes >= 1 && kLanes <= 64 && (kLanes & (kLanes - 1)) == 0, "group of 1..64 lanes, a power of two");
+    if constexpr (kLanes >= 2) x = op(x, dpp_move<kDppSwapPairs>(x));
+    if constexpr (kLanes >= 4) x = op(x, dpp_move<kDppSwapQuadHalves>(x));
+    if constexpr (kLanes >= 8) x = op(x, dpp_move<kDppMirror8>(x));
+    if constexpr (kLanes >= 16) x = op(x, dpp_move<kDppMirror16>(x));
+    if constexpr (kLanes >= 32) x = op(x, __shfl_xor(x, 16));
+    if constexpr (kLanes >= 64) x = op(x, __shfl_xor(x, 32));
+    return x;
+}
+
+// All-reduce over the 64 lanes of a wavefront: within the four 16-lane rows by DPP, then the four row results
+// are read into scalar registers and combined as (r0 op r1) op (r2 op r3).  The result is wavefront-uniform.
+template <typename Op>
+__device__ __forceinline__ float wave_all_reduce(float x, Op op)
+{
+    x = group_all_reduce<16>(x, op);
+    const int xi = __builtin_bit_cast(int, x);
+    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 0));
+    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 16));
+    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 32));
+    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 48));
+    return op(op(r0, r1), op(r2, r3));
+}
+__device__ __forceinline__ float wave_sum(float x) { return wave_all_reduce(x, OpSum{}); }
+__device__ __forceinline__ float wave_max(float x) { return wave_all_reduce(x, OpMax{}); }
+
+// Minimum of a 64-bit key over the wavefront (same lane patterns; wavefront-uniform result).
+__device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long x)
+{
+    auto step = [&](auto ctrl) {
+        constexpr int kCtrl = decltype(ctrl)::value;
+        const unsigned lo = dpp_move<kCtrl>(static_cast<unsigned>(x)), hi = dpp_move<kCtrl>(static_cast<unsigned>(x >> 32));
+        const unsigned long long o = (static_cast<unsigned long long>(hi) << 32) | lo;
+        x = o < x ? o : x;
+    };
+    step(std::integral_constant<int, kDppSwapPairs>{});
+    step(std::integral_constant<int, kDppSwapQuadHalves>{});
+    step(std::integral_constant<int, kDppMirror8>{});
+    step(std::integral_constant<int, kDppMirror16>{});
+    unsigned long long best = ~0ull;
+#pragma unroll
+    for (int row = 0; row < 4; ++row) {
+        const unsigned lo = static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>(static_cast<unsigned>(x)), 16 * row));
+        const unsigned hi = static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>(static_cast<unsigned>(x >> 32)), 16 * row));
+        const unsigned long long o = (static_cast<unsigned long long>(hi) << 32) | lo;
+        best = o < best ? o : best;
+    }
+    return best;
+}
+
+// This lane's share of <q, k>: the 16 bytes it holds of both rows.  bf16 pairs go through the two-element dot
+// instruction (fp32 accumulate), fp32 elements through fused multiply-adds.  Every kernel that forms decode
+// logits calls this and then group_all_reduce over the row's lanes, so they all produce the same bits.
+template <typename T> __device__ __forceinline__ float dot_16_bytes(const uint4 &k, const uint4 &q);
+template <> __device__ __forceinline__ float dot_16_bytes<float>(const uint4 &k, const uint4 &q) {
+    float acc = __uint_as_float(k.x) * __uint_as_float(q.x);
+    acc = fmaf(__uint_as_float(k.y), __uint_as_float(q.y), acc);
+    acc = fmaf(__uint_as_float(k.z), __uint_as_float(q.z), acc);
+    return fmaf(__uint_as_float(k.w), __uint_as_float(q.w), acc);
+}
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+template <> __device__ __forceinline__ float dot_16_bytes<bf16_t>(const uint4 &k, const uint4 &q) {
+    float acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, k.x), __builtin_bit_cast(bf16x2, q.x), 0.f, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, k.y), __builtin_bit_cast(bf16x2, q.y), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, k.z), __builtin_bit_cast(bf16x2, q.z), acc, false);
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, k.w), __builtin_bit_cast(bf16x2, q.w), acc, false);
+}
+
+// Norm of a value row whose 16-byte slices are spread over kLanes lanes (every lane of the group gets it).
+template <typename T, int kLanes>
+__device__ __forceinline__ float row_norm(int kind, const uint4 &raw)
+{
+    constexpr int kE = Elt<T>::kPer16B;
+    float x[kE], a = 0.f;
+    Elt<T>::unpack(raw, x);
+#pragma unroll
+    for (int e = 0; e < kE; ++e) a = norm_accum(kind, a, x[e]);
+    a = kind == VATP_NORM_LINF ? group_all_reduce<kLanes>(a, OpMax{}) : group_all_reduce<kLanes>(a, OpSum{});
+    return norm_finish(kind, a);
+}
+
+// Softmax statistics of one chunk of kDecodeChunk = 128 logits, formed by ONE wavefront: the lane brings
+// logits `lane` and `lane + 64` of the chunk (-inf past the end).  Returns (max, sum of 2^(t - max)): the two
+// halves are summed separately and added last.  Every kernel that leaves or uses chunk statistics calls this.
+__device__ __forceinline__ float2 chunk_stats_64x2(float t0, float t1)
+{
+    const float mx = wave_max(fmaxf(t0, t1));
+    const float e0 = wave_sum(exp2f(t0 - mx)), e1 = wave_sum(exp2f(t1 - mx));     // 2^(-inf) = 0 past the end
+    return make_float2(mx, e0 + e1);
+}
+
 // ---- v_mfma_f32_32x32x16_bf16: operand and accumulator conventions shared by the kernels that use it.
 // Lane (n = lane & 31, g = lane >> 5) supplies, as A operand, 8 consecutive contraction elements of row n
 // of the 32 x 16 left matrix and, as B operand, of column n of the right one (which 8 of the 16 is free as
@@ -98,8 +218,8 @@ __device__ __forceinline__ int swizzled_chunk(int row, int c) { return c ^ (row 
 // Softmax denominator of one decode step from the per-chunk statistics (max_c, sum_c of
 // 2^(t - max_c)) that the logits launch left behind: M = max_c max_c and
 // L = sum_c sum_c * 2^(max_c - M).  Every wavefront computes both by itself: lanes take chunks
-// lane, lane + 64, ... (one round trip to memory, not one per chunk) and combine with a
-// butterfly, which gives every lane the same bits.  The kernels that finish a decode step all
+// lane, lane + 64, ... (one round trip to memory, not one per chunk) and combine across the
+// wavefront (wave_max / wave_sum), which gives every lane the same bits.  The kernels that finish a decode step all
 // call this one function, so they agree bit for bit.
 __device__ __forceinline__ void merge_chunk_stats(const float2 *__restrict__ part, int n_chunks, float &M, float &L)
 {
@@ -108,14 +228,11 @@ __device__ __forceinline__ void merge_chunk_stats(const float2 *__restrict__ par
     if (lane < n_chunks) mine = part[lane];
     float m = mine.x;
     for (int c = lane + 64; c < n_chunks; c += 64) m = fmaxf(m, part[c].x);
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    m = wave_max(m);
     float l = mine.y * exp2f(mine.x - m);                 // 0 * 2^(-inf) = 0 for lanes without a chunk
     for (int c = lane + 64; c < n_chunks; c += 64) l += part[c].y * exp2f(part[c].x - m);
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) l += __shfl_xor(l, off);
     M = m;
-    L = l;
+    L = wave_sum(l);
 }
 
 // Component x of the attention output (paper Eq. 1) from the chunks' unnormalised partial sums,
@@ -166,12 +283,10 @@ __device__ __forceinline__ void merge_group_stats(const float2 *__restrict__ par
             const float2 *pi = part + static_cast<size_t>(i) * chunks_alloc;
             float m = mine[i].x;
             for (int c = lane + 64; c < n_chunks; c += 64) m = fmaxf(m, pi[c].x);
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+            m = wave_max(m);
             float l = mine[i].y * exp2f(mine[i].x - m);
             for (int c = lane + 64; c < n_chunks; c += 64) l += pi[c].y * exp2f(pi[c].x - m);
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) l += __shfl_xor(l, off);
+            l = wave_sum(l);
             lse2[i] = m + log2f(l) + log2g;
         }
     }
