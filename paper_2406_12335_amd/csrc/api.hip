@@ -82,6 +82,7 @@ void prepare(const vatp_params *p, int which_call, const int32_t *new_pos, Prepa
     const double c = p->scale > 0.f ? static_cast<double>(p->scale) : 1.0 / sqrt(static_cast<double>(p->head_dim));
     g.scale_log2 = static_cast<float>(c * 1.4426950408889634074);
     g.max_len = 0;
+    g.stream = 0;
     memset(&out->meta, 0, sizeof(out->meta));
     for (int b = 0; b < p->batch; ++b) {
         const int len = p->len[b];
@@ -97,6 +98,10 @@ void prepare(const vatp_params *p, int which_call, const int32_t *new_pos, Prepa
         }
         if (extent > g.max_len) g.max_len = extent;
     }
+    // streaming (non-temporal) accesses when the cache rows this call may touch will not stay resident anyway
+    size_t rows = 0;
+    for (int b = 0; b < p->batch; ++b) rows += static_cast<size_t>(p->len[b] > 0 ? p->len[b] : 0);
+    g.stream = stream_rows(static_cast<size_t>(p->n_heads), rows, static_cast<size_t>(p->head_dim) * (p->dtype == VATP_BF16 ? 2 : 4));
 }
 
 // the context's device must be the current one: kernels are launched on the current device

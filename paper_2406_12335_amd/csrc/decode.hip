@@ -20,7 +20,7 @@ namespace vatp {
 
 namespace {
 
-template <typename T, int D, bool kAttend>
+template <typename T, int D, bool kAttend, bool kStream>
 __global__ __launch_bounds__(256) void decode_logits_kernel(
     const T *__restrict__ q, const T *__restrict__ k_new, const T *__restrict__ v_new,
     T *__restrict__ K, T *__restrict__ V, float *__restrict__ nrm, int32_t *__restrict__ pos,
@@ -69,7 +69,7 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(
         for (int u = 0; u < kGroup; ++u) {
             const int r = row0 + (p0 + u) * kRowsPerPass + rloc;
             const uint4 *src = (r == n0) ? knew + sub : Ku + static_cast<size_t>(r) * kLanesPerRow + sub;
-            raw[u] = (r < n) ? *src : make_uint4(0, 0, 0, 0);
+            raw[u] = (r < n) ? load_rows<kStream>(src) : make_uint4(0, 0, 0, 0);
         }
         if (p0 == 0 && owns_new_row) {
             // the workgroup that owns the new row stores k, v, |v| and pos into the caches
@@ -117,7 +117,7 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(
             for (int u = 0; u < kGroup; ++u) {
                 const int r = row0 + (p0 + u) * kRowsPerPass + rloc;
                 const uint4 *src = (r == n0) ? vnew + sub : Vu + static_cast<size_t>(r) * kLanesPerRow + sub;
-                raw[u] = (r < n) ? *src : make_uint4(0, 0, 0, 0);
+                raw[u] = (r < n) ? load_rows<kStream>(src) : make_uint4(0, 0, 0, 0);
             }
 #pragma unroll
             for (int u = 0; u < kGroup; ++u) {
@@ -145,7 +145,7 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(
 // the cache is read once per group, not once per query head).  Logits and chunk statistics are kept
 // per query head ([g, cap] and [g, chunks] per unit); with an output pointer each head's share of
 // its attention output as well.
-template <typename T, int D, bool kAttend>
+template <typename T, int D, bool kAttend, bool kStream>
 __global__ __launch_bounds__(256) void decode_logits_group_kernel(
     const T *__restrict__ q, const T *__restrict__ k_new, const T *__restrict__ v_new,
     T *__restrict__ K, T *__restrict__ V, float *__restrict__ nrm, int32_t *__restrict__ pos,
@@ -207,7 +207,7 @@ __global__ __launch_bounds__(256) void decode_logits_group_kernel(
         for (int u = 0; u < kGroup; ++u) {
             const int r = row0 + (p0 + u) * kRowsPerPass + rloc;
             const uint4 *src = (r == n0) ? knew + sub : Ku + static_cast<size_t>(r) * kLanesPerRow + sub;
-            raw[u] = (r < n) ? *src : make_uint4(0, 0, 0, 0);
+            raw[u] = (r < n) ? load_rows<kStream>(src) : make_uint4(0, 0, 0, 0);
         }
         if (p0 == 0) {
             if constexpr (!kMfma) {
@@ -321,7 +321,7 @@ __global__ __launch_bounds__(256) void decode_logits_group_kernel(
             for (int u = 0; u < kGroup; ++u) {
                 const int r = row0 + (p0 + u) * kRowsPerPass + rloc;
                 const uint4 *src = (r == n0) ? vnew + sub : Vu + static_cast<size_t>(r) * kLanesPerRow + sub;
-                raw[u] = (r < n) ? *src : make_uint4(0, 0, 0, 0);
+                raw[u] = (r < n) ? load_rows<kStream>(src) : make_uint4(0, 0, 0, 0);
             }
 #pragma unroll
             for (int u = 0; u < kGroup; ++u) {
@@ -398,11 +398,16 @@ hipError_t launch_decode(int dtype, int head_dim, const void *q, const void *k, 
     const unsigned units = static_cast<unsigned>(g.batch) * g.n_heads;
     dim3 grid(units, (g.max_len + kDecodeChunk - 1) / kDecodeChunk), block(256);
     const bool attend = ws_out != nullptr;
-#define VATP_DEC(KERNEL, T, D, A, ...)                                                                 \
-    hipLaunchKernelGGL((KERNEL<T, D, A>), grid, block, 0, st, static_cast<const T *>(q),               \
+#define VATP_DEC_S(KERNEL, T, D, A, STREAM, ...)                                                           \
+    hipLaunchKernelGGL((KERNEL<T, D, A, STREAM>), grid, block, 0, st, static_cast<const T *>(q),            \
                        static_cast<const T *>(k), static_cast<const T *>(v), static_cast<T *>(K),      \
                        static_cast<T *>(V), nrm, pos, ws_logit, ws_part, ws_out, meta, g.n_heads,      \
                        g.cap, chunks_alloc, g.scale_log2, g.norm, ##__VA_ARGS__)
+#define VATP_DEC(KERNEL, T, D, A, ...)                                                                 \
+    do {                                                                                               \
+        if (g.stream) VATP_DEC_S(KERNEL, T, D, A, true, ##__VA_ARGS__);                                \
+        else VATP_DEC_S(KERNEL, T, D, A, false, ##__VA_ARGS__);                                        \
+    } while (0)
 #define VATP_DEC2(T, D)                                                                                \
     do {                                                                                               \
         if (g.group > 1) {                                                                             \
@@ -419,6 +424,7 @@ hipError_t launch_decode(int dtype, int head_dim, const void *q, const void *k, 
     else VATP_DEC2(bf16_t, 128);
 #undef VATP_DEC2
 #undef VATP_DEC
+#undef VATP_DEC_S
     if (finish) {   // (the fused decode-and-evict step has its own second launch)
         const dim3 fgrid(units, (g.max_len + 255) / 256);
 #define VATP_FIN(G)                                                                                               \

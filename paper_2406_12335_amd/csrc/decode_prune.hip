@@ -33,7 +33,7 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
     int32_t *__restrict__ pos_out, int32_t *__restrict__ kept_idx, const int32_t *__restrict__ synced_in,
     int32_t *__restrict__ synced_out, const float *__restrict__ ws_logit, const float2 *__restrict__ ws_part,
     const float *__restrict__ ws_out, float *__restrict__ out, WindowArgs win, BatchMeta meta, int n_heads,
-    int cap, int cap_out, int chunks_alloc, int n_sink, int recent, int group)
+    int cap, int cap_out, int chunks_alloc, int n_sink, int recent, int group, int stream)
 {
     constexpr int kE = Elt<T>::kPer16B;
     constexpr int kLanesPerRow = D / kE;
@@ -192,10 +192,18 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
         const int rloc = tid / kLanesPerRow;
         for (int o = first + g * kRowsPerPass + rloc; o < n_keep; o += G * kRowsPerPass) {
             const int src = o + (o >= evicted ? 1 : 0);
-            const uint4 kr = Ku[static_cast<size_t>(src) * kLanesPerRow + sub];
-            const uint4 vr = Vu[static_cast<size_t>(src) * kLanesPerRow + sub];
-            Ko[static_cast<size_t>(o) * kLanesPerRow + sub] = kr;
-            Vo[static_cast<size_t>(o) * kLanesPerRow + sub] = vr;
+            uint4 kr, vr;
+            if (stream) {       // (uniform: the whole call either streams or does not)
+                kr = load_stream(Ku + static_cast<size_t>(src) * kLanesPerRow + sub);
+                vr = load_stream(Vu + static_cast<size_t>(src) * kLanesPerRow + sub);
+                store_stream(Ko + static_cast<size_t>(o) * kLanesPerRow + sub, kr);
+                store_stream(Vo + static_cast<size_t>(o) * kLanesPerRow + sub, vr);
+            } else {
+                kr = Ku[static_cast<size_t>(src) * kLanesPerRow + sub];
+                vr = Vu[static_cast<size_t>(src) * kLanesPerRow + sub];
+                Ko[static_cast<size_t>(o) * kLanesPerRow + sub] = kr;
+                Vo[static_cast<size_t>(o) * kLanesPerRow + sub] = vr;
+            }
             if (sub == 0) {
                 nrm_out[unit * cap_out + o] = Nu[src];
                 if (pos_out) pos_out[unit * cap_out + o] = pos[unit * cap + src];
@@ -213,13 +221,24 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
 // The whole step in one launch, one workgroup of 16 wavefronts per head: logits of the new query
 // over the head's rows (they stay in LDS), softmax statistics, new scores, the evicted row, and
 // the rows of the other cache set that are out of date.  Used when every head's rows fit the LDS
-// buffer; no workspace traffic and no second launch.  The per-chunk statistics are formed
-// exactly as decode_logits_kernel forms them (128-row chunks, the same butterflies), so the
-// result has the same bits as the two-launch route.
+// buffer; no workspace traffic and no second launch.  Logits and per-chunk statistics are formed by
+// the same functions as in decode_logits_kernel (dot_16_bytes, group_all_reduce, chunk_stats_64x2 on
+// 128-row chunks), so the result has the same bits as the two-launch route.
+//
+// Rows are dealt to threads from the END of the cache: load slot u of thread (rloc, sub) is row
+// n-1 - (u * rows_per_pass + rloc).  The row that leaves is almost always the one at the edge of the recent
+// window, e* = n - recent - 1 (it has just lost the window's protection and has collected the least
+// attention), and then exactly the rows behind it move one position down in the other set.  Those rows are
+// the first slots of every thread: their V rows, norms and positions are the first loads of the kernel,
+// their K rows the first of the stream, and they are stored -- to the positions the guess e* implies -- as
+// soon as they have arrived, while the rest of the head is still streaming in, instead of in a burst at the
+// end.  When the real evicted row e turns out to lie before e*, what was stored is still right (rows behind
+// e* move down by one either way); row e* itself, which the guess skipped, is then stored to e* - 1 from the
+// registers that still hold it, and the rows between e and e* are copied the ordinary way.
 constexpr int kOneThreads = 1024;
 constexpr int kOneMaxRows = 2048;                          // logits, old scores and norms kept in LDS (24 KiB)
 
-template <typename T, int D>
+template <typename T, int D, bool kStream>
 __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
     const T *__restrict__ q, const T *__restrict__ k_new, const T *__restrict__ v_new, T *__restrict__ K,
     T *__restrict__ V, const float *__restrict__ S, float *__restrict__ nrm, int32_t *__restrict__ pos,
@@ -234,6 +253,9 @@ __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
     constexpr int kGroup = 16;                             // row loads in flight per thread: 1024 rows per round trip
     constexpr int kWaves = kOneThreads / 64;
     constexpr int kPre = kOneMaxRows / kOneThreads;        // rows of S and nrm a thread brings in
+    // rows requested ahead of the eviction: the last kSpecRows of the cache (>= 128), kSpecSlots per thread
+    constexpr int kSpecSlots = kRowsPerPass >= 64 ? 2 : 128 / kRowsPerPass, kSpecRows = kSpecSlots * kRowsPerPass;
+    static_assert(kSpecSlots <= kGroup, "the speculative rows are slots of the first round trip");
 
     __shared__ float s_logit[kOneMaxRows];
     __shared__ float s_score[kOneMaxRows];                 // old scores (0 for the appended row)
@@ -253,17 +275,40 @@ __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
     const uint4 *Ku = reinterpret_cast<const uint4 *>(K + unit * cap * D);
     const uint4 *Vu = reinterpret_cast<const uint4 *>(V + unit * cap * D);
     const uint4 *knew = reinterpret_cast<const uint4 *>(k_new + unit * D);
-    const int synced = synced_in[unit];
+    const uint4 *vnew = reinterpret_cast<const uint4 *>(v_new + unit * D);
 
-    // Every load this phase needs is requested before the first result is used: the query, the new row,
-    // the old scores and norms (parked in LDS after the sweep, so that the later phases do not start with a
-    // round trip to memory of their own), then the first 16 K rows of every thread.
-    const uint4 q_raw = reinterpret_cast<const uint4 *>(q + unit * D)[sub];
-    uint4 k_raw = make_uint4(0, 0, 0, 0), v_raw = make_uint4(0, 0, 0, 0);
-    if (tid < kLanesPerRow) {
-        k_raw = knew[sub];
-        v_raw = reinterpret_cast<const uint4 *>(v_new + unit * D)[sub];
+    // the row expected to leave (n > B: there are candidates, so n - recent - 1 >= n_sink), and the first of
+    // the rows that are stored ahead of the decision
+    const int e_star = n > B ? n - recent - 1 : n;
+    const int spec_lo = max(max(n - recent - 1, n - kSpecRows), 0);
+    uint4 *Ko = reinterpret_cast<uint4 *>(K_out + unit * cap_out * D);
+    uint4 *Vo = reinterpret_cast<uint4 *>(V_out + unit * cap_out * D);
+
+    // Every load this phase needs is requested before the first result is used: V rows, norms and positions
+    // of the rows stored ahead, the count of rows the two sets share, the query, the new row, the old scores
+    // and norms (parked in LDS after the sweep, so that the later phases do not start with a round trip to
+    // memory of their own), then the first 16 K rows of every thread.
+    uint4 spec_k[kSpecSlots], spec_v[kSpecSlots];
+    float spec_w[kSpecSlots];
+    int spec_pos[kSpecSlots];
+#pragma unroll
+    for (int u = 0; u < kSpecSlots; ++u) {
+        const int r = n - 1 - (u * kRowsPerPass + rloc);
+        spec_v[u] = make_uint4(0, 0, 0, 0);
+        spec_w[u] = 0.f;
+        spec_pos[u] = 0;
+        if (r >= spec_lo) {
+            spec_v[u] = r == n0 ? vnew[sub] : load_rows<kStream>(Vu + static_cast<size_t>(r) * kLanesPerRow + sub);
+            if (sub == 0 && r != n0) {
+                spec_w[u] = Nu[r];
+                if (pos) spec_pos[u] = pos[unit * cap + r];
+            }
+        }
     }
+    const int synced = synced_in[unit];
+    const uint4 q_raw = reinterpret_cast<const uint4 *>(q + unit * D)[sub];
+    uint4 k_raw = make_uint4(0, 0, 0, 0);
+    if (tid < kLanesPerRow) k_raw = knew[sub];
     float pre_s[kPre], pre_w[kPre];
 #pragma unroll
     for (int u = 0; u < kPre; ++u) {
@@ -271,52 +316,51 @@ __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
         pre_s[u] = r < n0 ? Su[r] : 0.f;
         pre_w[u] = r < n0 ? Nu[r] : 0.f;
     }
+
     // logits of all rows into LDS; the new row is read from the step's input, not from the cache
-    for (int r0 = 0; r0 < n; r0 += kGroup * kRowsPerPass) {
+    for (int base = 0; base < n; base += kGroup * kRowsPerPass) {
         uint4 raw[kGroup];
 #pragma unroll
         for (int u = 0; u < kGroup; ++u) {
-            const int r = r0 + u * kRowsPerPass + rloc;
+            const int r = n - 1 - (base + u * kRowsPerPass + rloc);
             const uint4 *src = (r == n0) ? knew + sub : Ku + static_cast<size_t>(r) * kLanesPerRow + sub;
-            raw[u] = (r < n) ? *src : make_uint4(0, 0, 0, 0);
+            raw[u] = (r >= 0) ? load_rows<kStream>(src) : make_uint4(0, 0, 0, 0);
         }
-        if (r0 == 0 && tid < kLanesPerRow) {
-            // append the new row: k, v, |v|, pos
-            reinterpret_cast<uint4 *>(K + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = k_raw;
-            reinterpret_cast<uint4 *>(V + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = v_raw;
-            const float new_norm = row_norm<T, kLanesPerRow>(norm, v_raw);
-            if (sub == 0) {
-                s_new_norm = new_norm;
-                Nu[n0] = new_norm;
-                if (pos) pos[unit * cap + n0] = len_pos.aux[b];
+        if (base == 0) {
+            if (tid < kLanesPerRow) {
+                // append the new row (slot 0 of these threads): k, v, |v|, pos
+                reinterpret_cast<uint4 *>(K + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = k_raw;
+                reinterpret_cast<uint4 *>(V + unit * cap * D)[static_cast<size_t>(n0) * kLanesPerRow + sub] = spec_v[0];
+                const float new_norm = row_norm<T, kLanesPerRow>(norm, spec_v[0]);
+                if (sub == 0) {
+                    s_new_norm = new_norm;
+                    Nu[n0] = new_norm;
+                    if (pos) pos[unit * cap + n0] = len_pos.aux[b];
+                    spec_w[0] = new_norm;
+                    spec_pos[0] = len_pos.aux[b];
+                }
+            }
+            // the rows behind the expected eviction go to the other set now, at the positions that guess implies
+#pragma unroll
+            for (int u = 0; u < kSpecSlots; ++u) {
+                const int r = n - 1 - (u * kRowsPerPass + rloc);
+                spec_k[u] = raw[u];
+                if (r >= spec_lo && r != e_star) {
+                    const int o = r - (r > e_star ? 1 : 0);
+                    store_rows<kStream>(Ko + static_cast<size_t>(o) * kLanesPerRow + sub, raw[u]);
+                    store_rows<kStream>(Vo + static_cast<size_t>(o) * kLanesPerRow + sub, spec_v[u]);
+                    if (sub == 0) {
+                        nrm_out[unit * cap_out + o] = spec_w[u];
+                        if (pos_out) pos_out[unit * cap_out + o] = spec_pos[u];
+                    }
+                }
             }
         }
 #pragma unroll
         for (int u = 0; u < kGroup; ++u) {
-            const int r = r0 + u * kRowsPerPass + rloc;
+            const int r = n - 1 - (base + u * kRowsPerPass + rloc);
             const float dot = group_all_reduce<kLanesPerRow>(dot_16_bytes<T>(raw[u], q_raw), OpSum{});
-            if (sub == 0 && r < n) s_logit[r] = dot * scale_log2;
-        }
-    }
-    // Rows that will most likely have to be copied to the other set are requested now, while the statistics
-    // and the scan below run on LDS alone: the row that leaves is almost always the one at the edge of the
-    // recent window, so the copy starts near min(synced, n - recent - 1).  At most kSpecRows rows, kSpecSlots per
-    // thread; whatever the guess misses is copied the ordinary way afterwards.  (The appended row comes from
-    // the step's input, not from the cache row other threads have just stored.)
-    constexpr int kSpecSlots = kRowsPerPass >= 64 ? 2 : 128 / kRowsPerPass, kSpecRows = kSpecSlots * kRowsPerPass;   // >= 128 rows
-    const int spec_first = max(max(min(synced, n - recent - 1), n - kSpecRows), 0);
-    uint4 spec_k[kSpecSlots], spec_v[kSpecSlots];
-    int spec_pos[kSpecSlots];
-#pragma unroll
-    for (int u = 0; u < kSpecSlots; ++u) {
-        const int r = spec_first + u * kRowsPerPass + rloc;
-        spec_k[u] = spec_v[u] = make_uint4(0, 0, 0, 0);
-        spec_pos[u] = 0;
-        if (r < n) {
-            spec_k[u] = r == n0 ? knew[sub] : Ku[static_cast<size_t>(r) * kLanesPerRow + sub];
-            spec_v[u] = r == n0 ? reinterpret_cast<const uint4 *>(v_new + unit * D)[sub]
-                                : Vu[static_cast<size_t>(r) * kLanesPerRow + sub];
-            if (pos && sub == 0) spec_pos[u] = r == n0 ? len_pos.aux[b] : pos[unit * cap + r];
+            if (sub == 0 && r >= 0) s_logit[r] = dot * scale_log2;
         }
     }
 #pragma unroll
@@ -324,8 +368,9 @@ __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
         const int r = tid + u * kOneThreads;
         if (r < n0) { s_score[r] = pre_s[u]; s_norm[r] = pre_w[u]; }
     }
-    __syncthreads();
-    if (tid == 0) { s_score[n0] = 0.f; s_norm[n0] = s_new_norm; }      // the appended row (published by the syncs below)
+    // (a barrier for LDS only: the writes above must be visible, the V rows requested ahead need not have arrived)
+    lds_barrier();
+    if (tid == 0) { s_score[n0] = 0.f; s_norm[n0] = s_new_norm; }      // the appended row (published by the barriers below)
 
     // Statistics of every 128-row chunk, one wavefront per chunk and no exchange between wavefronts: the lane
     // takes rows lane and lane + 64 of the chunk -- the same function, on the same values, as in
@@ -336,27 +381,34 @@ __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
         const float2 st = chunk_stats_64x2(r0 < n ? s_logit[r0] : -INFINITY, r1 < n ? s_logit[r1] : -INFINITY);
         if (lane == 0) s_part[chunk] = st;
     }
-    __syncthreads();
+    lds_barrier();
     float M, L;
     merge_chunk_stats(s_part, n_chunks, M, L);
     const float lse2 = M + log2f(L);
 
     auto new_score = [&](int r) { return s_score[r] + exp2f(s_logit[r] - lse2); };
-    auto row_norm = [&](int r) { return s_norm[r]; };
 
-    // the row that leaves: minimise (importance bits, ~row) over the unprotected rows
+    // the row that leaves: smallest importance among the unprotected rows, the highest row among equals.
+    // A thread looks at rows tid, tid + 1024, ...: within a wavefront rows ascend with the lane, so the
+    // wavefront's answer for one such round is the smallest key and the highest lane that holds it.
     int evicted = n;
     if (n > B) {
         unsigned long long best = ~0ull;
-        for (int r = n_sink + tid; r < n - recent; r += kOneThreads) {
-            const unsigned key = __float_as_uint(__fmul_rn(new_score(r), row_norm(r)));
-            const unsigned long long c =
-                (static_cast<unsigned long long>(key) << 32) | static_cast<unsigned>(~static_cast<unsigned>(r));
-            best = c < best ? c : best;
+        for (int r0 = 0; r0 < n - recent; r0 += kOneThreads) {
+            const int r = r0 + tid;
+            const bool cand = r >= n_sink && r < n - recent;
+            const unsigned key = cand ? __float_as_uint(__fmul_rn(new_score(r), s_norm[r])) : 0xffffffffu;
+            const unsigned kmin = wave_min_u32(key);
+            const unsigned long long holders = __ballot(cand && key == kmin);
+            if (holders != 0ull) {
+                const int top = 63 - __builtin_clzll(holders);
+                const unsigned long long c = (static_cast<unsigned long long>(kmin) << 32) |
+                                             static_cast<unsigned>(~static_cast<unsigned>(r0 + wave * 64 + top));
+                best = c < best ? c : best;
+            }
         }
-        best = wave_min_u64(best);
         if (lane == 0) s_min[wave] = best;
-        __syncthreads();
+        lds_barrier();
         best = s_min[0];
 #pragma unroll
         for (int w = 1; w < kWaves; ++w) best = s_min[w] < best ? s_min[w] : best;
@@ -367,39 +419,43 @@ __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
     // set, or from the evicted row if that comes earlier.  Source row r goes to row r - (r > evicted).
     const int first = min(synced, evicted);
     if (tid == 0) synced_out[unit] = evicted;
-    uint4 *Ko = reinterpret_cast<uint4 *>(K_out + unit * cap_out * D);
-    uint4 *Vo = reinterpret_cast<uint4 *>(V_out + unit * cap_out * D);
-    // ... those requested ahead of time, each stored by the thread that holds it
-#pragma unroll
-    for (int u = 0; u < kSpecSlots; ++u) {
-        const int r = spec_first + u * kRowsPerPass + rloc;
-        const int o = r - (r > evicted ? 1 : 0);
-        if (r < n && r != evicted && o >= first) {
-            Ko[static_cast<size_t>(o) * kLanesPerRow + sub] = spec_k[u];
-            Vo[static_cast<size_t>(o) * kLanesPerRow + sub] = spec_v[u];
-            if (sub == 0) {
-                nrm_out[unit * cap_out + o] = s_norm[r];
-                if (pos_out) pos_out[unit * cap_out + o] = spec_pos[u];
-            }
-        }
-    }
 
+    // new scores and source rows of the survivors
     for (int o = tid; o < n_keep; o += kOneThreads) {
         const int src = o + (o >= evicted ? 1 : 0);
         S_out[unit * cap_out + o] = new_score(src);
         if (kept_idx) kept_idx[unit * cap_out + o] = src;
     }
 
-    // ... and the rows before them, if the copy has to start earlier than guessed (source rows below
-    // spec_first: never the appended row, so everything is read from the cache as it was on entry)
+    // The rows from spec_lo on are in place already, except that a row e* which does not leave after all
+    // (evicted < e*) has not been stored: it goes to e* - 1.
+    if (evicted != e_star) {
+#pragma unroll
+        for (int u = 0; u < kSpecSlots; ++u) {
+            const int r = n - 1 - (u * kRowsPerPass + rloc);
+            if (r == e_star && r >= spec_lo) {
+                const int o = r - 1;
+                store_rows<kStream>(Ko + static_cast<size_t>(o) * kLanesPerRow + sub, spec_k[u]);
+                store_rows<kStream>(Vo + static_cast<size_t>(o) * kLanesPerRow + sub, spec_v[u]);
+                if (sub == 0) {
+                    nrm_out[unit * cap_out + o] = spec_w[u];
+                    if (pos_out) pos_out[unit * cap_out + o] = spec_pos[u];
+                }
+            }
+        }
+    }
+
+    // ... and the rows before spec_lo that are out of date (the two sets were in step only up to a row
+    // before it, or the evicted row lies before it) are copied from the cache as it was on entry: source
+    // rows below spec_lo, never the appended row
     {
-        const int o_end = min(n_keep, spec_first - (evicted < spec_first ? 1 : 0));
+        const int o_end = min(n_keep, spec_lo - (evicted < spec_lo ? 1 : 0));
         for (int o = first + rloc; o < o_end; o += kRowsPerPass) {
             const int src = o + (o >= evicted ? 1 : 0);
-            const uint4 kr = Ku[static_cast<size_t>(src) * kLanesPerRow + sub];
-            const uint4 vr = Vu[static_cast<size_t>(src) * kLanesPerRow + sub];
-            Ko[static_cast<size_t>(o) * kLanesPerRow + sub] = kr;
-            Vo[static_cast<size_t>(o) * kLanesPerRow + sub] = vr;
+            const uint4 kr = load_rows<kStream>(Ku + static_cast<size_t>(src) * kLanesPerRow + sub);
+            const uint4 vr = load_rows<kStream>(Vu + static_cast<size_t>(src) * kLanesPerRow + sub);
+            store_rows<kStream>(Ko + static_cast<size_t>(o) * kLanesPerRow + sub, kr);
+            store_rows<kStream>(Vo + static_cast<size_t>(o) * kLanesPerRow + sub, vr);
             if (sub == 0) {
                 nrm_out[unit * cap_out + o] = s_norm[src];
                 if (pos_out) pos_out[unit * cap_out + o] = pos[unit * cap + src];
@@ -429,7 +485,7 @@ hipError_t launch_decode_prune(int dtype, int head_dim, const void *K, const voi
     hipLaunchKernelGGL((decode_prune_kernel<T, D, G>), grid, block, 0, st, static_cast<const T *>(K),            \
                        static_cast<const T *>(V), S, nrm, pos, static_cast<T *>(K_out), static_cast<T *>(V_out), \
                        S_out, nrm_out, pos_out, kept_idx, synced_in, synced_out, ws_logit, ws_part, ws_out, out, \
-                       win, meta, g.n_heads, g.cap, g.cap_out, chunks_alloc, g.n_sink, g.recent, g.group)
+                       win, meta, g.n_heads, g.cap, g.cap_out, chunks_alloc, g.n_sink, g.recent, g.group, g.stream)
     // (instantiated for group sizes up to 2, 4, 8 and 16: the smallest that fits)
 #define VATP_DP(T, D)                                      \
     do {                                                   \
@@ -463,7 +519,12 @@ hipError_t launch_decode_prune_one(int dtype, int head_dim, const void *q, const
     const unsigned units = static_cast<unsigned>(g.batch) * g.n_heads;
     dim3 grid(units), block(kOneThreads);
 #define VATP_DP1(T, D)                                                                                           \
-    hipLaunchKernelGGL((decode_prune_one_kernel<T, D>), grid, block, 0, st, static_cast<const T *>(q),            \
+    do {                                                                                                         \
+        if (g.stream) VATP_DP1_S(T, D, true);                                                                    \
+        else VATP_DP1_S(T, D, false);                                                                            \
+    } while (0)
+#define VATP_DP1_S(T, D, STREAM)                                                                                    \
+    hipLaunchKernelGGL((decode_prune_one_kernel<T, D, STREAM>), grid, block, 0, st, static_cast<const T *>(q),         \
                        static_cast<const T *>(k), static_cast<const T *>(v), static_cast<T *>(K),                \
                        static_cast<T *>(V), S, nrm, pos, static_cast<T *>(K_out), static_cast<T *>(V_out), S_out, \
                        nrm_out, pos_out, kept_idx, synced_in, synced_out, len_pos, budget, g.n_heads, g.cap,     \
@@ -473,6 +534,7 @@ hipError_t launch_decode_prune_one(int dtype, int head_dim, const void *q, const
     else if (head_dim == 64) VATP_DP1(bf16_t, 64);
     else VATP_DP1(bf16_t, 128);
 #undef VATP_DP1
+#undef VATP_DP1_S
     return hipGetLastError();
 }
 

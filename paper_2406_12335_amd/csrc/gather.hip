@@ -19,7 +19,7 @@ namespace {
 
 constexpr int kGatherRows = 64;    // output rows per workgroup
 
-template <typename T, int D, bool kEvictOne>
+template <typename T, int D, bool kEvictOne, bool kStream>
 __global__ __launch_bounds__(256) void gather_kernel(
     const T *__restrict__ K, const T *__restrict__ V, const float *__restrict__ S,
     const float *__restrict__ nrm, const int32_t *__restrict__ pos, T *__restrict__ K_out,
@@ -102,10 +102,10 @@ __global__ __launch_bounds__(256) void gather_kernel(
         if (o < n_keep) {
             const size_t src = static_cast<size_t>(s_src[ol]) * kLanesPerRow + sub;
             const size_t dst = static_cast<size_t>(o) * kLanesPerRow + sub;
-            const uint4 kr = Ku[src];
-            const uint4 vr = Vu[src];
-            Ko[dst] = kr;
-            Vo[dst] = vr;
+            const uint4 kr = load_rows<kStream>(Ku + src);
+            const uint4 vr = load_rows<kStream>(Vu + src);
+            store_rows<kStream>(Ko + dst, kr);
+            store_rows<kStream>(Vo + dst, vr);
         }
     }
 }
@@ -158,7 +158,12 @@ hipError_t launch_gather(int dtype, int head_dim, bool evict_one,
     if (g.max_len <= 0) return hipSuccess;       // max_len: largest surviving row count
     dim3 grid((g.max_len + kGatherRows - 1) / kGatherRows, g.n_heads, g.batch), block(256);
 #define VATP_GA(T, D, E)                                                                         \
-    hipLaunchKernelGGL((gather_kernel<T, D, E>), grid, block, 0, st, static_cast<const T *>(K),   \
+    do {                                                                                         \
+        if (g.stream) VATP_GA_S(T, D, E, true);                                                  \
+        else VATP_GA_S(T, D, E, false);                                                          \
+    } while (0)
+#define VATP_GA_S(T, D, E, STREAM)                                                                    \
+    hipLaunchKernelGGL((gather_kernel<T, D, E, STREAM>), grid, block, 0, st, static_cast<const T *>(K), \
                        static_cast<const T *>(V), S, nrm, pos, static_cast<T *>(K_out),          \
                        static_cast<T *>(V_out), S_out, nrm_out, pos_out, kept_idx, meta,         \
                        g.n_heads, g.cap, g.cap_out, g.n_sink, g.recent)
@@ -169,6 +174,7 @@ hipError_t launch_gather(int dtype, int head_dim, bool evict_one,
     else VATP_GA2(bf16_t, 128);
 #undef VATP_GA2
 #undef VATP_GA
+#undef VATP_GA_S
     return hipGetLastError();
 }
 
