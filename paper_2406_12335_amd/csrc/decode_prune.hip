@@ -423,8 +423,13 @@ __global__ __launch_bounds__(kOneThreads) void decode_prune_one_kernel(
     // new scores and source rows of the survivors
     for (int o = tid; o < n_keep; o += kOneThreads) {
         const int src = o + (o >= evicted ? 1 : 0);
-        S_out[unit * cap_out + o] = new_score(src);
-        if (kept_idx) kept_idx[unit * cap_out + o] = src;
+        if constexpr (kStream) {
+            __builtin_nontemporal_store(new_score(src), &S_out[unit * cap_out + o]);
+            if (kept_idx) __builtin_nontemporal_store(src, &kept_idx[unit * cap_out + o]);
+        } else {
+            S_out[unit * cap_out + o] = new_score(src);
+            if (kept_idx) kept_idx[unit * cap_out + o] = src;
+        }
     }
 
     // The rows from spec_lo on are in place already, except that a row e* which does not leave after all
