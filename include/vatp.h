@@ -261,7 +261,8 @@ vatp_status vatp_decode_prune_step_static(vatp_ctx *ctx, const vatp_params *p,
  * left), after which hist_out (device
  * float32 [batch, n_heads, w+2, cap_hist], cap_hist >= min(len, budget)) holds the history of
  * the survivors as a ring (query j in row j mod (w+2)), column o for survivor o, hid_out ([batch, n_heads, cap_out] int32) is set to
- * o and free_out ([batch * n_heads] int32) to the survivor count.
+ * o and free_out ([batch * n_heads] int32) to the survivor count.  S_lo_out (device float32
+ * [batch, n_heads, cap_out]) receives the low-order part of every survivor's score (see below).
  *
  * vatp_decode_prune_step_window: vatp_decode_prune_step with S_new = S + a^t - a^(t-w-1),
  * t = new_pos[b] (HOST, required: the index of the new token in its sequence, counted on from
@@ -271,8 +272,12 @@ vatp_status vatp_decode_prune_step_static(vatp_ctx *ctx, const vatp_params *p,
  * one while the cache still grows); free_in / free_out are distinct device arrays
  * [batch * n_heads] that the caller swaps like synced_in / synced_out.  hist is updated in
  * place: ring row t mod (w+2) is written, row (t+1) mod (w+2) read.  cap_hist >= budget[b] + 1.
- * fp32 sums that add and later subtract the same weights carry an absolute error of a few
- * ulps of the largest score a row ever had, times the number of steps.
+ * The score of a row is carried as the unevaluated sum of two floats, S (what the selection
+ * sees) and a low-order part S_lo / S_lo_out (device float32, per row like S / S_out, moving with
+ * the rows; distinct arrays that alternate with the cache sets): a weight is added when it enters
+ * the window and the same float is subtracted when it leaves, each time by an error-free
+ * transformation, so the error of a score stays relative to the score itself (about 2^-47 of the
+ * running sum per step) however large the score once was and however many steps have passed.
  */
 vatp_status vatp_prefill_score_window(vatp_ctx *ctx, const vatp_params *p,
                                       const void *Q, const void *K, const void *V, int32_t window,
@@ -286,6 +291,7 @@ vatp_status vatp_select_compact_window(vatp_ctx *ctx, const vatp_params *p,
                                        void *K_out, void *V_out, float *S_out, float *nrm_out,
                                        int32_t *pos_out, int32_t *kept_idx, float *hist_out,
                                        int32_t cap_hist, int32_t *hid_out, int32_t *free_out,
+                                       float *S_lo_out,
                                        void *ws, size_t ws_bytes, void *hip_stream);
 
 vatp_status vatp_decode_prune_step_window(vatp_ctx *ctx, const vatp_params *p,
@@ -296,7 +302,8 @@ vatp_status vatp_decode_prune_step_window(vatp_ctx *ctx, const vatp_params *p,
                                           int32_t *pos_out, int32_t *hid_out, int32_t *kept_idx,
                                           const int32_t *synced_in, int32_t *synced_out,
                                           const int32_t *free_in, int32_t *free_out,
-                                          float *hist, int32_t window, int32_t cap_hist, float *out,
+                                          float *hist, const float *S_lo, float *S_lo_out,
+                                          int32_t window, int32_t cap_hist, float *out,
                                           void *ws, size_t ws_bytes, void *hip_stream);
 
 #ifdef __cplusplus

@@ -88,10 +88,10 @@ def load() -> ctypes.CDLL:
     i32, i32p = ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)
     L.vatp_prefill_score_window.argtypes = [_vp, pp, _vp, _vp, _vp, i32, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
     L.vatp_prefill_score_window.restype = ctypes.c_int
-    L.vatp_select_compact_window.argtypes = [_vp, pp] + [_vp] * 6 + [i32] + [_vp] * 7 + [i32, _vp, _vp] + \
+    L.vatp_select_compact_window.argtypes = [_vp, pp] + [_vp] * 6 + [i32] + [_vp] * 7 + [i32, _vp, _vp, _vp] + \
         [_vp, ctypes.c_size_t, _vp]
     L.vatp_select_compact_window.restype = ctypes.c_int
-    L.vatp_decode_prune_step_window.argtypes = [_vp, pp] + [_vp] * 9 + [i32p] + [_vp] * 12 + [i32, i32, _vp] + \
+    L.vatp_decode_prune_step_window.argtypes = [_vp, pp] + [_vp] * 9 + [i32p] + [_vp] * 14 + [i32, i32, _vp] + \
         [_vp, ctypes.c_size_t, _vp]
     L.vatp_decode_prune_step_window.restype = ctypes.c_int
     L.vatp_select_compact.argtypes = [_vp, pp] + [_vp] * 11 + [_vp, ctypes.c_size_t, _vp]
@@ -231,23 +231,26 @@ def vatp_prefill_score_window(ctx, p: Params, Q, K, V, window: int, S, nrm, hist
 
 
 def vatp_select_compact_window(ctx, p: Params, K, V, S, nrm, pos, hist, window: int, K_out, V_out, S_out, nrm_out,
-                               pos_out, kept_idx, hist_out, cap_hist: int, hid_out, free_out, ws=None,
+                               pos_out, kept_idx, hist_out, cap_hist: int, hid_out, free_out, S_lo_out, ws=None,
                                stream=None) -> None:
     _check(load().vatp_select_compact_window(ctx, p.ref(), _ptr(K), _ptr(V), _ptr(S), _ptr(nrm), _ptr(pos), _ptr(hist),
                                              int(window), _ptr(K_out), _ptr(V_out), _ptr(S_out), _ptr(nrm_out),
                                              _ptr(pos_out), _ptr(kept_idx), _ptr(hist_out), int(cap_hist),
-                                             _ptr(hid_out), _ptr(free_out), _ptr(ws), _nbytes(ws), _stream(stream)),
+                                             _ptr(hid_out), _ptr(free_out), _ptr(S_lo_out), _ptr(ws), _nbytes(ws),
+                                             _stream(stream)),
            "vatp_select_compact_window")
 
 
 def vatp_decode_prune_step_window(ctx, p: Params, q, k, v, K, V, S, nrm, pos, hid, new_pos: Sequence[int], K_out,
                                   V_out, S_out, nrm_out, pos_out, hid_out, kept_idx, synced_in, synced_out, free_in,
-                                  free_out, hist, window: int, cap_hist: int, out, ws, stream=None) -> None:
+                                  free_out, hist, S_lo, S_lo_out, window: int, cap_hist: int, out, ws,
+                                  stream=None) -> None:
     npos = (ctypes.c_int32 * len(new_pos))(*[int(x) for x in new_pos]) if new_pos is not None else None
     _check(load().vatp_decode_prune_step_window(
         ctx, p.ref(), _ptr(q), _ptr(k), _ptr(v), _ptr(K), _ptr(V), _ptr(S), _ptr(nrm), _ptr(pos), _ptr(hid), npos,
         _ptr(K_out), _ptr(V_out), _ptr(S_out), _ptr(nrm_out), _ptr(pos_out), _ptr(hid_out), _ptr(kept_idx),
-        _ptr(synced_in), _ptr(synced_out), _ptr(free_in), _ptr(free_out), _ptr(hist), int(window), int(cap_hist),
+        _ptr(synced_in), _ptr(synced_out), _ptr(free_in), _ptr(free_out), _ptr(hist), _ptr(S_lo), _ptr(S_lo_out),
+        int(window), int(cap_hist),
         _ptr(out), _ptr(ws), _nbytes(ws), _stream(stream)), "vatp_decode_prune_step_window")
 
 

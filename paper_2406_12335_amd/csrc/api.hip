@@ -432,14 +432,17 @@ vatp_status vatp_decode_prune_step_window(vatp_ctx *ctx, const vatp_params *p, c
                                           void *V_out, float *S_out, float *nrm_out, int32_t *pos_out,
                                           int32_t *hid_out, int32_t *kept_idx, const int32_t *synced_in,
                                           int32_t *synced_out, const int32_t *free_in, int32_t *free_out,
-                                          float *hist, int32_t window, int32_t cap_hist, float *out, void *ws,
-                                          size_t ws_bytes, void *hip_stream)
+                                          float *hist, const float *S_lo, float *S_lo_out, int32_t window,
+                                          int32_t cap_hist, float *out, void *ws, size_t ws_bytes, void *hip_stream)
 {
-    if (!p || !hid || !hid_out || !free_in || !free_out || !hist || !new_pos) return VATP_E_NULL;
-    if (window < 0 || window > kMaxWindow || hid == hid_out || free_in == free_out) return VATP_E_SHAPE;
+    if (!p || !hid || !hid_out || !free_in || !free_out || !hist || !new_pos || !S_lo || !S_lo_out) return VATP_E_NULL;
+    if (window < 0 || window > kMaxWindow || hid == hid_out || free_in == free_out || S_lo == S_lo_out)
+        return VATP_E_SHAPE;
     if (p->batch < 1 || p->batch > VATP_MAX_BATCH || !p->budget) return p->budget ? VATP_E_SHAPE : VATP_E_NULL;
     WindowArgs win = {};
     win.hist = hist;
+    win.s_lo = S_lo;
+    win.s_lo_out = S_lo_out;
     win.hid = hid;
     win.hid_out = hid_out;
     win.free_in = free_in;
@@ -459,10 +462,10 @@ vatp_status vatp_select_compact_window(vatp_ctx *ctx, const vatp_params *p, cons
                                        const float *S, const float *nrm, const int32_t *pos, const float *hist,
                                        int32_t window, void *K_out, void *V_out, float *S_out, float *nrm_out,
                                        int32_t *pos_out, int32_t *kept_idx, float *hist_out, int32_t cap_hist,
-                                       int32_t *hid_out, int32_t *free_out, void *ws, size_t ws_bytes,
-                                       void *hip_stream)
+                                       int32_t *hid_out, int32_t *free_out, float *S_lo_out, void *ws,
+                                       size_t ws_bytes, void *hip_stream)
 {
-    if (!hist || !hist_out || !hid_out || !free_out) return VATP_E_NULL;
+    if (!hist || !hist_out || !hid_out || !free_out || !S_lo_out) return VATP_E_NULL;
     if (window < 0 || window > kMaxWindow || hist == hist_out) return VATP_E_SHAPE;
     vatp_status st = check_params(p, VATP_CALL_SELECT_COMPACT);
     if (st != VATP_OK) return st;
@@ -473,7 +476,7 @@ vatp_status vatp_select_compact_window(vatp_ctx *ctx, const vatp_params *p, cons
     if (st != VATP_OK) return st;
     Prepared pr;
     prepare(p, VATP_CALL_SELECT_COMPACT, nullptr, &pr);
-    if (launch_hist_gather(hist, kept_idx, hist_out, hid_out, free_out, window + 2, cap_hist, pr.meta, pr.g,
+    if (launch_hist_gather(hist, kept_idx, hist_out, hid_out, free_out, S_out, S_lo_out, window + 2, cap_hist, pr.meta, pr.g,
                            static_cast<hipStream_t>(hip_stream)) != hipSuccess)
         return VATP_E_DEVICE;
     return VATP_OK;

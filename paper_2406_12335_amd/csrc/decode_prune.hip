@@ -67,11 +67,12 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
     const int new_col = windowed ? win.free_in[unit] : 0;
     auto column = [&](int r) { return r == n0 ? new_col : win.hid[unit * cap + r]; };
     auto leaving = [&](int r) { return windowed && r != n0 ? h_leave[column(r)] : 0.f; };
+    auto low_part = [&](int r) { return windowed && r != n0 ? win.s_lo[unit * cap + r] : 0.f; };
 
     // the unprotected rows this thread looks at (logit, old score, norm), requested before the
     // denominator is known so that both round trips to memory overlap
     constexpr int kScan = kMaxG > 8 ? 1 : 4;                 // rows per thread and round trip (each brings kMaxG logits)
-    float t_r[kScan][kMaxG], s_r[kScan], w_r[kScan], x_r[kScan];
+    float t_r[kScan][kMaxG], s_r[kScan], w_r[kScan], x_r[kScan], l_r[kScan];
 #pragma unroll
     for (int u = 0; u < kScan; ++u) {
         const int r = lo + tid + u * kThreads;
@@ -80,6 +81,7 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
         s_r[u] = ok && r != n0 ? Su[r] : 0.f;
         w_r[u] = ok ? Nu[r] : 0.f;
         x_r[u] = ok ? leaving(r) : 0.f;
+        l_r[u] = ok ? low_part(r) : 0.f;
     }
 
     // log2 of the softmax denominator of every query head of the group from the chunk statistics
@@ -88,14 +90,17 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
     float lse2[kMaxG];
     merge_group_stats<kMaxG>(part, chunks_alloc, group, n_chunks, lse2);
 
-    // new score from the old one, this step's attention weight and (windowed) the weight that leaves.  The
-    // leaving weight is subtracted first: when it is most of the old sum the difference is exact and the small
-    // new weight is not rounded away against the large old one (with a window of one step the score is then
-    // exactly the new weight).  Rounding may still leave a windowed sum a hair below zero: it is a sum of
-    // non-negative terms, and its bits are compared as unsigned integers.
-    auto combine = [&](float s_old, float p, float gone) {
-        return windowed ? fmaxf((s_old - gone) + p, 0.f) : s_old + p;
+    // new score from the old one, this step's attention weight and (windowed) the weight that leaves the
+    // window: accumulated scores are one fp32 addition; windowed scores are carried in two floats (window_update),
+    // so that adding a weight and subtracting the same float w+1 steps later leaves no residue behind
+    auto combine = [&](float s_old, float lo_old, float p, float gone, float &lo_new) {
+        if (!windowed) { lo_new = 0.f; return s_old + p; }
+        float hi = s_old, lo = lo_old;
+        window_update(hi, lo, gone, p);
+        lo_new = lo;
+        return hi;
     };
+    float unused_lo;
 
     // the row that leaves: minimise (importance bits, ~row) over the unprotected rows
     int evicted = n;                                       // n <= B: nothing leaves
@@ -110,11 +115,11 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
 #pragma unroll
         for (int u = 0; u < kScan; ++u) {
             const int r = lo + tid + u * kThreads;
-            if (r < hi) consider(r, combine(s_r[u], group_weight<kMaxG>(t_r[u], lse2, group), x_r[u]), w_r[u]);
+            if (r < hi) consider(r, combine(s_r[u], l_r[u], group_weight<kMaxG>(t_r[u], lse2, group), x_r[u], unused_lo), w_r[u]);
         }
         // further rows, four per thread at a time: loads first, then the arithmetic
         for (int r0 = lo + tid + kScan * kThreads; r0 < hi; r0 += kScan * kThreads) {
-            float t4[kScan][kMaxG], s4[kScan], w4[kScan], x4[kScan];
+            float t4[kScan][kMaxG], s4[kScan], w4[kScan], x4[kScan], l4[kScan];
 #pragma unroll
             for (int u = 0; u < kScan; ++u) {
                 const int r = r0 + u * kThreads;
@@ -123,11 +128,12 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
                 s4[u] = ok && r != n0 ? Su[r] : 0.f;
                 w4[u] = ok ? Nu[r] : 0.f;
                 x4[u] = ok ? leaving(r) : 0.f;
+                l4[u] = ok ? low_part(r) : 0.f;
             }
 #pragma unroll
             for (int u = 0; u < kScan; ++u) {
                 const int r = r0 + u * kThreads;
-                if (r < hi) consider(r, combine(s4[u], group_weight<kMaxG>(t4[u], lse2, group), x4[u]), w4[u]);
+                if (r < hi) consider(r, combine(s4[u], l4[u], group_weight<kMaxG>(t4[u], lse2, group), x4[u], unused_lo), w4[u]);
             }
         }
         best = wave_min_u64(best);
@@ -144,7 +150,7 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
         const int share = (n_keep + G - 1) / G;
         const int o_end = min(n_keep, (g + 1) * share);
         for (int o0 = g * share + tid; o0 < o_end; o0 += kScan * kThreads) {
-            float t4[kScan][kMaxG], s4[kScan], x4[kScan];
+            float t4[kScan][kMaxG], s4[kScan], x4[kScan], l4[kScan];
             int c4[kScan];
 #pragma unroll
             for (int u = 0; u < kScan; ++u) {           // loads first, then the arithmetic and the stores
@@ -154,6 +160,7 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
                 load_group_logits<kMaxG>(t4[u], Lu, cap, group, src, ok);
                 s4[u] = ok && src != n0 ? Su[src] : 0.f;
                 x4[u] = ok ? leaving(src) : 0.f;
+                l4[u] = ok ? low_part(src) : 0.f;
                 c4[u] = ok && windowed ? column(src) : 0;
             }
 #pragma unroll
@@ -161,7 +168,9 @@ __global__ __launch_bounds__(kThreads) void decode_prune_kernel(
                 const int o = o0 + u * kThreads;
                 if (o >= o_end) continue;
                 const float p = group_weight<kMaxG>(t4[u], lse2, group);
-                S_out[unit * cap_out + o] = combine(s4[u], p, x4[u]);
+                float lo_new;
+                S_out[unit * cap_out + o] = combine(s4[u], l4[u], p, x4[u], lo_new);
+                if (windowed) win.s_lo_out[unit * cap_out + o] = lo_new;
                 if (kept_idx) kept_idx[unit * cap_out + o] = o + (o >= evicted ? 1 : 0);
                 if (windowed) h_write[c4[u]] = p;
             }

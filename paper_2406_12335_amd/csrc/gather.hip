@@ -147,6 +147,31 @@ __global__ __launch_bounds__(256) void hist_gather_kernel(const float *__restric
         if (s0 + u < rows) hist_out[(unit * rows + s0 + u) * static_cast<size_t>(cap_hist) + o] = val[u];
 }
 
+// Low-order parts of the survivors' windowed scores after the prompt prune: the survivor's column of the ring is
+// summed in two floats (ring rows in order) and s_lo_out receives that sum minus the score the selection copied,
+// so that S_out + s_lo_out carries the window's weights exactly (to two floats) into the decode steps.
+__global__ __launch_bounds__(256) void window_low_part_kernel(const float *__restrict__ hist_out,
+                                                              const float *__restrict__ S_out, float *__restrict__ s_lo_out,
+                                                              BatchMeta meta, int n_heads, int cap_out, int cap_hist, int rows)
+{
+    const size_t unit = blockIdx.y;
+    const int b = static_cast<int>(unit / n_heads);
+    const int n = meta.len[b], B = meta.aux[b];
+    const int n_keep = n < B ? n : B;
+    const int o = blockIdx.x * 256 + threadIdx.x;
+    if (o >= n_keep) return;
+    float hi = 0.f, lo = 0.f;
+    for (int s0 = 0; s0 < rows; s0 += 8) {
+        float val[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            val[u] = s0 + u < rows ? hist_out[(unit * rows + s0 + u) * static_cast<size_t>(cap_hist) + o] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) two_float_add(hi, lo, val[u]);
+    }
+    s_lo_out[unit * cap_out + o] = __fadd_rn(__fsub_rn(hi, S_out[unit * cap_out + o]), lo);
+}
+
 }  // namespace
 
 hipError_t launch_gather(int dtype, int head_dim, bool evict_one,
@@ -183,8 +208,8 @@ hipError_t launch_gather(int dtype, int head_dim, bool evict_one,
 namespace vatp {
 
 hipError_t launch_hist_gather(const float *hist_in, const int32_t *kept_idx, float *hist_out, int32_t *hid_out,
-                              int32_t *free_out, int rows, int cap_hist, const BatchMeta &meta, const Geometry &g,
-                              hipStream_t st)
+                              int32_t *free_out, const float *S_out, float *s_lo_out, int rows, int cap_hist,
+                              const BatchMeta &meta, const Geometry &g, hipStream_t st)
 {
     const unsigned units = static_cast<unsigned>(g.batch) * g.n_heads;
     const int max_keep = g.max_len > 0 ? g.max_len : 1;       // max_len: largest surviving row count
@@ -192,6 +217,8 @@ hipError_t launch_hist_gather(const float *hist_in, const int32_t *kept_idx, flo
                        dim3((max_keep + 255) / 256, units, (rows + kHistRowsPerBlock - 1) / kHistRowsPerBlock), dim3(256), 0,
                        st, hist_in, kept_idx,
                        hist_out, hid_out, free_out, meta, g.n_heads, g.cap, g.cap_out, cap_hist, rows);
+    hipLaunchKernelGGL(window_low_part_kernel, dim3((max_keep + 255) / 256, units), dim3(256), 0, st, hist_out, S_out,
+                       s_lo_out, meta, g.n_heads, g.cap_out, cap_hist, rows);
     return hipGetLastError();
 }
 

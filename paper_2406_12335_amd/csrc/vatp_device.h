@@ -56,6 +56,8 @@ __device__ __forceinline__ float norm_finish(int kind, float a) {
 // the new row takes the column the last evicted row gave up (free_in), or the next fresh one.
 // hist == nullptr switches all of this off (accumulated scores, Eq. 2).
 struct WindowArgs {
+    const float *s_lo;               // [units, cap]      low-order part of every row's score (see window_update)
+    float *s_lo_out;                 // [units, cap_out]  ... of the other set
     float *hist;                     // [units, rows, cap_hist]
     int32_t *hid;                    // [units, cap]      column of every row of the current set
     int32_t *hid_out;                // [units, cap_out]  ... of the other set
@@ -64,6 +66,30 @@ struct WindowArgs {
     int32_t rows, cap_hist;
     int32_t step[VATP_MAX_BATCH];    // index t of the new token in its sequence
 };
+
+// A windowed score is kept as an unevaluated sum hi + lo of two floats (hi is what S holds): weights enter the
+// window and, w+1 steps later, the very same float leaves it, so a sum that is carried exactly stays a sum of
+// the weights currently in the window -- its error does not grow with the number of steps, and stays relative
+// to the score itself however large the score once was.  Every addition is an error-free transformation (the
+// rounding error of hi + x is recovered exactly and folded into lo); what is lost per step is at most 2^-47 of
+// the running sum.
+__device__ __forceinline__ void two_float_add(float &hi, float &lo, float x)
+{
+    const float s = __fadd_rn(hi, x);
+    const float bb = __fsub_rn(s, hi);
+    const float err = __fadd_rn(__fsub_rn(hi, __fsub_rn(s, bb)), __fsub_rn(x, bb));     // hi + x = s + err exactly
+    const float l = __fadd_rn(lo, err);
+    const float t = __fadd_rn(s, l);                                                   // renormalise: |s| >= |l|
+    lo = __fsub_rn(l, __fsub_rn(t, s));
+    hi = t;
+}
+// new score of a windowed row: the weight that leaves the window goes first, then the new one arrives
+__device__ __forceinline__ void window_update(float &hi, float &lo, float gone, float p)
+{
+    two_float_add(hi, lo, -gone);
+    two_float_add(hi, lo, p);
+    if (hi < 0.f) { hi = 0.f; lo = 0.f; }      // a sum of non-negative terms; its bits are compared as unsigned integers
+}
 
 constexpr int kDecodeChunk = 128;  // rows of one unit handled by one workgroup of the decode GEMV
 
@@ -432,8 +458,10 @@ hipError_t launch_gather(int dtype, int head_dim, bool evict_one,
                          const BatchMeta &meta, const Geometry &g, hipStream_t st);
 
 // prompt prune of the history-window variant: columns of the window's attention rows follow kept_idx
+// (S_out: the survivors' scores as the selection copied them; s_lo_out receives their low-order parts, such that
+// S_out + s_lo_out is the sum of the survivor's window weights carried in two floats)
 hipError_t launch_hist_gather(const float *hist_in, const int32_t *kept_idx, float *hist_out, int32_t *hid_out,
-                              int32_t *free_out, int rows, int cap_hist, const BatchMeta &meta, const Geometry &g,
-                              hipStream_t st);
+                              int32_t *free_out, const float *S_out, float *s_lo_out, int rows, int cap_hist,
+                              const BatchMeta &meta, const Geometry &g, hipStream_t st);
 
 }  // namespace vatp

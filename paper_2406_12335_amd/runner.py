@@ -59,6 +59,8 @@ class PrunedKVCache:
             self.hist = torch.zeros(batch, n_heads, window + 2, self.cap_hist, dtype=torch.float32, device=self.device)
             self.hid = [torch.zeros(*shape, dtype=torch.int32, device=self.device) for _ in range(2)]
             self.free = [torch.zeros(batch * n_heads, dtype=torch.int32, device=self.device) for _ in range(2)]
+            # low-order parts of the windowed scores (a score is carried in two floats), one array per cache set
+            self.S_lo = [torch.zeros(*shape, dtype=torch.float32, device=self.device) for _ in range(2)]
             self.hist_prompt = None
         # The decode calls are made once per generated token: their device pointers are converted to
         # ctypes values once, here, instead of on every call.
@@ -120,7 +122,7 @@ class PrunedKVCache:
             B.vatp_select_compact_window(self.ctx, p, K, V, self.S_prompt, self.nrm_prompt, pos_in, self.hist_prompt,
                                          self.window, self.K[0], self.V[0], self.S[0], self.nrm[0], self.pos[0],
                                          self.kept_idx, self.hist, self.cap_hist, self.hid[0], self.free[self.synced_cur],
-                                         None, stream)
+                                         self.S_lo[0], None, stream)
         self.lens = [min(n, bud) for n, bud in zip(self._prompt_lens, self.budgets)]
         self._synced_valid = False
 
@@ -175,7 +177,7 @@ class PrunedKVCache:
                 self.ctx, self._p_dec, q, k, v, self.K[c], self.V[c], self.S[c], self.nrm[c], self.pos[c], self.hid[c],
                 new_pos, self.K[o], self.V[o], self.S[o], self.nrm[o], self.pos[o], self.hid[o],
                 self.kept_idx if want_kept_idx else None, self.synced[si], self.synced[so], self.free[si], self.free[so],
-                self.hist, self.window, self.cap_hist, out, self.ws, stream)
+                self.hist, self.S_lo[c], self.S_lo[o], self.window, self.cap_hist, out, self.ws, stream)
             self.cur, self.synced_cur = o, so
             self.lens = [min(n + 1, bud) for n, bud in zip(self.lens, self.budgets)]
             return

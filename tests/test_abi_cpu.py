@@ -87,9 +87,9 @@ def test_entry_points_reject_null_before_any_launch():
     assert lib.vatp_decode_prune_step(None, p.ref(), *([None] * 18), None, 0, None) == binding.E_NULL
     assert lib.vatp_prefill_score_window(None, p.ref(), None, None, None, 4, None, None, None, None, 0, None) == binding.E_NULL
     assert lib.vatp_prefill_score_window(None, p.ref(), None, None, None, -1, None, None, None, None, 0, None) == binding.E_SHAPE
-    assert lib.vatp_select_compact_window(None, p.ref(), *([None] * 6), 4, *([None] * 7), 64, None, None, None, 0,
+    assert lib.vatp_select_compact_window(None, p.ref(), *([None] * 6), 4, *([None] * 7), 64, None, None, None, None, 0,
                                           None) == binding.E_NULL
-    assert lib.vatp_decode_prune_step_window(None, p.ref(), *([None] * 9), None, *([None] * 12), 4, 64, None, None, 0,
+    assert lib.vatp_decode_prune_step_window(None, p.ref(), *([None] * 9), None, *([None] * 14), 4, 64, None, None, 0,
                                              None) == binding.E_NULL
     assert "NULL" in vatp.strerror(binding.E_NULL)
     assert vatp.strerror(-99) == "unknown status"

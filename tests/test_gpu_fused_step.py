@@ -162,6 +162,30 @@ def test_history_window_trajectory_against_oracle(gpu_device, name, kw, w):
     assert rep.prune_events > 0
 
 
+@pytest.mark.parametrize("dtype,w", [("fp32", 3), ("bf16", 5)])
+def test_windowed_score_stays_relative_after_large_weights_leave(gpu_device, dtype, w):
+    """One key draws almost all of the attention for a few steps and almost none afterwards: its windowed
+    score falls by five orders of magnitude once the large weights have left the window.  A plain fp32
+    running sum keeps a residue of about 2^-24 of the LARGE score (a relative error of a per cent here);
+    the score carried in two floats must still match the oracle to the ordinary relative tolerance."""
+    d, L, T, row = 64, 40, 14, 10
+    cfg = vs.scaled(vs.CONFIGS["tiny"], n_heads=2, head_dim=d, prompt_len=L, dtype=dtype, decode_steps=T, recent=4,
+                    n_sinks=0)
+    inp = vs.make_inputs(cfg, seed=77)
+    inp.budgets = [L + T + 1]                      # nothing is evicted: the row lives through the whole run
+    k = inp.K[0, :, row].float()
+    unit = k / k.norm(dim=-1, keepdim=True)
+    for t in range(T):
+        # scaled logit of the chosen key: +9 for four steps (weight close to 1), -12 afterwards
+        want = 9.0 if t < 4 else -12.0
+        q = unit * (want * d ** 0.5 / k.norm(dim=-1, keepdim=True)) + 0.05 * inp.qd[t, 0].float()
+        inp.qd[t, 0] = q.to(inp.qd.dtype)
+    _say("windowed score after large weights leave, %s, w=%d" % (dtype, w))
+    rep = parity.run_trajectory(inp, gpu_device, fused=True, window=w, n_sink=0, cap_cache=L + T + 2)
+    _say("report %r" % rep)
+    assert rep.admitted_near_ties == 0
+
+
 @pytest.mark.parametrize("dtype,d,lens,w", [
     ("bf16", 128, [2500, 130], 400),        # two key ranges, window inside the second block
     ("bf16", 128, [4096, 4095], 400),
@@ -289,8 +313,8 @@ def test_window_calls_reject_bad_arguments_and_accept_no_history_buffer(gpu_devi
         with pytest.raises(vatp.VatpError) as e:                                    # the step index is required
             vatp.vatp_decode_prune_step_window(c.ctx, c._p_dec, x, x, x, c.K[0], c.V[0], c.S[0], c.nrm[0], c.pos[0], c.hid[0],
                                                None, c.K[1], c.V[1], c.S[1], c.nrm[1], c.pos[1], c.hid[1], None,
-                                               c.synced[0], c.synced[1], c.free[0], c.free[1], good_hist, w, c.cap_hist,
-                                               None, c.ws)
+                                               c.synced[0], c.synced[1], c.free[0], c.free[1], good_hist, c.S_lo[0], c.S_lo[1],
+                                               w, c.cap_hist, None, c.ws)
         assert e.value.status == vatp.binding.E_NULL
         c.decode_prune_step(x, x, x, [L])                                           # and the good call still works
         torch.cuda.synchronize()
