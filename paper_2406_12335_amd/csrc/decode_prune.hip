@@ -489,10 +489,10 @@ hipError_t launch_decode_prune(int dtype, int head_dim, const void *K, const voi
 {
     const int chunks_alloc = (g.cap + kDecodeChunk - 1) / kDecodeChunk;
     const unsigned units = static_cast<unsigned>(g.batch) * g.n_heads;
-    // enough workgroups per head to occupy the chip once (4 of these fit a compute unit)
-    // (each of them reads all of the head's logits, group times as many with grouped queries: measured best
-    // at 64 heads x 4 query heads: 2 to 8 workgroups per head, 28 us per step against 35 with 16)
-    unsigned G = 1024u / (units * static_cast<unsigned>(g.group));
+    // Workgroups per head: each of them repeats the scan over all of the head's rows (group times as many logits
+    // with grouped queries), so more of them only pay while the chip is not yet full.  Measured per step: 512 heads
+    // (ragged16) 49.8 us with one, 51.2 with two, 56 with four; 64 heads x 4 query heads 28 us with 2 to 8, 35 with 16.
+    unsigned G = 512u / (units * static_cast<unsigned>(g.group));
     G = G < 1u ? 1u : (G > 16u ? 16u : G);
     dim3 grid(units, G), block(kThreads);
 #define VATP_DPG(T, D, G)                                                                                      \
