@@ -76,6 +76,13 @@ def _seed_state(caches, lens, g, d, tdt, dev, weak_rows=None):
     ("bf16", 128, 43, [300, 290, 64], [300, 300, 70], 16, 2, 8),
     ("fp32", 64, 64, [1000, 129], [1000, 140], 8, 0, 7),
     ("bf16", 64, 32, [5, 130, 129, 257], [9, 130, 200, 257], 3, 1, 9),
+    # the single-launch route at the edges of what it stores ahead of the eviction decision
+    ("bf16", 128, 64, [400, 390], [400, 400], 0, 0, 9),        # no window, no prefix: the appended row is a candidate
+    ("bf16", 128, 64, [400, 390], [400, 400], 127, 2, 9),      # window + 1 rows = all the rows stored ahead
+    ("bf16", 128, 64, [400, 250], [400, 400], 128, 2, 9),      # window one row longer than that
+    ("bf16", 64, 64, [700, 690], [700, 700], 200, 1, 9),       # much longer: part of the window is copied afterwards
+    ("fp32", 128, 64, [300, 100], [300, 300], 40, 0, 9),       # 32 lanes per row
+    ("bf16", 128, 65, [1023, 1000], [1023, 1023], 64, 2, 6),   # 1024 rows after the append: the route's limit
 ])
 def test_fused_step_is_bit_identical_to_the_two_call_route(gpu_device, dtype, d, H, lens, budgets, R, F, steps):
     """Same K, V, S, nrm, pos, kept_idx and attention output as vatp_decode_attend_step followed by
