@@ -148,3 +148,25 @@ def test_header_is_plain_c(tmp_path):
     src.write_text("\n".join(lines) + "\n")
     subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(root, "include"),
                            "-c", str(src), "-o", str(tmp_path / "use_vatp.o")])
+
+
+def test_built_library_matches_its_sources():
+    """build_library() leaves a digest of sources, headers and flags beside the library; load() rebuilds when it no
+    longer matches.  Here: the digest is reproducible, the library that is loaded is current, and a change to any
+    source byte changes the digest."""
+    import shutil
+    from paper_2406_12335_amd import build
+    vatp.load()
+    assert build.is_current()
+    d0 = build.source_digest()
+    assert d0 == build.source_digest() and len(d0) == 64
+    victim = os.path.join(build.CSRC, "l1norm.hip")
+    backup = victim + ".bak_test"
+    shutil.copy2(victim, backup)
+    try:
+        with open(victim, "a") as f:
+            f.write("// touched by test_built_library_matches_its_sources\n")
+        assert build.source_digest() != d0 and not build.is_current()
+    finally:
+        shutil.move(backup, victim)
+    assert build.source_digest() == d0 and build.is_current()

@@ -201,6 +201,8 @@ def test_prompt_scores_with_a_late_dominant_key(gpu_device, jump):
     (4096, 2048, 2, 64, 0), (2049, 2048, 2, 64, 1), (1000, 999, 0, 0, 2), (1500, 300, 20, 100, 3),
     (70, 70, 2, 4, 4), (50, 80, 2, 4, 5), (300, 66, 2, 64, 6), (5000, 1, 0, 0, 7), (1025, 1024, 0, 1024, 8),
     (33000, 3276, 4, 128, 9),
+    (20000, 6000, 2, 64, 10),          # 32 keys per thread in registers
+    (70000, 7000, 4, 128, 11),         # beyond 64 keys per thread: the kernel that re-reads S and nrm per pass
 ])
 def test_select_compact_bit_exact_with_planted_ties(gpu_device, n, B, F, R, seed):
     """Same binary32 S and nrm on both sides, decision in binary32 on both sides: identical sets."""
