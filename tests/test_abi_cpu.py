@@ -1,6 +1,5 @@
 """Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
 the header declares, and rejects bad arguments before touching a device."""
-import ctypes
 import os
 import re
 

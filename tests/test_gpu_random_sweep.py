@@ -5,7 +5,6 @@ import random
 import sys
 
 import pytest
-import torch
 
 import parity
 import vatp_synth as vs

@@ -6,7 +6,6 @@ import sys
 import pytest
 import torch
 
-import vatp_synth as vs
 import paper_2406_12335_amd as vatp
 from paper_2406_12335_amd import binding as B
 
