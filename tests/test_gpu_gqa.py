@@ -236,6 +236,7 @@ def test_grouped_queries_with_history_window(gpu_device, dtype, d, H, g, L, w):
     _say("gqa window %s d=%d H=%d g=%d L=%d w=%d" % (dtype, d, H, g, L, w))
     rep = parity.run_trajectory(inp, gpu_device, units=[(0, 0), (0, H - 1)], fused=True, window=w)
     _say("report %r" % rep)
+    assert rep.admitted_near_ties <= 1
     # the stored attention rows themselves: the group mean of each query head's softmax row
     cache = PrunedKVCache(1, H, d, cfg.torch_dtype(), 2, cfg.recent, inp.budgets, gpu_device, window=w, q_per_kv=g)
     try:
@@ -283,3 +284,4 @@ def test_grouped_history_window_at_long_prompt(gpu_device):
     _say("gqa window at L=32768")
     rep = parity.run_trajectory(inp, gpu_device, units=[(0, 0), (0, 7)], fused=True, window=400, check_every=2)
     _say("report %r" % rep)
+    assert rep.admitted_near_ties <= 1
