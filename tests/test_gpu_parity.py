@@ -203,6 +203,7 @@ def test_prompt_scores_with_a_late_dominant_key(gpu_device, jump):
     (33000, 3276, 4, 128, 9),
     (20000, 6000, 2, 64, 10),          # 32 keys per thread in registers
     (70000, 7000, 4, 128, 11),         # beyond 64 keys per thread: the kernel that re-reads S and nrm per pass
+    (1000000, 200, 2, 64, 12),         # a million rows, few survivors (the oracle picks them one at a time)
 ])
 def test_select_compact_bit_exact_with_planted_ties(gpu_device, n, B, F, R, seed):
     """Same binary32 S and nrm on both sides, decision in binary32 on both sides: identical sets."""
