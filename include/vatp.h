@@ -197,8 +197,8 @@ vatp_status vatp_select_compact(vatp_ctx *ctx, const vatp_params *p,
  * when out is not NULL) followed by vatp_select_compact, for caches that hold at most
  * budget[b] rows before the step, so that at most one row per head leaves (Fig. 2: the new
  * token is added, the least important unprotected one removed; Eq. 2 incrementally, Eq. 4).
- * The results are bit-identical to the two separate calls; two launches instead of three, and
- * the rows that both cache sets already share are not copied again.
+ * The results are bit-identical to the two separate calls; one launch (many heads of at most 1024
+ * rows) or two instead of three, and the rows that both cache sets already share are not copied again.
  *
  * The caller keeps two cache sets and alternates them: (K, V, S, nrm, pos) is the current set
  * with len[b] rows, (K_out, V_out, S_out, nrm_out, pos_out) the other one.  The call appends the
